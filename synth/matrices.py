@@ -1,0 +1,304 @@
+"""Counter-based generators for the synthetic link matrices and embedding tables.
+
+Every random number is a pure function ``hash(seed, stream, a, b)`` of integer
+counters (a splitmix64-style mixer written with wrapping int64 torch ops), so a
+matrix is reproducible on any torch device and needs no generator state.
+
+The matrices stand in for the WebGraph link matrices of the paper's Section 5
+(square, heavy-tailed out-degrees, host locality), at the shapes the benchmark
+configurations name; they hold no item of that dataset.
+
+Recipes (degrees -> column ids), one per configuration key:
+
+``c1``  2000 x 1500; degrees: Zipf(1.1) truncated to 1..200; columns: Zipf(1.1)
+        over ranks, rank -> id through a seeded permutation.
+``c2``  1M x 1M; degrees: round(Pareto, pdf ~ k^-2.1 on [k_min, 5000]) with k_min
+        chosen so the mean is 30; columns uniform.
+``c3``  10M x 10M; degrees: shifted geometric, mean 20, clipped to [1, 2000];
+        nodes grouped into 100k contiguous "hosts" with lognormal sizes; an edge
+        lands inside the source's host with probability 0.8, else on a
+        Zipf(1.0)-popular node.
+``c4``  50M x 50M; degrees geometric, mean 6, max 1000; columns uniform.
+``c5``  100M x 100M; degrees round(Pareto, pdf ~ k^-2.5 on [k_min, 1e5]), mean 25;
+        columns uniform.
+
+Zipf(s) over ranks 1..N is drawn as floor of the continuous density x^-s on
+[1, N+1), which has the same tail and needs no table.  Duplicate (row, col)
+pairs are dropped after generation, so realised degrees can be slightly below
+the drawn ones; callers print the realised statistics.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_MASK63 = (1 << 63) - 1
+
+
+def _to_i64(x: int) -> int:
+    """Reinterpret an unsigned 64-bit constant as the signed value torch wants."""
+    x &= (1 << 64) - 1
+    return x - (1 << 64) if x >= (1 << 63) else x
+
+
+_C1 = _to_i64(0x9E3779B97F4A7C15)
+_C2 = _to_i64(0xBF58476D1CE4E5B9)
+_C3 = _to_i64(0x94D049BB133111EB)
+_C4 = _to_i64(0xD6E8FEB86659FD93)
+
+
+def _lsr(x: torch.Tensor, s: int) -> torch.Tensor:
+    """Logical right shift of int64 (torch's >> is arithmetic)."""
+    return (x >> s) & ((1 << (64 - s)) - 1)
+
+
+def _mix(z: torch.Tensor) -> torch.Tensor:
+    z = (z ^ _lsr(z, 30)) * _C2
+    z = (z ^ _lsr(z, 27)) * _C3
+    return z ^ _lsr(z, 31)
+
+
+def hash_u64(seed: int, stream: int, a: torch.Tensor, b: torch.Tensor | int = 0) -> torch.Tensor:
+    """64 hashed bits (as int64) for every element of counters ``a`` (and ``b``)."""
+    a = a.to(torch.int64)
+    k = _to_i64((seed * 0x9E3779B97F4A7C15) ^ (stream * 0xD6E8FEB86659FD93))
+    z = _mix(a * _C1 + k)
+    if isinstance(b, torch.Tensor):
+        b = b.to(torch.int64)
+        z = _mix(z ^ (b * _C4 + _C1))
+    else:
+        z = _mix(z ^ _to_i64(b * 0xD6E8FEB86659FD93 + 0x9E3779B97F4A7C15))
+    return z
+
+
+def uniform01(h: torch.Tensor) -> torch.Tensor:
+    """Hashed bits -> float64 uniform in (0, 1) (never exactly 0 or 1)."""
+    return (_lsr(h, 11).to(torch.float64) + 0.5) * (1.0 / 9007199254740992.0)
+
+
+def _normal(seed: int, stream: int, a: torch.Tensor, b) -> torch.Tensor:
+    u1 = uniform01(hash_u64(seed, stream, a, b))
+    u2 = uniform01(hash_u64(seed, stream + 1, a, b))
+    return torch.sqrt(-2.0 * torch.log(u1)) * torch.cos(2.0 * math.pi * u2)
+
+
+def init_table(rows: int, d: int, seed: int, stream: int, device="cpu",
+               dtype=torch.float32, chunk: int = 1 << 22) -> torch.Tensor:
+    """Embedding table with entries N(0, sigma), sigma = 0.1 / sqrt(d)."""
+    out = torch.empty((rows, d), dtype=dtype, device=device)
+    sigma = 0.1 / math.sqrt(d)
+    col = torch.arange(d, device=device, dtype=torch.int64)[None, :]
+    for r0 in range(0, rows, chunk):
+        r1 = min(rows, r0 + chunk)
+        r = torch.arange(r0, r1, device=device, dtype=torch.int64)[:, None]
+        out[r0:r1] = (sigma * _normal(seed, stream, r * d + col, 0)).to(dtype)
+    return out
+
+
+# --------------------------------------------------------------------------- degrees
+
+def _pareto_inv(u: torch.Tensor, a: float, lo: float, hi: float) -> torch.Tensor:
+    """Inverse CDF of the density x^-a on [lo, hi] (a != 1)."""
+    e = 1.0 - a
+    lo_e, hi_e = lo ** e, hi ** e
+    return (lo_e - u * (lo_e - hi_e)) ** (1.0 / e)
+
+
+def _pareto_mean(a: float, lo: float, hi: float) -> float:
+    e1, e2 = 1.0 - a, 2.0 - a
+    return ((hi ** e2 - lo ** e2) / e2) / ((hi ** e1 - lo ** e1) / e1)
+
+
+def _pareto_kmin(a: float, hi: float, mean: float) -> float:
+    lo, up = 0.5, mean
+    for _ in range(200):
+        mid = 0.5 * (lo + up)
+        if _pareto_mean(a, mid, hi) < mean:
+            lo = mid
+        else:
+            up = mid
+    return 0.5 * (lo + up)
+
+
+def _zipf_rank(u: torch.Tensor, s: float, n: int) -> torch.Tensor:
+    """Rank in 1..n with P(r) ~ r^-s (floor of the continuous law on [1, n+1))."""
+    if abs(s - 1.0) < 1e-12:
+        x = torch.exp(u * math.log(n + 1.0))
+    else:
+        x = _pareto_inv(u, s, 1.0, n + 1.0)
+    return torch.clamp(x.floor().to(torch.int64), 1, n)
+
+
+def _geometric(u: torch.Tensor, mean: float, kmax: int) -> torch.Tensor:
+    """Geometric on {1, 2, ...} with the given mean, clipped to kmax."""
+    p = 1.0 / mean
+    k = 1 + torch.floor(torch.log(u) / math.log(1.0 - p)).to(torch.int64)
+    return torch.clamp(k, 1, kmax)
+
+
+# --------------------------------------------------------------------------- CSR helpers
+
+def csr_from_edges(rows: int, cols: int, r: torch.Tensor, c: torch.Tensor,
+                   v: Optional[torch.Tensor] = None):
+    """Sort edges by (row, col), drop duplicate pairs, return (indptr, indices, values)."""
+    key = r.to(torch.int64) * cols + c.to(torch.int64)
+    if v is None:
+        key = torch.unique(key)  # sorted, duplicates removed
+        vals = None
+    else:
+        key, order = torch.sort(key, stable=True)
+        keep = torch.ones_like(key, dtype=torch.bool)
+        keep[1:] = key[1:] != key[:-1]
+        key = key[keep]
+        vals = v[order][keep].contiguous()
+    rr = torch.div(key, cols, rounding_mode="floor")
+    cc = (key - rr * cols).to(torch.int32)
+    counts = torch.bincount(rr, minlength=rows)
+    indptr = torch.zeros(rows + 1, dtype=torch.int64, device=key.device)
+    torch.cumsum(counts, 0, out=indptr[1:])
+    return indptr, cc.contiguous(), vals
+
+
+def _expand_rows(indptr: torch.Tensor) -> torch.Tensor:
+    rows = indptr.numel() - 1
+    deg = indptr[1:] - indptr[:-1]
+    return torch.repeat_interleave(torch.arange(rows, device=indptr.device, dtype=torch.int64), deg)
+
+
+def transpose_csr(rows: int, cols: int, indptr, indices, values=None):
+    """CSR of the transposed matrix (true transpose, columns sorted inside each row)."""
+    r = _expand_rows(indptr)
+    return csr_from_edges(cols, rows, indices.to(torch.int64), r, values)
+
+
+# --------------------------------------------------------------------------- problems
+
+@dataclass
+class SparseProblem:
+    name: str
+    rows: int
+    cols: int
+    d: int
+    alpha: float
+    lam: float
+    epochs: int
+    table_dtype: torch.dtype
+    indptr: torch.Tensor
+    indices: torch.Tensor
+    values: Optional[torch.Tensor]
+    t_indptr: torch.Tensor
+    t_indices: torch.Tensor
+    t_values: Optional[torch.Tensor]
+    W0: torch.Tensor
+    H0: torch.Tensor
+
+    @property
+    def nnz(self) -> int:
+        return int(self.indices.numel())
+
+    def stats(self) -> dict:
+        deg = self.indptr[1:] - self.indptr[:-1]
+        tdeg = self.t_indptr[1:] - self.t_indptr[:-1]
+        return {
+            "rows": self.rows, "cols": self.cols, "nnz": self.nnz, "d": self.d,
+            "row_deg_mean": float(deg.double().mean()), "row_deg_max": int(deg.max()),
+            "col_deg_mean": float(tdeg.double().mean()), "col_deg_max": int(tdeg.max()),
+            "empty_rows": int((deg == 0).sum()), "empty_cols": int((tdeg == 0).sum()),
+        }
+
+
+CONFIGS = {
+    "c1": dict(rows=2000, cols=1500, d=16, alpha=0.1, lam=1e-2, epochs=4, seed=20211201, dtype="f32"),
+    "c2": dict(rows=1_000_000, cols=1_000_000, d=64, alpha=0.1, lam=1e-2, epochs=1, seed=20211202, dtype="f32"),
+    "c3": dict(rows=10_000_000, cols=10_000_000, d=128, alpha=0.1, lam=1e-2, epochs=1, seed=20211203, dtype="f32"),
+    "c4": dict(rows=50_000_000, cols=50_000_000, d=128, alpha=0.05, lam=1e-2, epochs=1, seed=20211204, dtype="f32"),
+    "c5": dict(rows=100_000_000, cols=100_000_000, d=128, alpha=0.1, lam=1e-2, epochs=1, seed=20211205, dtype="bf16"),
+}
+
+
+def _degrees(kind: str, rows: int, seed: int, device) -> torch.Tensor:
+    r = torch.arange(rows, device=device, dtype=torch.int64)
+    u = uniform01(hash_u64(seed, 1, r))
+    if kind == "c1":
+        return _zipf_rank(u, 1.1, 200)
+    if kind == "c2":
+        kmin = _pareto_kmin(2.1, 5000.0, 30.0)
+        return torch.clamp(torch.round(_pareto_inv(u, 2.1, kmin, 5000.0)).to(torch.int64), 1, 5000)
+    if kind == "c3":
+        return _geometric(u, 20.0, 2000)
+    if kind == "c4":
+        return _geometric(u, 6.0, 1000)
+    if kind == "c5":
+        kmin = _pareto_kmin(2.5, 1e5, 25.0)
+        return torch.clamp(torch.round(_pareto_inv(u, 2.5, kmin, 1e5)).to(torch.int64), 1, 100_000)
+    raise ValueError(kind)
+
+
+def _permutation(n: int, seed: int, stream: int, device) -> torch.Tensor:
+    h = hash_u64(seed, stream, torch.arange(n, device=device, dtype=torch.int64))
+    return torch.argsort(h, stable=True)
+
+
+def _columns(kind: str, rows: int, cols: int, seed: int, r: torch.Tensor, j: torch.Tensor) -> torch.Tensor:
+    device = r.device
+    u = uniform01(hash_u64(seed, 2, r, j))
+    if kind == "c1":
+        perm = _permutation(cols, seed, 7, device)
+        return perm[_zipf_rank(u, 1.1, cols) - 1]
+    if kind in ("c2", "c4", "c5"):
+        return torch.clamp((u * cols).to(torch.int64), 0, cols - 1)
+    if kind == "c3":
+        nhosts = max(1, cols // 100)
+        hid = torch.arange(nhosts, device=device, dtype=torch.int64)
+        w = torch.exp(_normal(seed, 3, hid, 0))  # lognormal(0, 1)
+        size = torch.clamp(torch.floor(w / w.sum() * cols).to(torch.int64), min=1)
+        # give the rounding remainder to the largest host so sizes sum to cols
+        size[torch.argmax(size)] += cols - int(size.sum())
+        assert int(size.min()) >= 1
+        start = torch.zeros(nhosts + 1, dtype=torch.int64, device=device)
+        torch.cumsum(size, 0, out=start[1:])
+        host = torch.searchsorted(start, r, right=True) - 1
+        hs, h0 = size[host], start[host]
+        u2 = uniform01(hash_u64(seed, 5, r, j))
+        local = h0 + torch.clamp((u2 * (hs - 1).double()).to(torch.int64), max=torch.clamp(hs - 2, min=0))
+        local = local + (local >= r).to(torch.int64)  # skip self
+        perm = _permutation(cols, seed, 7, device)
+        popular = perm[_zipf_rank(u2, 1.0, cols) - 1]
+        inside = (u < 0.8) & (hs > 1)
+        return torch.where(inside, local, popular)
+    raise ValueError(kind)
+
+
+def make_problem(kind: str, device="cpu", rows: Optional[int] = None, cols: Optional[int] = None,
+                 d: Optional[int] = None, values: str = "ones", seed: Optional[int] = None,
+                 dtype: Optional[str] = None) -> SparseProblem:
+    """Build one synthetic problem.  ``rows``/``cols``/``d`` override the
+    configuration's sizes (the recipe scales with them); ``values`` is "ones"
+    (binary implicit feedback, stored as no value array) or "uniform" (labels in
+    [0.5, 1.5), to exercise general y)."""
+    cfg = dict(CONFIGS[kind])
+    rows = rows or cfg["rows"]
+    cols = cols or cfg["cols"]
+    d = d or cfg["d"]
+    seed = cfg["seed"] if seed is None else seed
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16}[dtype or cfg["dtype"]]
+    deg = _degrees(kind, rows, seed, device)
+    deg = torch.clamp(deg, max=cols)
+    indptr0 = torch.zeros(rows + 1, dtype=torch.int64, device=device)
+    torch.cumsum(deg, 0, out=indptr0[1:])
+    r = _expand_rows(indptr0)
+    j = torch.arange(r.numel(), device=device, dtype=torch.int64) - indptr0[r]
+    c = _columns(kind, rows, cols, seed, r, j)
+    v = None
+    if values == "uniform":
+        v = (0.5 + uniform01(hash_u64(seed, 9, r, j))).to(torch.float32)
+    indptr, indices, vals = csr_from_edges(rows, cols, r, c, v)
+    del r, j, c
+    t_indptr, t_indices, t_vals = transpose_csr(rows, cols, indptr, indices, vals)
+    W0 = init_table(rows, d, seed, 11, device=device, dtype=tdt)
+    H0 = init_table(cols, d, seed, 13, device=device, dtype=tdt)
+    return SparseProblem(kind, rows, cols, d, cfg["alpha"], cfg["lam"], cfg["epochs"], tdt,
+                         indptr, indices, vals, t_indptr, t_indices, t_vals, W0, H0)

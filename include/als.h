@@ -1,0 +1,145 @@
+/*
+ * libals — implicit Alternating Least Squares (iALS) half-epoch solve on one AMD MI355X (gfx950).
+ *
+ * Plain C ABI.  Every pointer marked "device" is HIP device memory on the
+ * context's GPU; "host" pointers are ordinary host memory.  The caller owns
+ * every buffer it passes; the library owns only the workspace held by an
+ * als_ctx and never frees or reallocates caller memory.  No C++ exception
+ * crosses this boundary: every entry point returns an als_status.
+ *
+ * Notation follows the paper (ALX, Section 3): a sparse label matrix Y
+ * (m rows "users" x n columns "items"), embedding tables W [m x d] and
+ * H [n x d], prediction <w_u, h_i>, unobserved weight alpha, L2 weight lambda.
+ * The objective is Eq. 3; one half-epoch replaces every row of one table by
+ * the exact minimiser of Eq. 3 with the other table held fixed (Eq. 4,
+ * Algorithm 1 lines 2-10).
+ */
+#ifndef ALS_H
+#define ALS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ALS_OK = 0,
+    ALS_EINVAL = 1,  /* null pointer, negative size, bad parameter value            */
+    ALS_ESHAPE = 2,  /* shapes of the arguments do not fit each other               */
+    ALS_EDTYPE = 3,  /* unsupported element type or d, or tables of different types */
+    ALS_EALIAS = 4,  /* output table overlaps an input table                        */
+    ALS_ENOTSPD = 5, /* lambda <= 0, or a non-positive pivot met on the device      */
+    ALS_ENOMEM = 6,  /* workspace allocation failed                                 */
+    ALS_EHIP = 7     /* a HIP runtime call failed (see als_last_error)              */
+} als_status;
+
+typedef enum { ALS_F32 = 0, ALS_BF16 = 1 } als_dtype;
+
+/* Which formulation als_solve_rows uses for a row with k stored entries.
+ *   ALS_PATH_AUTO   : rows with 0 < k <= dual_max_k use the k x k dual system,
+ *                     all others the d x d normal equations.
+ *   ALS_PATH_PRIMAL : every row forms and solves the d x d normal equations of
+ *                     Eq. 4 (Algorithm 1 lines 4-10 literally).
+ *   ALS_PATH_DUAL   : as AUTO (kept distinct so callers can state intent).
+ * Both formulations reach the same minimiser of Eq. 3; see DESIGN notes in the
+ * source for the algebra. */
+typedef enum { ALS_PATH_AUTO = 0, ALS_PATH_PRIMAL = 1, ALS_PATH_DUAL = 2 } als_path;
+
+/* Sparse label matrix in CSR form (Section 3: the training set S as a matrix Y).
+ * Entries of a row may be in any order; every stored entry is one term of the
+ * sums in Eq. 4 (duplicates are not merged). */
+typedef struct {
+    int64_t rows, cols, nnz;
+    const int64_t *indptr; /* device [rows+1], non-decreasing, indptr[0]=0, indptr[rows]=nnz */
+    const int32_t *indices; /* device [nnz], 0 <= id < cols                                   */
+    const float *values;    /* device [nnz] labels y, or NULL meaning y = 1 for every entry    */
+} als_csr;
+
+/* Embedding table, row-major: element (r, c) at data[r*ld + c], 0 <= c < d.
+ * Supported d: 16, 32, 64, 128.  ld is in elements and must be >= d and keep
+ * rows 16-byte aligned (ld*sizeof(element) % 16 == 0; data 16-byte aligned). */
+typedef struct {
+    void *data; /* device */
+    int64_t rows;
+    int32_t d;
+    int64_t ld;
+    als_dtype dtype; /* ALS_F32, or ALS_BF16 (Section 4.4: bf16 storage, fp32 arithmetic) */
+} als_table;
+
+typedef struct {
+    float alpha;        /* weight of the all-pairs term of Eq. 3, >= 0                         */
+    float lambda;       /* L2 weight of Eq. 3, > 0 (keeps every system positive definite)      */
+    int32_t path;       /* als_path                                                             */
+    int32_t dual_max_k; /* 0 = library default; largest k solved in the dual form (<= 128)      */
+    int32_t split_nnz;  /* 0 = library default; rows longer than this are cut into segments whose
+                           partial statistics are summed (Section 4.3's row splitting)           */
+} als_params;
+
+typedef struct als_ctx als_ctx;
+
+/* Create / destroy a context bound to one GPU.  als_create sets that device
+ * current for the calling thread.  Workspace grows on demand and is released
+ * by als_destroy.  Calls on one context must not overlap. */
+als_status als_create(als_ctx **ctx, int device);
+als_status als_destroy(als_ctx *ctx);
+
+/* G = V^T V, the Gramian of a table (Section 3 after Eq. 4; Algorithm 1 line 2).
+ * G: device fp32 [d*d], row-major, both triangles written.  bf16 tables are
+ * widened exactly; products and sums are fp32 within a block of rows, fp64
+ * across blocks.  Asynchronous on `stream` (a hipStream_t, NULL = default). */
+als_status als_gramian(als_ctx *ctx, const als_table *V, float *G, void *stream);
+
+/* Row update of Eq. 4 (Algorithm 1 lines 3-10) for rows row_begin <= u < row_end of Y:
+ *     X[u] = ( sum_{i in Y[u]} v_i (x) v_i + alpha*G + lambda*I )^{-1} sum_{i in Y[u]} y_ui v_i
+ * with v_i the rows of the fixed table V (V->rows == Y->cols) and G = V^T V as
+ * produced by als_gramian.  A row with no stored entry gets X[u] = 0.  X must
+ * have Y->rows rows, the same d and dtype as V, and must not overlap V.  All
+ * arithmetic is fp32 (fp64 for the one shared d x d factorisation); the result
+ * is rounded once (to nearest even) to X's dtype.  Rows outside the range are
+ * left untouched.  Enqueues on `stream`; synchronises that stream once, after
+ * classifying the rows, to size the long-row workspace.  A non-positive pivot
+ * sets a device flag reported as ALS_ENOTSPD by the next als_loss/als_status_sync. */
+als_status als_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
+                          const als_params *params, als_table *X, int64_t row_begin,
+                          int64_t row_end, void *stream);
+
+/* One epoch (Algorithm 1, one pass of the outer loop): G_H = H^T H; W <- rows of Y
+ * solved against H; G_W = W^T W (from the new W); H <- rows of Yt solved against W.
+ * Yt must be the transpose of Y in CSR form.  W and H are updated in place. */
+als_status als_epoch(als_ctx *ctx, const als_csr *Y, const als_csr *Yt, als_table *W,
+                     als_table *H, const als_params *params, void *stream);
+
+/* The objective of Eq. 3,
+ *     sum_{(u,i,y) in Y} (y - <w_u,h_i>)^2 + alpha * sum_u sum_i <w_u,h_i>^2
+ *       + lambda * (||W||_F^2 + ||H||_F^2),
+ * with the all-pairs term evaluated as <W^T W, H^T H>_F.  Writes one fp64 value
+ * to host memory; synchronises `stream`. */
+als_status als_loss(als_ctx *ctx, const als_csr *Y, const als_table *W, const als_table *H,
+                    const als_params *params, double *loss_host, void *stream);
+
+/* Synchronise `stream` and report (then clear) the device-side error flag. */
+als_status als_status_sync(als_ctx *ctx, void *stream);
+
+/* Opt-in validation pass over a CSR matrix (one pass over indptr and indices):
+ * ALS_OK, or ALS_EINVAL if indptr is not monotone from 0 to nnz or a column id
+ * is out of range.  Synchronises `stream`. */
+als_status als_check_csr(als_ctx *ctx, const als_csr *Y, void *stream);
+
+/* Accumulated GPU time in milliseconds (HIP events on the call's stream) of the
+ * kernels launched by the most recent als_gramian / als_solve_rows / als_epoch,
+ * by stage: [0] gramian, [1] row classification, [2] table transform for the dual
+ * form, [3] dual row kernel, [4] primal fused row kernel, [5] long-row segment
+ * accumulation, [6] long-row reduce+solve, [7] number of dual-kernel launches.
+ * Timing is recorded only while enabled with als_set_timing(ctx, 1); reading
+ * synchronises the recorded events. */
+als_status als_set_timing(als_ctx *ctx, int enabled);
+als_status als_get_timing(als_ctx *ctx, double *ms_host /* [8] */);
+
+const char *als_strerror(als_status status);
+const char *als_last_error(const als_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ALS_H */

@@ -1,0 +1,127 @@
+// Gramian G = V^T V of an embedding table (paper Section 3, the remark after Eq. 4; Algorithm 1
+// line 2): a tall-skinny contraction over the table's rows on the fp32 matrix cores.
+//
+// Each wavefront walks a strided set of row groups; a lane fetches NC consecutive columns of one
+// row with a single vector load and feeds them as both MFMA operands (see Geo<> for the column
+// interleave), accumulating all (d/TM)^2 output tiles in registers.  The four wavefronts of a
+// workgroup are summed through LDS in a fixed order, every workgroup writes one fp32 partial
+// Gramian, and a second kernel adds the partials in fp64 in a fixed order, so the result is
+// reproducible bit for bit and the fp32 summation chains stay short (rows / (waves * KS)).
+#include "als_internal.h"
+
+namespace als {
+
+constexpr int GRAM_THREADS = 256;
+constexpr int GRAM_MAX_BLOCKS = 1024;
+
+template <int D, bool BF16>
+__global__ __launch_bounds__(GRAM_THREADS) void gramian_partial_kernel(const void *__restrict__ V, int64_t rows,
+                                                                       int64_t ld, float *__restrict__ partials) {
+    using G = Geo<D>;
+    constexpr int NC = G::NC, TM = G::TM, KS = G::KS, ACC = G::ACC;
+    typedef typename AccT<ACC>::type acc_t;
+    __shared__ float red[D * D];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane % TM, kk = lane / TM;
+    const int64_t wave_id = (int64_t)blockIdx.x * (GRAM_THREADS / 64) + wave;
+    const int64_t nwaves = (int64_t)gridDim.x * (GRAM_THREADS / 64);
+
+    acc_t acc[NC][NC];
+#pragma unroll
+    for (int i = 0; i < NC; ++i)
+#pragma unroll
+        for (int j = 0; j < NC; ++j)
+#pragma unroll
+            for (int v = 0; v < ACC; ++v) acc[i][j][v] = 0.f;
+
+    // rows r0 + kk, r0 advancing by KS per MFMA step; two steps in flight per iteration
+    for (int64_t r0 = wave_id * KS; r0 < rows; r0 += nwaves * KS * 2) {
+        float x0[NC], x1[NC];
+        const int64_t ra = r0 + kk, rb = r0 + nwaves * KS + kk;
+        if (ra < rows) {
+            load_vec<NC, BF16>(V, ra * ld + NC * m, x0);
+        } else {
+#pragma unroll
+            for (int c = 0; c < NC; ++c) x0[c] = 0.f;
+        }
+        if (rb < rows) {
+            load_vec<NC, BF16>(V, rb * ld + NC * m, x1);
+        } else {
+#pragma unroll
+            for (int c = 0; c < NC; ++c) x1[c] = 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < NC; ++i)
+#pragma unroll
+            for (int j = i; j < NC; ++j) {  // upper tiles only; the result is symmetric
+                acc[i][j] = mfma<D>(x0[i], x0[j], acc[i][j]);
+                acc[i][j] = mfma<D>(x1[i], x1[j], acc[i][j]);
+            }
+    }
+
+    // fixed-order sum of the four wavefronts through LDS
+    for (int w = 0; w < GRAM_THREADS / 64; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int i = 0; i < NC; ++i)
+#pragma unroll
+                for (int j = i; j < NC; ++j)
+#pragma unroll
+                    for (int v = 0; v < ACC; ++v) {
+                        const int r = NC * acc_row<D>(v, lane) + i, c = NC * m + j;
+                        if (w == 0) red[r * D + c] = acc[i][j][v];
+                        else red[r * D + c] += acc[i][j][v];
+                    }
+        }
+        __syncthreads();
+    }
+    float *out = partials + (int64_t)blockIdx.x * D * D;
+    for (int e = threadIdx.x; e < D * D; e += GRAM_THREADS) {
+        const int r = e / D, c = e % D;
+        // tile (i,j) with i<=j was computed, where i = r % NC, j = c % NC; otherwise mirror
+        const bool have = (r % NC) <= (c % NC);
+        out[e] = have ? red[r * D + c] : red[c * D + r];
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void gramian_reduce_kernel(const float *__restrict__ partials, int nblocks,
+                                                             float *__restrict__ G) {
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= D * D) return;
+    double s = 0.0;
+#pragma unroll 8
+    for (int b = 0; b < nblocks; ++b) s += (double)partials[(int64_t)b * D * D + e];
+    G[e] = (float)s;
+}
+
+template <int D, bool BF16>
+static als_status gramian_typed(als_ctx *ctx, const als_table *V, float *G, hipStream_t s) {
+    constexpr int KS = Geo<D>::KS;
+    int64_t per_block = (int64_t)(GRAM_THREADS / 64) * KS * 2 * 8;  // at least 8 iterations per wave
+    int nblocks = (int)std::min<int64_t>(GRAM_MAX_BLOCKS, std::max<int64_t>(1, (V->rows + per_block - 1) / per_block));
+    als_status st = ensure(ctx, ctx->gram_partials, (size_t)GRAM_MAX_BLOCKS * D * D * sizeof(float));
+    if (st != ALS_OK) return st;
+    timer_begin(ctx, T_GRAMIAN, s);
+    hipLaunchKernelGGL((gramian_partial_kernel<D, BF16>), dim3(nblocks), dim3(GRAM_THREADS), 0, s, V->data, V->rows,
+                       V->ld, (float *)ctx->gram_partials.p);
+    hipLaunchKernelGGL((gramian_reduce_kernel<D>), dim3((D * D + 255) / 256), dim3(256), 0, s,
+                       (const float *)ctx->gram_partials.p, nblocks, G);
+    timer_end(ctx, s);
+    ALS_HIP(ctx, hipGetLastError());
+    return ALS_OK;
+}
+
+als_status launch_gramian(als_ctx *ctx, const als_table *V, float *G, hipStream_t s) {
+    const bool bf = V->dtype == ALS_BF16;
+    switch (V->d) {
+        case 16: return bf ? gramian_typed<16, true>(ctx, V, G, s) : gramian_typed<16, false>(ctx, V, G, s);
+        case 32: return bf ? gramian_typed<32, true>(ctx, V, G, s) : gramian_typed<32, false>(ctx, V, G, s);
+        case 64: return bf ? gramian_typed<64, true>(ctx, V, G, s) : gramian_typed<64, false>(ctx, V, G, s);
+        case 128: return bf ? gramian_typed<128, true>(ctx, V, G, s) : gramian_typed<128, false>(ctx, V, G, s);
+    }
+    return fail(ctx, ALS_EDTYPE, "unsupported d");
+}
+
+}  // namespace als

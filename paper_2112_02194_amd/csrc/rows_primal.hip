@@ -1,0 +1,300 @@
+// Primal row update: the d x d normal equations of the paper's Eq. 4, formed and solved per row
+// exactly in the order of Algorithm 1 lines 4-10:
+//     A = alpha*G + lambda*I ;  b = 0
+//     for every stored (u, i, y):  A += v_i (x) v_i ;  b += y * v_i
+//     x_u = A^{-1} b            (Cholesky, A is symmetric positive definite because lambda > 0)
+//
+// One workgroup owns one row (or one segment of a long row).  The gathered rows of the fixed
+// table go straight from global memory into MFMA operand registers (no staging): lane (m, kk)
+// loads the NC consecutive columns NC*m.. of the kk-th entry of the current step, wavefront I of
+// the workgroup accumulates tile-row I of V_I^T V_I (see Geo<>).  The finished tiles are written
+// to LDS together with alpha*G + lambda*I, factorised there, and the two triangular solves give
+// the new row, which is rounded once to the table's element type.
+//
+// Rows longer than `split` are cut into segments (the counterpart of the paper's Section 4.3 row
+// splitting): each segment's partial statistics go to a workspace and a second kernel sums them
+// in a fixed order before the same factorisation.
+#include "als_internal.h"
+
+namespace als {
+
+template <int D> struct Team {
+    static constexpr int WAVES = Geo<D>::NC;      // one wavefront per tile-row
+    static constexpr int THREADS = 64 * WAVES;
+    static constexpr int LD = D + 1;              // LDS leading dimension (odd: conflict-free both ways)
+    static constexpr size_t LDS_BYTES = (size_t)(D * LD + 4 * D) * sizeof(float);
+};
+
+// ---------------------------------------------------------------------------------------------- accumulate
+// Accumulates, for entries [begin, end) of the CSR arrays, tile-row `I` of sum v (x) v into acc[]
+// and this lane's share of sum y*v into bsum[] (lane (m,kk) holds columns NC*m.. of entries kk mod KS).
+template <int D, bool BF16>
+__device__ __forceinline__ void accumulate_entries(const void *__restrict__ V, int64_t ld,
+                                                   const int32_t *__restrict__ indices,
+                                                   const float *__restrict__ values, int64_t begin, int64_t end,
+                                                   int I, typename AccT<Geo<D>::ACC>::type (&acc)[Geo<D>::NC],
+                                                   float (&bsum)[Geo<D>::NC]) {
+    using G = Geo<D>;
+    constexpr int NC = G::NC, TM = G::TM, KS = G::KS, U = 4;
+    const int lane = threadIdx.x & 63;
+    const int m = lane % TM, kk = lane / TM;
+    for (int64_t base = begin; base < end; base += 64) {
+        const int64_t p = base + lane;
+        const int myidx = p < end ? indices[p] : -1;
+        const float myy = p < end ? (values ? values[p] : 1.f) : 0.f;
+        const int cnt = (int)((end - base) < 64 ? (end - base) : 64);
+        const int nsteps = (cnt + KS - 1) / KS;
+        for (int s0 = 0; s0 < nsteps; s0 += U) {
+            float x[U][NC], y[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int e = (s0 + u) * KS + kk;
+                const int idx = e < 64 ? __shfl(myidx, e & 63) : -1;
+                y[u] = e < 64 ? __shfl(myy, e & 63) : 0.f;
+                if (idx >= 0) {
+                    load_vec<NC, BF16>(V, (int64_t)idx * ld + NC * m, x[u]);
+                } else {
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) x[u][c] = 0.f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float a = x[u][0];
+#pragma unroll
+                for (int c = 1; c < NC; ++c) a = (I == c) ? x[u][c] : a;
+#pragma unroll
+                for (int j = 0; j < NC; ++j) {
+                    acc[j] = mfma<D>(a, x[u][j], acc[j]);
+                    bsum[j] += y[u] * x[u][j];
+                }
+            }
+        }
+    }
+}
+
+// Sum bsum over the KS lanes that hold the same columns; afterwards lanes with kk == 0 hold b.
+template <int D> __device__ __forceinline__ void fold_b(float (&bsum)[Geo<D>::NC]) {
+    constexpr int TM = Geo<D>::TM, KS = Geo<D>::KS, NC = Geo<D>::NC;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+#pragma unroll
+        for (int off = TM * KS / 2; off >= TM; off >>= 1) bsum[c] += __shfl_xor(bsum[c], off);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------- LDS solve
+// a: [D][LD] with entry (r, c), r >= c, at a[c*LD + r]; on exit column c of L sits at a[c*LD + r]
+// and its mirror copy at a[r*LD + c].  aux: dinv[D], z[D], xout[D], bvec[D].
+template <int D>
+__device__ __forceinline__ void cholesky_solve_lds(float *a, float *aux, int32_t *err_flag) {
+    constexpr int LD = Team<D>::LD, T = Team<D>::THREADS, TY = T / 32;
+    float *dinv = aux, *z = aux + D, *xout = aux + 2 * D, *bvec = aux + 3 * D;
+    const int t = threadIdx.x, tx = t & 31, ty = t >> 5;
+    for (int k = 0; k < D; ++k) {
+        const float pivot = a[k * LD + k];
+        if (t == 0 && !(pivot > 0.f)) atomicOr(err_flag, 1);
+        const float rinv = 1.0f / sqrtf(pivot);
+        for (int i = k + 1 + t; i < D; i += T) {
+            const float l = a[k * LD + i] * rinv;
+            a[k * LD + i] = l;
+            a[i * LD + k] = l;
+        }
+        if (t == 0) dinv[k] = rinv;
+        __syncthreads();
+        for (int j = k + 1 + ty; j < D; j += TY) {
+            const float cj = a[k * LD + j];
+            for (int i = j + tx; i < D; i += 32) a[j * LD + i] -= a[k * LD + i] * cj;
+        }
+        __syncthreads();
+    }
+    // L z = b
+    for (int j = 0; j < D; ++j) {
+        const float zj = bvec[j] * dinv[j];  // final: only entries i > j change in step j
+        for (int i = j + 1 + t; i < D; i += T) bvec[i] -= a[j * LD + i] * zj;
+        if (t == 0) z[j] = zj;
+        __syncthreads();
+    }
+    // L^T x = z
+    for (int i = D - 1; i >= 0; --i) {
+        const float xi = z[i] * dinv[i];
+        for (int j = t; j < i; j += T) z[j] -= a[i * LD + j] * xi;
+        if (t == 0) xout[i] = xi;
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------------------------- kernels
+enum PrimalMode { MODE_FUSED = 0, MODE_SEGMENT = 1 };
+
+// MODE_FUSED:   work item = a whole row u (u = row_list ? row_list[item] : row_begin + item);
+//               rows with k_lo < k <= k_hi entries are solved, others skipped.
+// MODE_SEGMENT: work item = segment `item` of segs[]; raw partial statistics are written to
+//               partials[item][D*D + D] (row-major D x D, then b).
+template <int D, bool BF16, int MODE>
+__global__ __launch_bounds__(Team<D>::THREADS) void primal_kernel(
+    const int64_t *__restrict__ indptr, const int32_t *__restrict__ indices, const float *__restrict__ values,
+    const void *__restrict__ V, int64_t ldv, const float *__restrict__ G, float alpha, float lambda,
+    void *__restrict__ X, int64_t ldx, int64_t row_begin, const int64_t *__restrict__ row_list,
+    int64_t k_lo, int64_t k_hi, const Segment *__restrict__ segs, float *__restrict__ partials,
+    int32_t *__restrict__ err_flag) {
+    using GE = Geo<D>;
+    constexpr int NC = GE::NC, TM = GE::TM, ACC = GE::ACC, LD = Team<D>::LD;
+    typedef typename AccT<ACC>::type acc_t;
+    extern __shared__ float lds[];
+    float *a = lds, *aux = lds + D * LD, *bvec = aux + 3 * D;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane % TM, kk = lane / TM;
+    const int64_t item = blockIdx.x;
+    int64_t u = 0, begin, end;
+    if constexpr (MODE == MODE_FUSED) {
+        u = row_list ? row_list[item] : row_begin + item;
+        begin = indptr[u];
+        end = indptr[u + 1];
+        const int64_t k = end - begin;
+        if (k <= k_lo || k > k_hi) return;  // k_lo >= 0: empty rows are zeroed by the row classifier
+    } else {
+        begin = segs[item].begin;
+        end = segs[item].end;
+    }
+
+    acc_t acc[NC];
+    float bsum[NC];
+#pragma unroll
+    for (int j = 0; j < NC; ++j) {
+        bsum[j] = 0.f;
+#pragma unroll
+        for (int v = 0; v < ACC; ++v) acc[j][v] = 0.f;
+    }
+    accumulate_entries<D, BF16>(V, ldv, indices, values, begin, end, wave, acc, bsum);
+    fold_b<D>(bsum);
+
+    if constexpr (MODE == MODE_SEGMENT) {
+        float *out = partials + item * (int64_t)(D * D + D);
+#pragma unroll
+        for (int j = 0; j < NC; ++j)
+#pragma unroll
+            for (int v = 0; v < ACC; ++v) {
+                const int r = NC * acc_row<D>(v, lane) + wave, c = NC * m + j;
+                out[r * D + c] = acc[j][v];
+            }
+        if (wave == 0 && kk == 0) {
+#pragma unroll
+            for (int j = 0; j < NC; ++j) out[D * D + NC * m + j] = bsum[j];
+        }
+        return;
+    } else {
+        // A = alpha*G + lambda*I + V_I^T V_I into LDS (entry (r,c) at a[c*LD + r])
+#pragma unroll
+        for (int j = 0; j < NC; ++j)
+#pragma unroll
+            for (int v = 0; v < ACC; ++v) {
+                const int r = NC * acc_row<D>(v, lane) + wave, c = NC * m + j;
+                a[c * LD + r] = acc[j][v] + alpha * G[r * D + c] + (r == c ? lambda : 0.f);
+            }
+        if (wave == 0 && kk == 0) {
+#pragma unroll
+            for (int j = 0; j < NC; ++j) bvec[NC * m + j] = bsum[j];
+        }
+        __syncthreads();
+        cholesky_solve_lds<D>(a, aux, err_flag);
+        const float *xout = aux + 2 * D;
+        for (int c = threadIdx.x; c < D; c += Team<D>::THREADS) store_elem<BF16>(X, u * ldx + c, xout[c]);
+    }
+}
+
+// Sums the segment partials of one long row (fixed order), adds alpha*G + lambda*I, solves, stores.
+template <int D, bool BF16>
+__global__ __launch_bounds__(Team<D>::THREADS) void reduce_solve_kernel(
+    const LongRow *__restrict__ long_rows, const float *__restrict__ partials, const float *__restrict__ G,
+    float alpha, float lambda, void *__restrict__ X, int64_t ldx, int32_t *__restrict__ err_flag) {
+    constexpr int LD = Team<D>::LD, T = Team<D>::THREADS;
+    extern __shared__ float lds[];
+    float *a = lds, *aux = lds + D * LD, *bvec = aux + 3 * D;
+    const LongRow lr = long_rows[blockIdx.x];
+    const float *p0 = partials + (int64_t)lr.seg_first * (D * D + D);
+    for (int e = threadIdx.x; e < D * D + D; e += T) {
+        float s = 0.f;
+        for (int g = 0; g < lr.nseg; ++g) s += p0[(int64_t)g * (D * D + D) + e];
+        if (e < D * D) {
+            const int r = e / D, c = e % D;
+            a[c * LD + r] = s + alpha * G[e] + (r == c ? lambda : 0.f);
+        } else {
+            bvec[e - D * D] = s;
+        }
+    }
+    __syncthreads();
+    cholesky_solve_lds<D>(a, aux, err_flag);
+    const float *xout = aux + 2 * D;
+    for (int c = threadIdx.x; c < D; c += T) store_elem<BF16>(X, lr.row * ldx + c, xout[c]);
+}
+
+// ---------------------------------------------------------------------------------------------- launchers
+template <int D, bool BF16>
+static als_status primal_typed(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
+                               const als_params *prm, als_table *X, int64_t r0, const int64_t *row_list,
+                               int64_t nitems, int64_t k_lo, int64_t k_hi, hipStream_t s) {
+    if (nitems <= 0) return ALS_OK;
+    int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
+    auto kern = primal_kernel<D, BF16, MODE_FUSED>;
+    ALS_HIP(ctx, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)Team<D>::LDS_BYTES));
+    timer_begin(ctx, T_PRIMAL, s);
+    hipLaunchKernelGGL(kern, dim3((unsigned)nitems), dim3(Team<D>::THREADS), Team<D>::LDS_BYTES, s, Y->indptr,
+                       Y->indices, Y->values, V->data, V->ld, G, prm->alpha, prm->lambda, X->data, X->ld, r0,
+                       row_list, k_lo, k_hi, (const Segment *)nullptr, (float *)nullptr, err);
+    timer_end(ctx, s);
+    ALS_HIP(ctx, hipGetLastError());
+    return ALS_OK;
+}
+
+template <int D, bool BF16>
+static als_status long_typed(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
+                             const als_params *prm, als_table *X, const LongRow *long_rows, int n_long,
+                             const Segment *segs, int n_seg, hipStream_t s) {
+    if (n_long <= 0) return ALS_OK;
+    als_status st = ensure(ctx, ctx->seg_partials, (size_t)n_seg * (D * D + D) * sizeof(float));
+    if (st != ALS_OK) return st;
+    int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
+    auto kseg = primal_kernel<D, BF16, MODE_SEGMENT>;
+    auto kred = reduce_solve_kernel<D, BF16>;
+    ALS_HIP(ctx, hipFuncSetAttribute((const void *)kred, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)Team<D>::LDS_BYTES));
+    timer_begin(ctx, T_SEGMENT, s);
+    hipLaunchKernelGGL(kseg, dim3((unsigned)n_seg), dim3(Team<D>::THREADS), 0, s, Y->indptr, Y->indices, Y->values,
+                       V->data, V->ld, G, prm->alpha, prm->lambda, X->data, X->ld, (int64_t)0,
+                       (const int64_t *)nullptr, (int64_t)0, (int64_t)0, segs, (float *)ctx->seg_partials.p, err);
+    timer_end(ctx, s);
+    timer_begin(ctx, T_REDUCE, s);
+    hipLaunchKernelGGL(kred, dim3((unsigned)n_long), dim3(Team<D>::THREADS), Team<D>::LDS_BYTES, s, long_rows,
+                       (const float *)ctx->seg_partials.p, G, prm->alpha, prm->lambda, X->data, X->ld, err);
+    timer_end(ctx, s);
+    ALS_HIP(ctx, hipGetLastError());
+    return ALS_OK;
+}
+
+#define ALS_DISPATCH(fn, d, bf, ...)                                                       \
+    switch (d) {                                                                           \
+        case 16: return bf ? fn<16, true>(__VA_ARGS__) : fn<16, false>(__VA_ARGS__);       \
+        case 32: return bf ? fn<32, true>(__VA_ARGS__) : fn<32, false>(__VA_ARGS__);       \
+        case 64: return bf ? fn<64, true>(__VA_ARGS__) : fn<64, false>(__VA_ARGS__);       \
+        case 128: return bf ? fn<128, true>(__VA_ARGS__) : fn<128, false>(__VA_ARGS__);    \
+    }                                                                                      \
+    return fail(ctx, ALS_EDTYPE, "unsupported d")
+
+als_status launch_primal_fused(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
+                               const als_params *prm, als_table *X, int64_t r0, const int64_t *row_list,
+                               int64_t nitems, int64_t k_lo, int64_t k_hi, hipStream_t s) {
+    const bool bf = V->dtype == ALS_BF16;
+    ALS_DISPATCH(primal_typed, V->d, bf, ctx, Y, V, G, prm, X, r0, row_list, nitems, k_lo, k_hi, s);
+}
+
+als_status launch_primal_long(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
+                              const als_params *prm, als_table *X, const LongRow *long_rows, int n_long,
+                              const Segment *segs, int n_seg, hipStream_t s) {
+    const bool bf = V->dtype == ALS_BF16;
+    ALS_DISPATCH(long_typed, V->d, bf, ctx, Y, V, G, prm, X, long_rows, n_long, segs, n_seg, s);
+}
+
+}  // namespace als

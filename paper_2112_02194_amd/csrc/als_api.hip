@@ -153,7 +153,7 @@ als_status als_destroy(als_ctx *ctx) {
     if (!ctx) return ALS_OK;
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
-    DevBuf *bufs[] = {&ctx->gram_partials, &ctx->lists, &ctx->seg_partials, &ctx->ztable, &ctx->small,
+    DevBuf *bufs[] = {&ctx->gram_partials, &ctx->lists, &ctx->seg_partials, &ctx->ztable, &ctx->rtable, &ctx->small,
                       &ctx->loss_partials, &ctx->gram_w, &ctx->gram_h};
     for (DevBuf *b : bufs)
         if (b->p) (void)hipFree(b->p);

@@ -135,6 +135,7 @@ struct als_ctx {
     als::DevBuf lists;          // long-row and segment descriptors
     als::DevBuf seg_partials;   // fp32 [nseg][d*d + d] partial statistics of long-row segments
     als::DevBuf ztable;         // fp32 [rows][d] transformed fixed table of the dual form
+    als::DevBuf rtable;         // fp32 [rows][d] untransformed dual solutions when the output table is bf16
     als::DevBuf small;          // counters, flags, factor matrices, scalars
     als::DevBuf loss_partials;  // fp64 per-workgroup sums
     als::DevBuf gram_w, gram_h; // fp32 [d*d] Gramians used by als_epoch / als_loss

@@ -79,6 +79,12 @@ als_status launch_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V,
     int64_t *mid_list = dual_max > 0 ? (int64_t *)((char *)ctx->lists.p + off_mid) : nullptr;
     int32_t *counters = (int32_t *)((char *)ctx->small.p + SM_COUNTERS);
 
+    // Short rows first: the dual kernels need nothing from the classification, and their closing
+    // table transform passes over every row of the range, so the classifier (which zeroes the empty
+    // rows) and the primal kernels must come after it.
+    if (dual_max > 0) {
+        if ((st = launch_dual(ctx, Y, V, G, prm, X, r0, r1, dual_max, s)) != ALS_OK) return st;
+    }
     timer_begin(ctx, T_CLASSIFY, s);
     hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, s, counters);
     const unsigned cblocks = (unsigned)((nrows + 255) / 256);
@@ -91,11 +97,6 @@ als_status launch_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V,
     timer_end(ctx, s);
     ALS_HIP(ctx, hipGetLastError());
     ALS_HIP(ctx, hipMemcpyAsync(ctx->host_counters, counters, 4 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
-
-    // short rows need nothing from the classification: enqueue them before waiting for the counts
-    if (dual_max > 0) {
-        if ((st = launch_dual(ctx, Y, V, G, prm, X, r0, r1, dual_max, s)) != ALS_OK) return st;
-    }
     ALS_HIP(ctx, hipStreamSynchronize(s));
     const int n_long = ctx->host_counters[0], n_seg = ctx->host_counters[1], n_mid = ctx->host_counters[3];
     if (n_long > cap_long || n_seg > cap_seg || n_mid > cap_mid)

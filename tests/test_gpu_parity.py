@@ -75,10 +75,44 @@ def test_solve_rows_primal_matches_oracle(ctx, gpu_device, d, values):
 
 
 @pytest.mark.parametrize("d", [16, 128])
-def test_solve_rows_primal_bf16_tables(ctx, gpu_device, d):
-    say(f"solve_rows primal bf16 d={d}")
+@pytest.mark.parametrize("path", [als.PATH_PRIMAL, als.PATH_AUTO])
+def test_solve_rows_bf16_tables(ctx, gpu_device, d, path):
+    say(f"solve_rows bf16 d={d} path={path}")
     p = make_problem("c1", rows=500, cols=400, d=d, dtype="bf16")
-    _solve_case(ctx, gpu_device, p, als.PATH_PRIMAL, scale_v=8.0)
+    _solve_case(ctx, gpu_device, p, path, scale_v=8.0)
+
+
+@pytest.mark.parametrize("d", [16, 32, 64, 128])
+@pytest.mark.parametrize("values", ["ones", "uniform"])
+def test_solve_rows_auto_path_matches_oracle(ctx, gpu_device, d, values):
+    """Rows with k <= min(d, 64) entries take the k x k dual system, the rest the d x d one."""
+    say(f"solve_rows auto d={d} values={values}")
+    p = make_problem("c1", rows=900, cols=700, d=d, values=values)
+    deg = (p.indptr[1:] - p.indptr[:-1])
+    assert int(deg.max()) > 64 and int(deg.min()) <= 2  # both formulations are exercised
+    got_auto, ref = _solve_case(ctx, gpu_device, p, als.PATH_AUTO, scale_v=8.0)
+    got_primal, _ = _solve_case(ctx, gpu_device, p, als.PATH_PRIMAL, scale_v=8.0)
+    assert rel_fro(got_auto, got_primal) <= 2e-5
+
+
+@pytest.mark.parametrize("dual_max_k", [1, 7, 16, 17, 33, 48, 64])
+def test_dual_threshold_sweep(ctx, gpu_device, dual_max_k):
+    """The result does not depend on where the switch between the two formulations sits."""
+    say(f"solve_rows auto d=128 dual_max_k={dual_max_k}")
+    p = make_problem("c1", rows=600, cols=900, d=128, values="uniform")
+    _solve_case(ctx, gpu_device, p, als.PATH_AUTO, dual_max_k=dual_max_k, split=40, scale_v=8.0,
+                row_range=(3, 590))
+
+
+def test_dual_ill_conditioned_gramian(ctx, gpu_device):
+    """A table whose Gramian has a wide spectrum and a small lambda: cond(alpha*G + lambda*I) ~ 7e4."""
+    say("solve_rows auto ill-conditioned table")
+    p = make_problem("c1", rows=500, cols=800, d=64)
+    scale = torch.logspace(0, -2.5, 64)[None, :]
+    p.H0 = p.H0 * 40.0 * scale
+    p.lam = 1e-4
+    for path in (als.PATH_AUTO, als.PATH_PRIMAL):
+        _solve_case(ctx, gpu_device, p, path)
 
 
 @pytest.mark.parametrize("d,split", [(16, 5), (64, 7), (128, 16), (128, 33)])
@@ -95,12 +129,14 @@ def test_row_range_and_column_half(ctx, gpu_device):
     say("solve_rows row range + transposed matrix with hub rows and empty rows")
     p = make_problem("c1", rows=900, cols=700, d=32)
     _solve_case(ctx, gpu_device, p, als.PATH_PRIMAL, row_range=(101, 640), scale_v=8.0)
+    _solve_case(ctx, gpu_device, p, als.PATH_AUTO, row_range=(101, 640), scale_v=8.0)
     # the column half: rows of Y^T (hubs with > 500 entries, some empty rows)
     q = make_problem("c1", rows=900, cols=700, d=32)
     q.indptr, q.indices, q.values, q.rows, q.cols = p.t_indptr, p.t_indices, p.t_values, p.cols, p.rows
     q.H0 = p.W0
     assert int((q.indptr[1:] - q.indptr[:-1]).max()) > 300
     _solve_case(ctx, gpu_device, q, als.PATH_PRIMAL, split=128, scale_v=8.0)
+    _solve_case(ctx, gpu_device, q, als.PATH_AUTO, split=128, scale_v=8.0)
 
 
 def test_c1_four_epochs_end_to_end(ctx, gpu_device):

@@ -138,7 +138,7 @@ als_status als_create(als_ctx **out, int device) {
     als_status st = ensure(ctx, ctx->small, SM_BYTES);
     if (st == ALS_OK) st = ensure(ctx, ctx->gram_w, 128 * 128 * sizeof(float));
     if (st == ALS_OK) st = ensure(ctx, ctx->gram_h, 128 * 128 * sizeof(float));
-    if (st == ALS_OK && hipHostMalloc((void **)&ctx->host_counters, 8 * sizeof(int32_t)) != hipSuccess) st = ALS_ENOMEM;
+    if (st == ALS_OK && hipHostMalloc((void **)&ctx->host_counters, 16 * sizeof(int32_t)) != hipSuccess) st = ALS_ENOMEM;
     if (st == ALS_OK && hipHostMalloc((void **)&ctx->host_scalar, 2 * sizeof(double)) != hipSuccess) st = ALS_ENOMEM;
     if (st == ALS_OK && hipMemset(ctx->small.p, 0, ctx->small.bytes) != hipSuccess) st = ALS_EHIP;
     if (st != ALS_OK) {

@@ -139,7 +139,7 @@ struct als_ctx {
     als::DevBuf small;          // counters, flags, factor matrices, scalars
     als::DevBuf loss_partials;  // fp64 per-workgroup sums
     als::DevBuf gram_w, gram_h; // fp32 [d*d] Gramians used by als_epoch / als_loss
-    int32_t *host_counters = nullptr;  // pinned, 8 ints
+    int32_t *host_counters = nullptr;  // pinned, 16 ints
     double *host_scalar = nullptr;     // pinned, 2 doubles
     bool timing = false;
     std::vector<als::Timer> timers;
@@ -150,7 +150,7 @@ struct als_ctx {
 namespace als {
 
 // Layout of ctx->small (byte offsets).
-constexpr size_t SM_COUNTERS = 0;       // int32[8]: [0] n_long, [1] n_seg, [2] error flag, [3] n_mid
+constexpr size_t SM_COUNTERS = 0;       // int32[16]: [0] n_long [1] n_seg [2] error flag [3] n_mid [4] csr check [8..15] dual classes
 constexpr size_t SM_LOSS = 64;          // double[2]
 constexpr size_t SM_FACTOR = 256;       // fp32 [2][128*128]: L^{-1} and scratch for the dual form
 constexpr size_t SM_BYTES = SM_FACTOR + 2 * 128 * 128 * sizeof(float) + 128 * 128 * sizeof(double);

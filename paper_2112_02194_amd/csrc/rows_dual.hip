@@ -10,10 +10,12 @@
 // [1, 1 + k/alpha], so fp32 is comfortable.  Steps:
 //   factor_kernel     B -> L^{-1} in fp64 (one workgroup), stored fp32
 //   transform_kernel  Z = V L^{-T}   (fp32 MFMA, table-sized workspace)
-//   dual_wave_kernel  one wavefront per row: gather Z_I straight into MFMA operand registers,
-//                     S = I + Z_I Z_I^T on the matrix cores, Cholesky + two triangular solves with
-//                     one lane per row of S, r = Z_I^T t by a cross-lane reduction
+//   dual_rows_kernel  one wavefront per 4 / 2 / 1 rows (k <= 16 / 32 / 64): gather Z_I straight into
+//                     MFMA operand registers, S = I + Z_I Z_I^T on the matrix cores, Cholesky + two
+//                     triangular solves with one lane per row of S, then r = Z_I^T t
 //   transform_kernel  X = R L^{-1}   (rows r -> L^{-T} r), rounding to the table's element type
+#include <type_traits>
+
 #include "als_internal.h"
 
 namespace als {
@@ -69,14 +71,16 @@ __global__ __launch_bounds__(256) void factor_kernel(const float *__restrict__ G
 }
 
 // ---------------------------------------------------------------------------------------------- transform
-// Out[r][:] = In[r][:] * M for rows r in [r0, r1), M fp32 [D x D] row-major.  In may be bf16 or
+// Out[r][:] = In[r][:] * M for rows r in [r0, r1) (only rows with 0 < k <= k_max stored entries when
+// indptr is given), M fp32 [D x D] row-major.  In may be bf16 or
 // fp32, Out fp32 or bf16; Out may be the same buffer as In (a workgroup reads its whole row tile
 // into LDS before it writes).  Wavefront w owns output column tile w % NCT for the row sub-tiles
 // of its group and keeps its slice of M in registers.
 template <int D, bool IN_BF16, bool OUT_BF16>
 __global__ __launch_bounds__(256) void transform_kernel(const void *__restrict__ In, int64_t ldi,
                                                         void *__restrict__ Out, int64_t ldo,
-                                                        const float *__restrict__ M, int64_t r0, int64_t r1) {
+                                                        const float *__restrict__ M, int64_t r0, int64_t r1,
+                                                        const int64_t *__restrict__ indptr, int64_t k_max) {
     using GE = Geo<D>;
     constexpr int TM = GE::TM, KS = GE::KS, ACC = GE::ACC;
     constexpr int NCT = D / TM, RG = 4 / NCT, RT = 64, NSUB = RT / TM, LD = D + 1, NS = D / KS;
@@ -110,7 +114,12 @@ __global__ __launch_bounds__(256) void transform_kernel(const void *__restrict__
 #pragma unroll
             for (int v = 0; v < ACC; ++v) {
                 const int64_t r = base + sub * TM + acc_row<D>(v, lane);
-                if (r < r1) store_elem<OUT_BF16>(Out, r * ldo + TM * J + m, acc[v]);
+                bool keep = r < r1;
+                if (keep && indptr) {  // only rows solved in the dual form (0 < k <= k_max) are rewritten
+                    const int64_t k = indptr[r + 1] - indptr[r];
+                    keep = k > 0 && k <= k_max;
+                }
+                if (keep) store_elem<OUT_BF16>(Out, r * ldo + TM * J + m, acc[v]);
             }
         }
     }
@@ -123,8 +132,23 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__device__ __forceinline__ float readlane_f(float v, int l) {
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
+template <int B, int E, class F> __device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(f);
+    }
+}
+
+// Value of lane C of this lane's group of GW consecutive lanes (GW = 16: DPP row broadcast,
+// GW = 32: LDS-crossbar swizzle, GW = 64: scalar read of the lane).
+template <int GW, int C> __device__ __forceinline__ float group_bcast(float x) {
+    if constexpr (GW == 16) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x150 + C, 0xf, 0xf, true));
+    } else if constexpr (GW == 32) {
+        return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(x), C << 5));
+    } else {
+        return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), C));
+    }
 }
 
 // x + (x rotated by N lanes inside each row of 16 lanes)
@@ -133,166 +157,411 @@ template <int N> __device__ __forceinline__ float add_row_ror(float x) {
     return x + __int_as_float(r);
 }
 
-// One wavefront per row u with k_lo < k <= k_hi <= 16*KT stored entries.
-//   lane (a = lane%16, q = lane/16) loads, for entry e = 16*t + a and j < D/16, the four columns
-//   (4j+q)*4.. of z_e; the same register is the A and the B operand of v_mfma_f32_16x16x4, so tile
-//   (t1,t2) accumulates S[16*t1 + .][16*t2 + .] over all d columns.
-//   sbuf (LDS, per wavefront): K x (K+1) floats.
-template <int D, int KT>
-__global__ __launch_bounds__(256) void dual_wave_kernel(const int64_t *__restrict__ indptr,
-                                                        const int32_t *__restrict__ indices,
-                                                        const float *__restrict__ values,
-                                                        const float *__restrict__ Z, float *__restrict__ R,
-                                                        int64_t ldr, int64_t r0, int64_t r1, int k_lo, int k_hi) {
-    constexpr int K = 16 * KT, KP = K + 1, NJ = D / 16;
+template <int D, int K> struct DualCfg {
+    static constexpr int KT = K / 16;                       // 16-entry tiles per row
+    static constexpr int GW = K <= 16 ? 16 : (K <= 32 ? 32 : 64);  // lanes that share one row's k x k system
+    static constexpr int RPW = 64 / GW;                     // rows per wavefront
+    static constexpr int KP = K + 4;                        // LDS row stride of S (keeps rows 16-byte aligned)
+    static constexpr int NJ = D / 16;                       // float4 loads per lane and entry
+    static constexpr bool ZBUF = K <= 32;                   // r = Z_I^T t through an LDS copy of Z_I
+    static constexpr int ZLD = D + 4;
+    static constexpr int SB_FLOATS = RPW * K * KP;
+    static constexpr int ZB_FLOATS = ZBUF ? K * ZLD : 0;
+    static constexpr int LDS_FLOATS = (SB_FLOATS > ZB_FLOATS ? SB_FLOATS : ZB_FLOATS) + 64;
+};
+
+// One wavefront (= one workgroup) solves RPW rows taken from `list` (row ids relative to r0), all
+// with at most K stored entries:
+//   1. per row, lane (a = lane%16, q = lane/16) loads for entry e = 16t + a and j < D/16 the four
+//      columns (4j+q)*4.. of z_e; the same register is the A and the B operand of
+//      v_mfma_f32_16x16x4, so tile (t1,t2) accumulates S[16 t1 + .][16 t2 + .] over all d columns;
+//      S = I + Z_I Z_I^T goes to LDS;
+//   2. lane i of a row's group of GW lanes owns row i of S: right-looking Cholesky with the column
+//      broadcast inside the group, then L w = y, then L^T t = w with L read back transposed;
+//   3. r = Z_I^T t, either from an LDS copy of Z_I with one lane per output column pair, or (K > 32)
+//      by a cross-lane reduction of the lanes' own pieces.
+template <int D, int K>
+__global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict__ indptr,
+                                                       const int32_t *__restrict__ indices,
+                                                       const float *__restrict__ values,
+                                                       const float *__restrict__ Z, float *__restrict__ R,
+                                                       int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
+                                                       int count, int32_t *__restrict__ err_flag) {
+    using C = DualCfg<D, K>;
+    constexpr int KT = C::KT, GW = C::GW, RPW = C::RPW, KP = C::KP, NJ = C::NJ, ZLD = C::ZLD;
     extern __shared__ float lds[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    float *sbuf = lds + wave * K * KP;
-    const int64_t u = r0 + (int64_t)blockIdx.x * 4 + wave;
-    if (u >= r1) return;  // no workgroup barrier below: wavefronts are independent
-    const int64_t b = indptr[u];
-    const int k = (int)(indptr[u + 1] - b);
-    if (k <= k_lo || k > k_hi) return;
+    float *sb = lds, *zb = lds, *tb = lds + (C::LDS_FLOATS - 64);
+    const int lane = threadIdx.x;
     const int a = lane & 15, q = lane >> 4;
+    const int grp = lane / GW, gi = lane % GW;
+    const int myrow = gi < K ? gi : K - 1;  // K = 48: lanes 48..63 shadow row 47
 
-    float4 z[KT][NJ];
+    int64_t u[RPW], b[RPW];
+    int k[RPW], kmax = 0;
 #pragma unroll
-    for (int t = 0; t < KT; ++t) {
-        const int e = 16 * t + a;
-        const int64_t idx = e < k ? (int64_t)indices[b + e] : -1;
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-            if (idx >= 0) z[t][j] = *(const float4 *)(Z + idx * D + (4 * j + q) * 4);
-            else z[t][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int p = 0; p < RPW; ++p) {
+        const int item = blockIdx.x * RPW + p;
+        u[p] = -1; b[p] = 0; k[p] = 0;
+        if (item < count) {
+            u[p] = r0 + list[item];
+            b[p] = indptr[u[p]];
+            k[p] = (int)(indptr[u[p] + 1] - b[p]);
         }
+        kmax = k[p] > kmax ? k[p] : kmax;
     }
-    float yv = 0.f;  // lane e holds the label of entry e
-    if (lane < k) yv = values ? values[b + lane] : 1.f;
 
-    floatx4 acc[KT][KT];
+    // ---- 1. gather + S tiles
+    float4 z[RPW][KT][NJ];
 #pragma unroll
-    for (int t1 = 0; t1 < KT; ++t1)
+    for (int p = 0; p < RPW; ++p)
 #pragma unroll
-        for (int t2 = 0; t2 <= t1; ++t2) acc[t1][t2] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < KT; ++t) {
+            const int e = 16 * t + a;
+            const int64_t idx = e < k[p] ? (int64_t)indices[b[p] + e] : -1;
 #pragma unroll
-    for (int j = 0; j < NJ; ++j)
+            for (int j = 0; j < NJ; ++j) {
+                if (idx >= 0) z[p][t][j] = *(const float4 *)(Z + idx * D + (4 * j + q) * 4);
+                else z[p][t][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+    int myk = 0;
+    int64_t myb = 0;
+#pragma unroll
+    for (int p = 0; p < RPW; ++p) {
+        myk = grp == p ? k[p] : myk;
+        myb = grp == p ? b[p] : myb;
+    }
+    float yv = 0.f;  // lane i of a group holds the label of entry i
+    if (gi < myk) yv = values ? values[myb + gi] : 1.f;
+
+#pragma unroll
+    for (int p = 0; p < RPW; ++p) {
+        floatx4 acc[KT][KT];
 #pragma unroll
         for (int t1 = 0; t1 < KT; ++t1)
 #pragma unroll
-            for (int t2 = 0; t2 <= t1; ++t2) {
-                acc[t1][t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[t1][j].x, z[t2][j].x, acc[t1][t2], 0, 0, 0);
-                acc[t1][t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[t1][j].y, z[t2][j].y, acc[t1][t2], 0, 0, 0);
-                acc[t1][t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[t1][j].z, z[t2][j].z, acc[t1][t2], 0, 0, 0);
-                acc[t1][t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[t1][j].w, z[t2][j].w, acc[t1][t2], 0, 0, 0);
-            }
-    // S = I + Z_I Z_I^T into LDS (lower block triangle; diagonal tiles in full)
+            for (int t2 = 0; t2 <= t1; ++t2) acc[t1][t2] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int t1 = 0; t1 < KT; ++t1)
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
-        for (int t2 = 0; t2 <= t1; ++t2)
+            for (int t1 = 0; t1 < KT; ++t1)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int i = 16 * t1 + 4 * q + v, jc = 16 * t2 + a;
-                sbuf[i * KP + jc] = acc[t1][t2][v] + (i == jc ? 1.f : 0.f);
-            }
+                for (int t2 = 0; t2 <= t1; ++t2) {
+                    acc[t1][t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][t1][j].x, z[p][t2][j].x, acc[t1][t2], 0, 0, 0);
+                    acc[t1][t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][t1][j].y, z[p][t2][j].y, acc[t1][t2], 0, 0, 0);
+                    acc[t1][t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][t1][j].z, z[p][t2][j].z, acc[t1][t2], 0, 0, 0);
+                    acc[t1][t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][t1][j].w, z[p][t2][j].w, acc[t1][t2], 0, 0, 0);
+                }
+        // lower block triangle of S = I + Z_I Z_I^T (diagonal tiles in full)
+#pragma unroll
+        for (int t1 = 0; t1 < KT; ++t1)
+#pragma unroll
+            for (int t2 = 0; t2 <= t1; ++t2)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int i = 16 * t1 + 4 * q + v, jc = 16 * t2 + a;
+                    sb[(p * K + i) * KP + jc] = acc[t1][t2][v] + (i == jc ? 1.f : 0.f);
+                }
+    }
     wave_sync();
-    // lane i owns row i of S; entries right of the diagonal are never used
-    const int myrow = lane < K ? lane : K - 1;
+
+    // ---- 2. Cholesky and the two triangular solves; entries right of the diagonal are never used
     float s[K];
+    {
+        const float4 *row = (const float4 *)(sb + (grp * K + myrow) * KP);
 #pragma unroll
-    for (int c = 0; c < K; ++c) s[c] = sbuf[myrow * KP + c];
+        for (int c4 = 0; c4 < K / 4; ++c4) {
+            const float4 v = row[c4];
+            s[4 * c4] = v.x; s[4 * c4 + 1] = v.y; s[4 * c4 + 2] = v.z; s[4 * c4 + 3] = v.w;
+        }
+    }
     wave_sync();
-    // right-looking Cholesky, one column per step; lane i ends with L[i][c] in s[c] (c <= i)
     float myrinv = 1.f;
-#pragma unroll
-    for (int c = 0; c < K; ++c) {
-        if (c < k) {
-            const float pivot = readlane_f(s[c], c);
-            const float rinv = 1.0f / sqrtf(pivot);
+    bool bad = false;
+    static_for<0, K>([&](auto cc) {
+        constexpr int c = decltype(cc)::value;
+        if (c < kmax) {  // steps beyond every row's k only meet identity rows
+            const float pivot = group_bcast<GW, c>(s[c]);
+            bad |= !(pivot > 0.f);
+            float rinv = __builtin_amdgcn_rsqf(pivot);
+            rinv = rinv * (1.5f - 0.5f * pivot * rinv * rinv);  // one Newton step on the hardware estimate
             const float lc = s[c] * rinv;
             s[c] = lc;
-            myrinv = lane == c ? rinv : myrinv;
-#pragma unroll
-            for (int i = c + 1; i < K; ++i) s[i] -= lc * readlane_f(lc, i);
+            myrinv = myrow == c ? rinv : myrinv;
+            static_for<c + 1, K>([&](auto ii) {
+                constexpr int i = decltype(ii)::value;
+                s[i] -= lc * group_bcast<GW, i>(lc);
+            });
         }
-    }
-    // L w = y (lane i ends with w_i); rows beyond k are identity rows with zero right-hand side
-#pragma unroll
-    for (int c = 0; c < K; ++c) {
-        if (c < k) {
-            const float wc = readlane_f(yv, c) * readlane_f(myrinv, c);
-            yv = lane > c ? yv - s[c] * wc : (lane == c ? wc : yv);
+    });
+    if (bad && myk > 0) atomicOr(err_flag, 1);
+    static_for<0, K>([&](auto cc) {  // L w = y
+        constexpr int c = decltype(cc)::value;
+        if (c < kmax) {
+            const float wc = group_bcast<GW, c>(yv) * group_bcast<GW, c>(myrinv);
+            yv = myrow > c ? yv - s[c] * wc : (myrow == c ? wc : yv);
         }
-    }
-    // L^T t = w: lane i needs column i of L, read back transposed through LDS
+    });
+    {
+        float4 *row = (float4 *)(sb + (grp * K + myrow) * KP);
 #pragma unroll
-    for (int c = 0; c < K; ++c) sbuf[myrow * KP + c] = s[c];
+        for (int c4 = 0; c4 < K / 4; ++c4) row[c4] = make_float4(s[4 * c4], s[4 * c4 + 1], s[4 * c4 + 2], s[4 * c4 + 3]);
+    }
     wave_sync();
-#pragma unroll
-    for (int c = K - 1; c >= 0; --c) {
-        if (c < k) {
-            const float tc = readlane_f(yv, c) * readlane_f(myrinv, c);
-            const float lt = sbuf[c * KP + myrow];  // L[c][lane], meaningful for lane <= c
-            yv = lane < c ? yv - lt * tc : (lane == c ? tc : yv);
+    static_for<0, K>([&](auto cc) {  // L^T t = w
+        constexpr int c = K - 1 - decltype(cc)::value;
+        if (c < kmax) {
+            const float tc = group_bcast<GW, c>(yv) * group_bcast<GW, c>(myrinv);
+            const float lt = sb[(grp * K + c) * KP + myrow];  // L[c][myrow], meaningful for myrow <= c
+            yv = myrow < c ? yv - lt * tc : (myrow == c ? tc : yv);
         }
-    }
-    // r = Z_I^T t: scale this lane's pieces by t_e, add over the tiles, then over the 16 lanes a
-    float4 rp[NJ];
+    });
+
+    // ---- 3. r = Z_I^T t
+    if constexpr (C::ZBUF) {
+        constexpr int CPL = D >= 128 ? 2 : 1;  // output columns per lane
+        tb[lane] = yv;                         // K <= 32: lane == grp*K + row
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) rp[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int p = 0; p < RPW; ++p) {
+            wave_sync();  // zb aliases sb and the previous row's copy: all reads of those are done
 #pragma unroll
-    for (int t = 0; t < KT; ++t) {
-        const float te = __shfl(yv, 16 * t + a);
+            for (int t = 0; t < KT; ++t)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) *(float4 *)(zb + (16 * t + a) * ZLD + (4 * j + q) * 4) = z[p][t][j];
+            wave_sync();
+            if (u[p] >= 0 && lane * CPL < D) {
+                float r0v = 0.f, r1v = 0.f;
+                for (int e = 0; e < k[p]; ++e) {
+                    const float te = tb[p * K + e];
+                    if constexpr (CPL == 2) {
+                        const float2 zz = *(const float2 *)(zb + e * ZLD + 2 * lane);
+                        r0v += te * zz.x;
+                        r1v += te * zz.y;
+                    } else {
+                        r0v += te * zb[e * ZLD + lane];
+                    }
+                }
+                if constexpr (CPL == 2) *(float2 *)(R + u[p] * ldr + 2 * lane) = make_float2(r0v, r1v);
+                else R[u[p] * ldr + lane] = r0v;
+            }
+        }
+    } else {
+        // scale this lane's pieces by t_e, add over the tiles, then over the 16 lanes a of each q
+        float4 rp[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) rp[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int t = 0; t < KT; ++t) {
+            const float te = __shfl(yv, 16 * t + a);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                rp[j].x += te * z[0][t][j].x; rp[j].y += te * z[0][t][j].y;
+                rp[j].z += te * z[0][t][j].z; rp[j].w += te * z[0][t][j].w;
+            }
+        }
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
-            rp[j].x += te * z[t][j].x; rp[j].y += te * z[t][j].y;
-            rp[j].z += te * z[t][j].z; rp[j].w += te * z[t][j].w;
+            float4 v = rp[j];
+            v.x = add_row_ror<8>(v.x); v.y = add_row_ror<8>(v.y); v.z = add_row_ror<8>(v.z); v.w = add_row_ror<8>(v.w);
+            v.x = add_row_ror<4>(v.x); v.y = add_row_ror<4>(v.y); v.z = add_row_ror<4>(v.z); v.w = add_row_ror<4>(v.w);
+            v.x = add_row_ror<2>(v.x); v.y = add_row_ror<2>(v.y); v.z = add_row_ror<2>(v.z); v.w = add_row_ror<2>(v.w);
+            v.x = add_row_ror<1>(v.x); v.y = add_row_ror<1>(v.y); v.z = add_row_ror<1>(v.z); v.w = add_row_ror<1>(v.w);
+            if (a == j && u[0] >= 0) *(float4 *)(R + u[0] * ldr + (4 * j + q) * 4) = v;
         }
     }
-    float4 out = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+// ---------------------------------------------------------------------------------------------- dual rows, 64 < k <= 128
+// One workgroup of KT wavefronts per row (k <= K = 16*KT).  Wavefront w owns rows R = 16w + a of S;
+// lane (a, q) keeps S[R][c] for the columns c = 16*t2 + 4q + v (t2 <= w, v < 4) in acc[t2][v], which
+// is exactly where v_mfma_f32_16x16x4 leaves them when tile t2 is the A operand and the wavefront's
+// own tile the B operand (S is symmetric), so S never moves between the MFMA and the factorisation.
+//   1. every wavefront gathers its 16 entries into registers and into LDS; S tiles from LDS (A) and
+//      registers (B);
+//   2. right-looking elimination S = M D M^T (M unit lower, D the pivots), one column per step: the
+//      owners publish the column in LDS, one workgroup barrier, everybody updates; the forward
+//      substitution u = M^{-1} y rides along;
+//   3. M^T t = D^{-1} u column by column with one thread per unknown (factor read back transposed
+//      from LDS);
+//   4. r = Z_I^T t: per wavefront a cross-lane reduction of its 16 entries, then a sum over wavefronts.
+template <int D, int KT> struct BigCfg {
+    static constexpr int K = 16 * KT, ZLD = D + 4, MLD = K + 1;
+    static constexpr int MAIN = K * ZLD > K * MLD ? K * ZLD : K * MLD;  // zb, later the transposed factor
+    static constexpr int OFF_COL = MAIN;                                // colbuf[2][K]
+    static constexpr int OFF_Y = OFF_COL + 2 * K;                       // ybuf[4]
+    static constexpr int OFF_U = OFF_Y + 4;                             // ubuf[K]
+    static constexpr int OFF_P = OFF_U + K;                             // pbuf[K]
+    static constexpr int OFF_T = OFF_P + K;                             // tbuf[K]
+    static constexpr int OFF_R = OFF_T + K;                             // rbuf[KT][D]
+    static constexpr int LDS_FLOATS = OFF_R + KT * D;
+};
+
+template <int D, int KT>
+__global__ __launch_bounds__(64 * KT) void dual_big_kernel(const int64_t *__restrict__ indptr,
+                                                           const int32_t *__restrict__ indices,
+                                                           const float *__restrict__ values,
+                                                           const float *__restrict__ Z, float *__restrict__ R,
+                                                           int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
+                                                           int32_t *__restrict__ err_flag) {
+    using C = BigCfg<D, KT>;
+    constexpr int K = C::K, NJ = D / 16, ZLD = C::ZLD, MLD = C::MLD;
+    extern __shared__ float lds[];
+    float *zb = lds, *mb = lds, *colbuf = lds + C::OFF_COL, *ybuf = lds + C::OFF_Y, *ubuf = lds + C::OFF_U,
+          *pbuf = lds + C::OFF_P, *tbuf = lds + C::OFF_T, *rbuf = lds + C::OFF_R;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int a = lane & 15, q = lane >> 4;
+    const int myR = 16 * w + a;
+    const int64_t u = r0 + list[blockIdx.x];
+    const int64_t b = indptr[u];
+    const int k = (int)(indptr[u + 1] - b);  // <= K by the list's class
+
+    // ---- 1. gather, S rows
+    float4 z[NJ];
+    {
+        const int64_t idx = myR < k ? (int64_t)indices[b + myR] : -1;
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-        float4 v = rp[j];
-        v.x = add_row_ror<8>(v.x); v.y = add_row_ror<8>(v.y); v.z = add_row_ror<8>(v.z); v.w = add_row_ror<8>(v.w);
-        v.x = add_row_ror<4>(v.x); v.y = add_row_ror<4>(v.y); v.z = add_row_ror<4>(v.z); v.w = add_row_ror<4>(v.w);
-        v.x = add_row_ror<2>(v.x); v.y = add_row_ror<2>(v.y); v.z = add_row_ror<2>(v.z); v.w = add_row_ror<2>(v.w);
-        v.x = add_row_ror<1>(v.x); v.y = add_row_ror<1>(v.y); v.z = add_row_ror<1>(v.z); v.w = add_row_ror<1>(v.w);
-        out = (a == j) ? v : out;
+        for (int j = 0; j < NJ; ++j) {
+            z[j] = idx >= 0 ? *(const float4 *)(Z + idx * D + (4 * j + q) * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+            *(float4 *)(zb + myR * ZLD + (4 * j + q) * 4) = z[j];
+        }
     }
-    if (a < NJ) *(float4 *)(R + u * ldr + (4 * a + q) * 4) = out;
+    float yv = 0.f;  // every lane of row R carries y_R, later u_R
+    if (myR < k) yv = values ? values[b + myR] : 1.f;
+    __syncthreads();
+    floatx4 acc[KT];
+#pragma unroll
+    for (int t2 = 0; t2 < KT; ++t2) {
+        acc[t2] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (t2 <= w) {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const float4 za = *(const float4 *)(zb + (16 * t2 + a) * ZLD + (4 * j + q) * 4);
+                acc[t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(za.x, z[j].x, acc[t2], 0, 0, 0);
+                acc[t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(za.y, z[j].y, acc[t2], 0, 0, 0);
+                acc[t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(za.z, z[j].z, acc[t2], 0, 0, 0);
+                acc[t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(za.w, z[j].w, acc[t2], 0, 0, 0);
+            }
+            if (t2 == w) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[t2][v] += (4 * q + v == a) ? 1.f : 0.f;  // S = I + Z Z^T
+            }
+        }
+    }
+    __syncthreads();  // zb is dead from here on (its space becomes mb in step 3)
+
+    // ---- 2. elimination with the forward substitution riding along
+    float mypiv = 1.f;
+    bool bad = false;
+    static_for<0, K>([&](auto cc) {
+        constexpr int c = decltype(cc)::value;
+        constexpr int tc = c / 16, qc = (c % 16) / 4, vc = c % 4;
+        if (c < k) {  // the remaining rows are identity rows with zero right-hand side
+            float *buf = colbuf + (c & 1) * K;
+            if (w >= tc) {
+                if (q == qc) buf[myR] = acc[tc][vc];  // S'[R][c] as it stands (column c is final)
+                if (myR == c && q == qc) ybuf[c & 1] = yv;
+            }
+            __syncthreads();
+            if (w >= tc) {
+                const float pivot = buf[c];
+                const float uc = ybuf[c & 1];
+                bad |= !(pivot > 0.f);
+                float rp = __builtin_amdgcn_rcpf(pivot);
+                rp = rp * (2.f - pivot * rp);  // one Newton step on the hardware reciprocal
+                mypiv = myR == c ? pivot : mypiv;
+                const float f = myR > c ? buf[myR] * rp : 0.f;  // M[R][c]; rows above stay as they are
+                yv -= f * uc;
+#pragma unroll
+                for (int t2 = tc; t2 < KT; ++t2) {
+                    if (t2 <= w) {
+                        const float4 col = *(const float4 *)(buf + 16 * t2 + 4 * q);
+                        if (t2 == tc) {  // same tile as column c: only columns right of c change
+                            if (4 * q + 0 > 4 * qc + vc) acc[t2][0] -= f * col.x;
+                            if (4 * q + 1 > 4 * qc + vc) acc[t2][1] -= f * col.y;
+                            if (4 * q + 2 > 4 * qc + vc) acc[t2][2] -= f * col.z;
+                            if (4 * q + 3 > 4 * qc + vc) acc[t2][3] -= f * col.w;
+                        } else {
+                            acc[t2][0] -= f * col.x; acc[t2][1] -= f * col.y;
+                            acc[t2][2] -= f * col.z; acc[t2][3] -= f * col.w;
+                        }
+                    }
+                }
+            }
+        }
+    });
+    if (bad && tid == 0) atomicOr(err_flag, 1);
+
+    // ---- 3. back substitution: t_c = (u_c - sum_{R>c} S'[R][c] t_R) / pivot_c, one thread per c
+#pragma unroll
+    for (int t2 = 0; t2 < KT; ++t2) {
+        if (t2 <= w) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) mb[myR * MLD + 16 * t2 + 4 * q + v] = acc[t2][v];
+        }
+    }
+    if (q == 0) {
+        ubuf[myR] = yv;
+        pbuf[myR] = mypiv;
+    }
+    __syncthreads();
+    {
+        float accv = 0.f, rpiv = 0.f;
+        if (tid < K) {
+            accv = ubuf[tid];
+            rpiv = 1.0f / pbuf[tid];
+            if (tid >= k) tbuf[tid] = 0.f;
+        }
+        for (int Rr = k - 1; Rr >= 0; --Rr) {
+            if (tid == Rr) tbuf[Rr] = accv * rpiv;
+            __syncthreads();
+            if (tid < Rr) accv -= mb[Rr * MLD + tid] * tbuf[Rr];
+        }
+    }
+    __syncthreads();
+
+    // ---- 4. r = Z_I^T t
+    {
+        const float te = tbuf[myR];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            float4 v = make_float4(te * z[j].x, te * z[j].y, te * z[j].z, te * z[j].w);
+            v.x = add_row_ror<8>(v.x); v.y = add_row_ror<8>(v.y); v.z = add_row_ror<8>(v.z); v.w = add_row_ror<8>(v.w);
+            v.x = add_row_ror<4>(v.x); v.y = add_row_ror<4>(v.y); v.z = add_row_ror<4>(v.z); v.w = add_row_ror<4>(v.w);
+            v.x = add_row_ror<2>(v.x); v.y = add_row_ror<2>(v.y); v.z = add_row_ror<2>(v.z); v.w = add_row_ror<2>(v.w);
+            v.x = add_row_ror<1>(v.x); v.y = add_row_ror<1>(v.y); v.z = add_row_ror<1>(v.z); v.w = add_row_ror<1>(v.w);
+            if (a == j) *(float4 *)(rbuf + w * D + (4 * j + q) * 4) = v;
+        }
+    }
+    __syncthreads();
+    if (tid < D) {
+        float r = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < KT; ++ww) r += rbuf[ww * D + tid];
+        R[u * ldr + tid] = r;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------- launchers
-int dual_supported_max_k(int d) { return d < 64 ? d : 64; }
+int dual_supported_max_k(int d) { return d < 128 ? (d < 64 ? d : 64) : 128; }
 
-template <int D, int KT>
-static void launch_dual_class(const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, int64_t r1,
-                              int dual_max, hipStream_t s) {
-    const int k_lo = 16 * (KT - 1), k_hi = std::min(16 * KT, dual_max);
-    if (k_hi <= k_lo) return;
-    constexpr size_t lds = 4 * (16 * KT) * (16 * KT + 1) * sizeof(float);
-    const unsigned blocks = (unsigned)((r1 - r0 + 3) / 4);
-    hipLaunchKernelGGL((dual_wave_kernel<D, KT>), dim3(blocks), dim3(256), lds, s, Y->indptr, Y->indices, Y->values, Z,
-                       R, ldr, r0, r1, k_lo, k_hi);
+template <int D, int K>
+static void launch_dual_class(const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0,
+                              const int32_t *list, int count, int32_t *err, hipStream_t s) {
+    if (count <= 0) return;
+    using C = DualCfg<D, K>;
+    const unsigned blocks = (unsigned)((count + C::RPW - 1) / C::RPW);
+    hipLaunchKernelGGL((dual_rows_kernel<D, K>), dim3(blocks), dim3(64), C::LDS_FLOATS * sizeof(float), s, Y->indptr,
+                       Y->indices, Y->values, Z, R, ldr, r0, list, count, err);
 }
 
+// Part 1 (needs no row classification): factorise B and build Z = V L^{-T}.
 template <int D, bool BF16>
-static als_status dual_typed(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
-                             const als_params *prm, als_table *X, int64_t r0, int64_t r1, int dual_max,
-                             hipStream_t s) {
+static als_status dual_prepare_typed(als_ctx *ctx, const als_table *V, const float *G, const als_params *prm,
+                                     hipStream_t s) {
     als_status st = ensure(ctx, ctx->ztable, (size_t)V->rows * D * sizeof(float));
     if (st != ALS_OK) return st;
-    float *R = (float *)X->data;
-    int64_t ldr = X->ld;
-    if (BF16) {
-        st = ensure(ctx, ctx->rtable, (size_t)(r1 - r0) * D * sizeof(float));
-        if (st != ALS_OK) return st;
-        R = (float *)ctx->rtable.p - r0 * D;  // row u lives at rtable[(u - r0) * D]
-        ldr = D;
-    }
     float *Linv = (float *)((char *)ctx->small.p + SM_FACTOR), *LinvT = Linv + 128 * 128;
     int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
-    float *Z = (float *)ctx->ztable.p;
     constexpr size_t factor_lds = (size_t)(D * (D + 1) + D) * sizeof(double);
     ALS_HIP(ctx, hipFuncSetAttribute((const void *)factor_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)factor_lds));
@@ -300,32 +569,91 @@ static als_status dual_typed(als_ctx *ctx, const als_csr *Y, const als_table *V,
     hipLaunchKernelGGL(factor_kernel<D>, dim3(1), dim3(256), factor_lds, s, G, prm->alpha, prm->lambda, Linv, LinvT,
                        err);
     const unsigned tblocks = (unsigned)std::min<int64_t>(2048, std::max<int64_t>(1, (V->rows + 63) / 64));
-    hipLaunchKernelGGL((transform_kernel<D, BF16, false>), dim3(tblocks), dim3(256), 0, s, V->data, V->ld, (void *)Z,
-                       (int64_t)D, (const float *)LinvT, (int64_t)0, V->rows);
-    timer_end(ctx, s);
-    timer_begin(ctx, T_DUAL, s);
-    launch_dual_class<D, 1>(Y, Z, R, ldr, r0, r1, dual_max, s);
-    launch_dual_class<D, 2>(Y, Z, R, ldr, r0, r1, dual_max, s);
-    launch_dual_class<D, 3>(Y, Z, R, ldr, r0, r1, dual_max, s);
-    launch_dual_class<D, 4>(Y, Z, R, ldr, r0, r1, dual_max, s);
-    timer_end(ctx, s);
-    timer_begin(ctx, T_TRANSFORM, s);
-    const unsigned xblocks = (unsigned)std::min<int64_t>(2048, std::max<int64_t>(1, (r1 - r0 + 63) / 64));
-    hipLaunchKernelGGL((transform_kernel<D, false, BF16>), dim3(xblocks), dim3(256), 0, s, (const void *)R, ldr,
-                       X->data, X->ld, (const float *)Linv, r0, r1);
+    hipLaunchKernelGGL((transform_kernel<D, BF16, false>), dim3(tblocks), dim3(256), 0, s, V->data, V->ld,
+                       ctx->ztable.p, (int64_t)D, (const float *)LinvT, (int64_t)0, V->rows,
+                       (const int64_t *)nullptr, (int64_t)0);
     timer_end(ctx, s);
     ALS_HIP(ctx, hipGetLastError());
     return ALS_OK;
 }
 
-als_status launch_dual(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G, const als_params *prm,
-                       als_table *X, int64_t r0, int64_t r1, int dual_max, hipStream_t s) {
+// Part 2: the row kernels of the four k-classes, then X = R L^{-1} on the rows they solved.
+template <int D, int KT>
+static als_status launch_big_class(als_ctx *ctx, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0,
+                                   const int32_t *list, int count, int32_t *err, hipStream_t s) {
+    if (count <= 0) return ALS_OK;
+    if constexpr (D == 128) {
+        using C = BigCfg<D, KT>;
+        auto kern = dual_big_kernel<D, KT>;
+        ALS_HIP(ctx, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)(C::LDS_FLOATS * sizeof(float))));
+        hipLaunchKernelGGL(kern, dim3((unsigned)count), dim3(64 * KT), C::LDS_FLOATS * sizeof(float), s, Y->indptr,
+                           Y->indices, Y->values, Z, R, ldr, r0, list, err);
+        return ALS_OK;
+    } else {
+        return fail(ctx, ALS_EINVAL, "rows with more than 64 entries take the dual form only for d = 128");
+    }
+}
+
+template <int D, bool BF16>
+static als_status dual_rows_typed(als_ctx *ctx, const als_csr *Y, als_table *X, int64_t r0, int64_t r1,
+                                  int dual_max, const int32_t *const lists[8], const int counts[8], hipStream_t s) {
+    float *R = (float *)X->data;
+    int64_t ldr = X->ld;
+    if (BF16) {
+        als_status st = ensure(ctx, ctx->rtable, (size_t)(r1 - r0) * D * sizeof(float));
+        if (st != ALS_OK) return st;
+        R = (float *)ctx->rtable.p - r0 * D;  // row u lives at rtable[(u - r0) * D]
+        ldr = D;
+    }
+    const float *Linv = (const float *)((char *)ctx->small.p + SM_FACTOR);
+    int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
+    const float *Z = (const float *)ctx->ztable.p;
+    auto k1 = dual_rows_kernel<D, 16>;
+    auto k2 = dual_rows_kernel<D, 32>;
+    auto k3 = dual_rows_kernel<D, 48>;
+    auto k4 = dual_rows_kernel<D, 64>;
+    (void)k1; (void)k2; (void)k3; (void)k4;
+    timer_begin(ctx, T_DUAL, s);
+    launch_dual_class<D, 16>(Y, Z, R, ldr, r0, lists[0], counts[0], err, s);
+    launch_dual_class<D, 32>(Y, Z, R, ldr, r0, lists[1], counts[1], err, s);
+    launch_dual_class<D, 48>(Y, Z, R, ldr, r0, lists[2], counts[2], err, s);
+    launch_dual_class<D, 64>(Y, Z, R, ldr, r0, lists[3], counts[3], err, s);
+    als_status stb = launch_big_class<D, 5>(ctx, Y, Z, R, ldr, r0, lists[4], counts[4], err, s);
+    if (stb == ALS_OK) stb = launch_big_class<D, 6>(ctx, Y, Z, R, ldr, r0, lists[5], counts[5], err, s);
+    if (stb == ALS_OK) stb = launch_big_class<D, 7>(ctx, Y, Z, R, ldr, r0, lists[6], counts[6], err, s);
+    if (stb == ALS_OK) stb = launch_big_class<D, 8>(ctx, Y, Z, R, ldr, r0, lists[7], counts[7], err, s);
+    timer_end(ctx, s);
+    if (stb != ALS_OK) return stb;
+    timer_begin(ctx, T_TRANSFORM, s);
+    const unsigned xblocks = (unsigned)std::min<int64_t>(2048, std::max<int64_t>(1, (r1 - r0 + 63) / 64));
+    hipLaunchKernelGGL((transform_kernel<D, false, BF16>), dim3(xblocks), dim3(256), 0, s, (const void *)R, ldr,
+                       X->data, X->ld, Linv, r0, r1, Y->indptr, (int64_t)dual_max);
+    timer_end(ctx, s);
+    ALS_HIP(ctx, hipGetLastError());
+    return ALS_OK;
+}
+
+als_status launch_dual_prepare(als_ctx *ctx, const als_table *V, const float *G, const als_params *prm,
+                               hipStream_t s) {
     const bool bf = V->dtype == ALS_BF16;
     switch (V->d) {
-        case 16: return bf ? dual_typed<16, true>(ctx, Y, V, G, prm, X, r0, r1, dual_max, s) : dual_typed<16, false>(ctx, Y, V, G, prm, X, r0, r1, dual_max, s);
-        case 32: return bf ? dual_typed<32, true>(ctx, Y, V, G, prm, X, r0, r1, dual_max, s) : dual_typed<32, false>(ctx, Y, V, G, prm, X, r0, r1, dual_max, s);
-        case 64: return bf ? dual_typed<64, true>(ctx, Y, V, G, prm, X, r0, r1, dual_max, s) : dual_typed<64, false>(ctx, Y, V, G, prm, X, r0, r1, dual_max, s);
-        case 128: return bf ? dual_typed<128, true>(ctx, Y, V, G, prm, X, r0, r1, dual_max, s) : dual_typed<128, false>(ctx, Y, V, G, prm, X, r0, r1, dual_max, s);
+        case 16: return bf ? dual_prepare_typed<16, true>(ctx, V, G, prm, s) : dual_prepare_typed<16, false>(ctx, V, G, prm, s);
+        case 32: return bf ? dual_prepare_typed<32, true>(ctx, V, G, prm, s) : dual_prepare_typed<32, false>(ctx, V, G, prm, s);
+        case 64: return bf ? dual_prepare_typed<64, true>(ctx, V, G, prm, s) : dual_prepare_typed<64, false>(ctx, V, G, prm, s);
+        case 128: return bf ? dual_prepare_typed<128, true>(ctx, V, G, prm, s) : dual_prepare_typed<128, false>(ctx, V, G, prm, s);
+    }
+    return fail(ctx, ALS_EDTYPE, "unsupported d");
+}
+
+als_status launch_dual_rows(als_ctx *ctx, const als_csr *Y, als_table *X, int64_t r0, int64_t r1, int dual_max,
+                            const int32_t *const lists[8], const int counts[8], hipStream_t s) {
+    const bool bf = X->dtype == ALS_BF16;
+    switch (X->d) {
+        case 16: return bf ? dual_rows_typed<16, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, s) : dual_rows_typed<16, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, s);
+        case 32: return bf ? dual_rows_typed<32, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, s) : dual_rows_typed<32, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, s);
+        case 64: return bf ? dual_rows_typed<64, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, s) : dual_rows_typed<64, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, s);
+        case 128: return bf ? dual_rows_typed<128, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, s) : dual_rows_typed<128, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, s);
     }
     return fail(ctx, ALS_EDTYPE, "unsupported d");
 }

@@ -35,7 +35,7 @@ __device__ __forceinline__ void accumulate_entries(const void *__restrict__ V, i
                                                    int I, typename AccT<Geo<D>::ACC>::type (&acc)[Geo<D>::NC],
                                                    float (&bsum)[Geo<D>::NC]) {
     using G = Geo<D>;
-    constexpr int NC = G::NC, TM = G::TM, KS = G::KS, U = 4;
+    constexpr int NC = G::NC, TM = G::TM, KS = G::KS, U = 8;
     const int lane = threadIdx.x & 63;
     const int m = lane % TM, kk = lane / TM;
     for (int64_t base = begin; base < end; base += 64) {
@@ -127,16 +127,15 @@ __device__ __forceinline__ void cholesky_solve_lds(float *a, float *aux, int32_t
 // ---------------------------------------------------------------------------------------------- kernels
 enum PrimalMode { MODE_FUSED = 0, MODE_SEGMENT = 1 };
 
-// MODE_FUSED:   work item = a whole row u (u = row_list ? row_list[item] : row_begin + item);
-//               rows with k_lo < k <= k_hi entries are solved, others skipped.
+// MODE_FUSED:   work item = the whole row u = row_begin + row_list[item].
 // MODE_SEGMENT: work item = segment `item` of segs[]; raw partial statistics are written to
 //               partials[item][D*D + D] (row-major D x D, then b).
 template <int D, bool BF16, int MODE>
 __global__ __launch_bounds__(Team<D>::THREADS) void primal_kernel(
     const int64_t *__restrict__ indptr, const int32_t *__restrict__ indices, const float *__restrict__ values,
     const void *__restrict__ V, int64_t ldv, const float *__restrict__ G, float alpha, float lambda,
-    void *__restrict__ X, int64_t ldx, int64_t row_begin, const int64_t *__restrict__ row_list,
-    int64_t k_lo, int64_t k_hi, const Segment *__restrict__ segs, float *__restrict__ partials,
+    void *__restrict__ X, int64_t ldx, int64_t row_begin, const int32_t *__restrict__ row_list,
+    const Segment *__restrict__ segs, float *__restrict__ partials,
     int32_t *__restrict__ err_flag) {
     using GE = Geo<D>;
     constexpr int NC = GE::NC, TM = GE::TM, ACC = GE::ACC, LD = Team<D>::LD;
@@ -149,11 +148,9 @@ __global__ __launch_bounds__(Team<D>::THREADS) void primal_kernel(
     const int64_t item = blockIdx.x;
     int64_t u = 0, begin, end;
     if constexpr (MODE == MODE_FUSED) {
-        u = row_list ? row_list[item] : row_begin + item;
+        u = row_begin + row_list[item];
         begin = indptr[u];
         end = indptr[u + 1];
-        const int64_t k = end - begin;
-        if (k <= k_lo || k > k_hi) return;  // k_lo >= 0: empty rows are zeroed by the row classifier
     } else {
         begin = segs[item].begin;
         end = segs[item].end;
@@ -204,7 +201,28 @@ __global__ __launch_bounds__(Team<D>::THREADS) void primal_kernel(
     }
 }
 
-// Sums the segment partials of one long row (fixed order), adds alpha*G + lambda*I, solves, stores.
+// Adds the segment partials of every long row in a fixed order: workgroup (x, y) handles elements
+// [256y, 256y+256) of long row x and overwrites the row's first partial with the sum.
+template <int D>
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const LongRow *__restrict__ long_rows,
+                                                              float *__restrict__ partials) {
+    const LongRow lr = long_rows[blockIdx.x];
+    const int e = blockIdx.y * 256 + threadIdx.x;
+    if (e >= D * D + D || lr.nseg <= 1) return;
+    float *p0 = partials + (int64_t)lr.seg_first * (D * D + D) + e;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    int g = 0;
+    for (; g + 4 <= lr.nseg; g += 4) {
+        s0 += p0[(int64_t)(g + 0) * (D * D + D)];
+        s1 += p0[(int64_t)(g + 1) * (D * D + D)];
+        s2 += p0[(int64_t)(g + 2) * (D * D + D)];
+        s3 += p0[(int64_t)(g + 3) * (D * D + D)];
+    }
+    for (; g < lr.nseg; ++g) s0 += p0[(int64_t)g * (D * D + D)];
+    p0[0] = (s0 + s1) + (s2 + s3);
+}
+
+// Loads the summed statistics of one long row, adds alpha*G + lambda*I, solves, stores.
 template <int D, bool BF16>
 __global__ __launch_bounds__(Team<D>::THREADS) void reduce_solve_kernel(
     const LongRow *__restrict__ long_rows, const float *__restrict__ partials, const float *__restrict__ G,
@@ -215,8 +233,7 @@ __global__ __launch_bounds__(Team<D>::THREADS) void reduce_solve_kernel(
     const LongRow lr = long_rows[blockIdx.x];
     const float *p0 = partials + (int64_t)lr.seg_first * (D * D + D);
     for (int e = threadIdx.x; e < D * D + D; e += T) {
-        float s = 0.f;
-        for (int g = 0; g < lr.nseg; ++g) s += p0[(int64_t)g * (D * D + D) + e];
+        const float s = p0[e];
         if (e < D * D) {
             const int r = e / D, c = e % D;
             a[c * LD + r] = s + alpha * G[e] + (r == c ? lambda : 0.f);
@@ -233,8 +250,8 @@ __global__ __launch_bounds__(Team<D>::THREADS) void reduce_solve_kernel(
 // ---------------------------------------------------------------------------------------------- launchers
 template <int D, bool BF16>
 static als_status primal_typed(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
-                               const als_params *prm, als_table *X, int64_t r0, const int64_t *row_list,
-                               int64_t nitems, int64_t k_lo, int64_t k_hi, hipStream_t s) {
+                               const als_params *prm, als_table *X, int64_t r0, const int32_t *row_list,
+                               int64_t nitems, hipStream_t s) {
     if (nitems <= 0) return ALS_OK;
     int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
     auto kern = primal_kernel<D, BF16, MODE_FUSED>;
@@ -243,7 +260,7 @@ static als_status primal_typed(als_ctx *ctx, const als_csr *Y, const als_table *
     timer_begin(ctx, T_PRIMAL, s);
     hipLaunchKernelGGL(kern, dim3((unsigned)nitems), dim3(Team<D>::THREADS), Team<D>::LDS_BYTES, s, Y->indptr,
                        Y->indices, Y->values, V->data, V->ld, G, prm->alpha, prm->lambda, X->data, X->ld, r0,
-                       row_list, k_lo, k_hi, (const Segment *)nullptr, (float *)nullptr, err);
+                       row_list, (const Segment *)nullptr, (float *)nullptr, err);
     timer_end(ctx, s);
     ALS_HIP(ctx, hipGetLastError());
     return ALS_OK;
@@ -264,9 +281,11 @@ static als_status long_typed(als_ctx *ctx, const als_csr *Y, const als_table *V,
     timer_begin(ctx, T_SEGMENT, s);
     hipLaunchKernelGGL(kseg, dim3((unsigned)n_seg), dim3(Team<D>::THREADS), 0, s, Y->indptr, Y->indices, Y->values,
                        V->data, V->ld, G, prm->alpha, prm->lambda, X->data, X->ld, (int64_t)0,
-                       (const int64_t *)nullptr, (int64_t)0, (int64_t)0, segs, (float *)ctx->seg_partials.p, err);
+                       (const int32_t *)nullptr, segs, (float *)ctx->seg_partials.p, err);
     timer_end(ctx, s);
     timer_begin(ctx, T_REDUCE, s);
+    hipLaunchKernelGGL(reduce_partials_kernel<D>, dim3((unsigned)n_long, (D * D + D + 255) / 256), dim3(256), 0, s,
+                       long_rows, (float *)ctx->seg_partials.p);
     hipLaunchKernelGGL(kred, dim3((unsigned)n_long), dim3(Team<D>::THREADS), Team<D>::LDS_BYTES, s, long_rows,
                        (const float *)ctx->seg_partials.p, G, prm->alpha, prm->lambda, X->data, X->ld, err);
     timer_end(ctx, s);
@@ -284,10 +303,10 @@ static als_status long_typed(als_ctx *ctx, const als_csr *Y, const als_table *V,
     return fail(ctx, ALS_EDTYPE, "unsupported d")
 
 als_status launch_primal_fused(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
-                               const als_params *prm, als_table *X, int64_t r0, const int64_t *row_list,
-                               int64_t nitems, int64_t k_lo, int64_t k_hi, hipStream_t s) {
+                               const als_params *prm, als_table *X, int64_t r0, const int32_t *row_list,
+                               int64_t nitems, hipStream_t s) {
     const bool bf = V->dtype == ALS_BF16;
-    ALS_DISPATCH(primal_typed, V->d, bf, ctx, Y, V, G, prm, X, r0, row_list, nitems, k_lo, k_hi, s);
+    ALS_DISPATCH(primal_typed, V->d, bf, ctx, Y, V, G, prm, X, r0, row_list, nitems, s);
 }
 
 als_status launch_primal_long(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,

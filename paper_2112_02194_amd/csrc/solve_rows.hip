@@ -6,59 +6,93 @@
 namespace als {
 
 als_status launch_primal_fused(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
-                               const als_params *prm, als_table *X, int64_t r0, const int64_t *row_list,
-                               int64_t nitems, int64_t k_lo, int64_t k_hi, hipStream_t s);
+                               const als_params *prm, als_table *X, int64_t r0, const int32_t *row_list,
+                               int64_t nitems, hipStream_t s);
 als_status launch_primal_long(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
                               const als_params *prm, als_table *X, const LongRow *long_rows, int n_long,
                               const Segment *segs, int n_seg, hipStream_t s);
-als_status launch_dual(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G, const als_params *prm,
-                       als_table *X, int64_t r0, int64_t r1, int dual_max_k, hipStream_t s);
+als_status launch_dual_prepare(als_ctx *ctx, const als_table *V, const float *G, const als_params *prm,
+                               hipStream_t s);
+als_status launch_dual_rows(als_ctx *ctx, const als_csr *Y, als_table *X, int64_t r0, int64_t r1, int dual_max,
+                            const int32_t *const lists[8], const int counts[8], hipStream_t s);
 int dual_supported_max_k(int d);
 
-constexpr int DEFAULT_SPLIT = 2048;
+constexpr int DEFAULT_SPLIT = 512;
 
 __global__ void clear_counters_kernel(int32_t *counters) {
-    if (threadIdx.x < 2) counters[threadIdx.x] = 0;
-    if (threadIdx.x == 3) counters[3] = 0;
+    const int t = threadIdx.x;
+    if (t < 16 && t != 2 && t != 4) counters[t] = 0;  // [2] is the sticky error flag, [4] the CSR check flag
 }
 
-// One thread per row of [r0, r1): empty rows get X[u] = 0; rows with k > split become a long row
-// with ceil(k/split) balanced segments; rows with mid_lo < k <= split are appended to mid_list.
+constexpr int CLS_THREADS = 256, CLS_RPT = 8, CLS_ROWS = CLS_THREADS * CLS_RPT;  // rows per workgroup
+constexpr int MAX_SEGS_PER_ROW = 128;
+struct ListOffsets { int64_t v[8]; };  // start of each dual class list, passed by value
+
+// One workgroup per CLS_ROWS consecutive rows of [r0, r1):
+//   k = 0               X[u] = 0
+//   0 < k <= dual_max   appended to the dual list of its class ceil(k/16) in 1..8 (row id relative to r0)
+//   dual_max < k <= split  appended to the mid list (primal, one workgroup per row)
+//   k > split           becomes a long row cut into balanced segments of about `split` entries
+//                       (at most MAX_SEGS_PER_ROW of them)
+// List positions are reserved with one atomic per workgroup and list (counts gathered in LDS), and
+// rows keep their order inside a workgroup's slice.
 template <bool BF16>
-__global__ __launch_bounds__(256) void classify_kernel(const int64_t *__restrict__ indptr, int64_t r0, int64_t r1,
-                                                       int64_t split, int64_t mid_lo, int d, void *__restrict__ X,
-                                                       int64_t ldx, int32_t *__restrict__ counters,
-                                                       LongRow *__restrict__ long_rows, Segment *__restrict__ segs,
-                                                       int64_t *__restrict__ mid_list) {
-    const int64_t u = r0 + (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (u >= r1) return;
-    const int64_t b = indptr[u], e = indptr[u + 1], k = e - b;
-    if (k <= 0) {
-        for (int c = 0; c < d; ++c) store_elem<BF16>(X, u * ldx + c, 0.f);
-        return;
-    }
-    if (k > split) {
-        const int nseg = (int)((k + split - 1) / split);
-        const int64_t len = (k + nseg - 1) / nseg;
-        const int slot = atomicAdd(&counters[0], 1);
-        const int first = atomicAdd(&counters[1], nseg);
-        long_rows[slot].row = u;
-        long_rows[slot].seg_first = first;
-        long_rows[slot].nseg = nseg;
-        for (int g = 0; g < nseg; ++g) {
-            segs[first + g].begin = b + g * len;
-            const int64_t stop = b + (g + 1) * len;
-            segs[first + g].end = stop < e ? stop : e;
+__global__ __launch_bounds__(CLS_THREADS) void classify_kernel(
+    const int64_t *__restrict__ indptr, int64_t r0, int64_t r1, int64_t split, int64_t dual_max, int d,
+    void *__restrict__ X, int64_t ldx, int32_t *__restrict__ counters, LongRow *__restrict__ long_rows,
+    Segment *__restrict__ segs, int32_t *__restrict__ mid_list, int32_t *__restrict__ dual_lists,
+    ListOffsets list_off) {
+    __shared__ int32_t cnt[9], base[9];
+    const int t = threadIdx.x;
+    if (t < 9) cnt[t] = 0;
+    __syncthreads();
+    const int64_t u0 = r0 + (int64_t)blockIdx.x * CLS_ROWS;
+    int cls[CLS_RPT], pos[CLS_RPT];
+#pragma unroll
+    for (int i = 0; i < CLS_RPT; ++i) {
+        const int64_t u = u0 + (int64_t)i * CLS_THREADS + t;  // coalesced indptr reads
+        cls[i] = -1;
+        pos[i] = 0;
+        if (u < r1) {
+            const int64_t b = indptr[u], e = indptr[u + 1], k = e - b;
+            if (k <= 0) {
+                for (int c = 0; c < d; ++c) store_elem<BF16>(X, u * ldx + c, 0.f);
+            } else if (k > split) {
+                int nseg = (int)((k + split - 1) / split);
+                if (nseg > MAX_SEGS_PER_ROW) nseg = MAX_SEGS_PER_ROW;
+                const int64_t len = (k + nseg - 1) / nseg;
+                const int slot = atomicAdd(&counters[0], 1);
+                const int first = atomicAdd(&counters[1], nseg);
+                long_rows[slot].row = u;
+                long_rows[slot].seg_first = first;
+                long_rows[slot].nseg = nseg;
+                for (int g = 0; g < nseg; ++g) {
+                    const int64_t start = b + g * len, stop = b + (g + 1) * len;
+                    segs[first + g].begin = start < e ? start : e;
+                    segs[first + g].end = stop < e ? stop : e;
+                }
+            } else {
+                cls[i] = k > dual_max ? 0 : (int)((k + 15) / 16);  // 0 = mid list, 1..8 = dual classes
+                pos[i] = atomicAdd(&cnt[cls[i]], 1);
+            }
         }
-    } else if (mid_list && k > mid_lo) {
-        const int slot = atomicAdd(&counters[3], 1);
-        mid_list[slot] = u;
+    }
+    __syncthreads();
+    if (t < 9 && cnt[t] > 0) base[t] = atomicAdd(&counters[t == 0 ? 3 : 8 + t - 1], cnt[t]);
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < CLS_RPT; ++i) {
+        if (cls[i] < 0) continue;
+        const int32_t rel = (int32_t)(u0 + (int64_t)i * CLS_THREADS + t - r0);
+        int32_t *list = cls[i] == 0 ? mid_list : dual_lists + list_off.v[cls[i] - 1];
+        list[base[cls[i]] + pos[i]] = rel;
     }
 }
 
 als_status launch_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
                              const als_params *prm, als_table *X, int64_t r0, int64_t r1, hipStream_t s) {
     const int64_t nrows = r1 - r0;
+    if (nrows > INT32_MAX) return fail(ctx, ALS_EINVAL, "row range longer than 2^31-1: call per sub-range");
     const int64_t split = prm->split_nnz > 0 ? prm->split_nnz : DEFAULT_SPLIT;
     int dual_max = 0;
     if (prm->path != ALS_PATH_PRIMAL) {
@@ -68,46 +102,62 @@ als_status launch_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V,
     }
     // capacities: rows longer than split number at most nnz/split, their segments at most twice that
     const int64_t cap_long = Y->nnz / split + 1, cap_seg = 2 * (Y->nnz / split) + 2;
-    const int64_t cap_mid = dual_max > 0 ? Y->nnz / (dual_max + 1) + 1 : 0;
     if (cap_seg > INT32_MAX) return fail(ctx, ALS_EINVAL, "split_nnz too small for this matrix");
+    // list capacities: class c (k > 16(c-1)) holds at most nnz/(16(c-1)+1) rows, the mid list at most
+    // nnz/(dual_max+1); offsets go to the device through a small table in the context's scratch
+    int64_t off[9];
+    off[0] = 0;
+    for (int c = 1; c <= 8; ++c) {
+        int64_t cap = 0;
+        if (dual_max > 16 * (c - 1)) cap = std::min<int64_t>(nrows, Y->nnz / (16 * (c - 1) + 1) + 1);
+        off[c] = off[c - 1] + cap;
+    }
+    const int64_t cap_mid = std::min<int64_t>(nrows, Y->nnz / (dual_max + 1) + 1);
     const size_t off_seg = (size_t)cap_long * sizeof(LongRow);
-    const size_t off_mid = off_seg + (size_t)cap_seg * sizeof(Segment);
-    als_status st = ensure(ctx, ctx->lists, off_mid + (size_t)cap_mid * sizeof(int64_t));
+    const size_t off_lists = off_seg + (size_t)cap_seg * sizeof(Segment);
+    als_status st = ensure(ctx, ctx->lists, off_lists + (size_t)(cap_mid + off[8]) * sizeof(int32_t));
     if (st != ALS_OK) return st;
     LongRow *long_rows = (LongRow *)ctx->lists.p;
     Segment *segs = (Segment *)((char *)ctx->lists.p + off_seg);
-    int64_t *mid_list = dual_max > 0 ? (int64_t *)((char *)ctx->lists.p + off_mid) : nullptr;
+    int32_t *mid_list = (int32_t *)((char *)ctx->lists.p + off_lists);
+    int32_t *dual_lists = mid_list + cap_mid;
     int32_t *counters = (int32_t *)((char *)ctx->small.p + SM_COUNTERS);
+    ListOffsets list_off;
+    for (int c = 0; c < 8; ++c) list_off.v[c] = off[c];
 
-    // Short rows first: the dual kernels need nothing from the classification, and their closing
-    // table transform passes over every row of the range, so the classifier (which zeroes the empty
-    // rows) and the primal kernels must come after it.
-    if (dual_max > 0) {
-        if ((st = launch_dual(ctx, Y, V, G, prm, X, r0, r1, dual_max, s)) != ALS_OK) return st;
-    }
     timer_begin(ctx, T_CLASSIFY, s);
     hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, s, counters);
-    const unsigned cblocks = (unsigned)((nrows + 255) / 256);
+    const unsigned cblocks = (unsigned)((nrows + CLS_ROWS - 1) / CLS_ROWS);
     if (V->dtype == ALS_BF16)
-        hipLaunchKernelGGL(classify_kernel<true>, dim3(cblocks), dim3(256), 0, s, Y->indptr, r0, r1, split,
-                           (int64_t)dual_max, V->d, X->data, X->ld, counters, long_rows, segs, mid_list);
+        hipLaunchKernelGGL(classify_kernel<true>, dim3(cblocks), dim3(CLS_THREADS), 0, s, Y->indptr, r0, r1, split,
+                           (int64_t)dual_max, V->d, X->data, X->ld, counters, long_rows, segs, mid_list, dual_lists,
+                           list_off);
     else
-        hipLaunchKernelGGL(classify_kernel<false>, dim3(cblocks), dim3(256), 0, s, Y->indptr, r0, r1, split,
-                           (int64_t)dual_max, V->d, X->data, X->ld, counters, long_rows, segs, mid_list);
+        hipLaunchKernelGGL(classify_kernel<false>, dim3(cblocks), dim3(CLS_THREADS), 0, s, Y->indptr, r0, r1, split,
+                           (int64_t)dual_max, V->d, X->data, X->ld, counters, long_rows, segs, mid_list, dual_lists,
+                           list_off);
     timer_end(ctx, s);
     ALS_HIP(ctx, hipGetLastError());
-    ALS_HIP(ctx, hipMemcpyAsync(ctx->host_counters, counters, 4 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    ALS_HIP(ctx, hipMemcpyAsync(ctx->host_counters, counters, 16 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    // the shared factorisation and the table transform need no counts: enqueue them before waiting
+    if (dual_max > 0) {
+        if ((st = launch_dual_prepare(ctx, V, G, prm, s)) != ALS_OK) return st;
+    }
     ALS_HIP(ctx, hipStreamSynchronize(s));
     const int n_long = ctx->host_counters[0], n_seg = ctx->host_counters[1], n_mid = ctx->host_counters[3];
-    if (n_long > cap_long || n_seg > cap_seg || n_mid > cap_mid)
+    if (n_long > cap_long || n_seg > cap_seg)
         return fail(ctx, ALS_EINVAL, "CSR structure inconsistent with nnz (run als_check_csr)");
 
     if (dual_max > 0) {
-        st = launch_primal_fused(ctx, Y, V, G, prm, X, r0, mid_list, n_mid, dual_max, split, s);
-    } else {
-        st = launch_primal_fused(ctx, Y, V, G, prm, X, r0, nullptr, nrows, 0, split, s);
+        const int32_t *lists[8];
+        int counts[8];
+        for (int c = 0; c < 8; ++c) {
+            lists[c] = dual_lists + off[c];
+            counts[c] = ctx->host_counters[8 + c];
+        }
+        if ((st = launch_dual_rows(ctx, Y, X, r0, r1, dual_max, lists, counts, s)) != ALS_OK) return st;
     }
-    if (st != ALS_OK) return st;
+    if ((st = launch_primal_fused(ctx, Y, V, G, prm, X, r0, mid_list, n_mid, s)) != ALS_OK) return st;
     return launch_primal_long(ctx, Y, V, G, prm, X, long_rows, n_long, segs, n_seg, s);
 }
 

@@ -85,17 +85,22 @@ def test_solve_rows_bf16_tables(ctx, gpu_device, d, path):
 @pytest.mark.parametrize("d", [16, 32, 64, 128])
 @pytest.mark.parametrize("values", ["ones", "uniform"])
 def test_solve_rows_auto_path_matches_oracle(ctx, gpu_device, d, values):
-    """Rows with k <= min(d, 64) entries take the k x k dual system, the rest the d x d one."""
+    """Rows with few entries (k <= 16/32/64/128 for d = 16/32/64/128) take the k x k dual system, the
+    rest the d x d one."""
     say(f"solve_rows auto d={d} values={values}")
     p = make_problem("c1", rows=900, cols=700, d=d, values=values)
+    # solve the column side: its rows run from empty ones to hubs with several hundred entries
+    p.indptr, p.indices, p.values, p.rows, p.cols = p.t_indptr, p.t_indices, p.t_values, p.cols, p.rows
+    p.H0 = p.W0
     deg = (p.indptr[1:] - p.indptr[:-1])
-    assert int(deg.max()) > 64 and int(deg.min()) <= 2  # both formulations are exercised
+    assert int(deg.max()) > 128 and int(deg.min()) <= 2  # both formulations are exercised
+    assert int(((deg > 64) & (deg <= 128)).sum()) >= 5
     got_auto, ref = _solve_case(ctx, gpu_device, p, als.PATH_AUTO, scale_v=8.0)
     got_primal, _ = _solve_case(ctx, gpu_device, p, als.PATH_PRIMAL, scale_v=8.0)
     assert rel_fro(got_auto, got_primal) <= 2e-5
 
 
-@pytest.mark.parametrize("dual_max_k", [1, 7, 16, 17, 33, 48, 64])
+@pytest.mark.parametrize("dual_max_k", [1, 7, 16, 17, 33, 48, 64, 65, 81, 100, 128])
 def test_dual_threshold_sweep(ctx, gpu_device, dual_max_k):
     """The result does not depend on where the switch between the two formulations sits."""
     say(f"solve_rows auto d=128 dual_max_k={dual_max_k}")

@@ -126,15 +126,17 @@ als_status als_status_sync(als_ctx *ctx, void *stream);
  * is out of range.  Synchronises `stream`. */
 als_status als_check_csr(als_ctx *ctx, const als_csr *Y, void *stream);
 
-/* Accumulated GPU time in milliseconds (HIP events on the call's stream) of the
- * kernels launched by the most recent als_gramian / als_solve_rows / als_epoch,
- * by stage: [0] gramian, [1] row classification, [2] table transform for the dual
- * form, [3] dual row kernel, [4] primal fused row kernel, [5] long-row segment
- * accumulation, [6] long-row reduce+solve, [7] number of dual-kernel launches.
- * Timing is recorded only while enabled with als_set_timing(ctx, 1); reading
- * synchronises the recorded events. */
+/* Accumulated GPU time in milliseconds (HIP events on the call's stream) of the kernels launched by
+ * the most recent als_gramian / als_solve_rows / als_epoch / als_loss, by stage:
+ *   [0] Gramian   [1] row classification   [2] shared factorisation + table transforms of the dual form
+ *   [3] all dual row kernels   [4] primal fused row kernel   [5] long-row segment accumulation
+ *   [6] long-row reduce + solve   [7] number of dual row-kernel launches
+ *   [8..15] dual row kernel of class c = 0..7 (rows with 16c < k <= 16(c+1) stored entries)
+ *   [16..23] launches of that class's kernel
+ * Timing is recorded only while enabled with als_set_timing(ctx, 1); reading waits for the recorded
+ * events. */
 als_status als_set_timing(als_ctx *ctx, int enabled);
-als_status als_get_timing(als_ctx *ctx, double *ms_host /* [8] */);
+als_status als_get_timing(als_ctx *ctx, double *ms_host /* [24] */);
 
 const char *als_strerror(als_status status);
 const char *als_last_error(const als_ctx *ctx);

@@ -201,10 +201,11 @@ def als_set_timing(ctx: Context, enabled: bool) -> None:
     ctx._check(ctx.lib.als_set_timing(ctx.handle, int(enabled)))
 
 
-TIMING_SLOTS = ["gramian", "classify", "transform", "dual", "primal", "segment", "reduce", "dual_launches"]
+TIMING_SLOTS = (["gramian", "classify", "transform", "dual", "primal", "segment", "reduce", "dual_launches"]
+                + [f"dual_k{16 * (c + 1)}" for c in range(8)] + [f"launches_k{16 * (c + 1)}" for c in range(8)])
 
 
 def als_get_timing(ctx: Context) -> dict:
-    buf = (ctypes.c_double * 8)()
+    buf = (ctypes.c_double * 24)()
     ctx._check(ctx.lib.als_get_timing(ctx.handle, buf))
     return dict(zip(TIMING_SLOTS, list(buf)))

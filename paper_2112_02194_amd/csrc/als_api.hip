@@ -270,7 +270,11 @@ als_status als_get_timing(als_ctx *ctx, double *ms_host) {
         float ms = 0.f;
         ALS_HIP(ctx, hipEventElapsedTime(&ms, t.e0, t.e1));
         ctx->timing_ms[t.slot] += ms;
-        if (t.slot == T_DUAL) ctx->timing_ms[7] += 1.0;
+        if (t.slot >= T_DUAL_CLASS0 && t.slot < T_DUAL_CLASS0 + 8) {
+            ctx->timing_ms[T_DUAL] += ms;
+            ctx->timing_ms[T_LAUNCHES] += 1.0;
+            ctx->timing_ms[t.slot + 8] += 1.0;
+        }
     }
     for (int i = 0; i < T_COUNT; ++i) ms_host[i] = ctx->timing_ms[i];
     return ALS_OK;

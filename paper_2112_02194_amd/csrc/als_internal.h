@@ -119,7 +119,8 @@ struct DevBuf {
     size_t bytes = 0;
 };
 
-enum TimingSlot { T_GRAMIAN = 0, T_CLASSIFY, T_TRANSFORM, T_DUAL, T_PRIMAL, T_SEGMENT, T_REDUCE, T_COUNT = 8 };
+enum TimingSlot { T_GRAMIAN = 0, T_CLASSIFY, T_TRANSFORM, T_DUAL, T_PRIMAL, T_SEGMENT, T_REDUCE, T_LAUNCHES,
+                  T_DUAL_CLASS0 = 8, T_COUNT = 24 };  // [8..15] ms per dual class, [16..23] launches per class
 
 struct Timer {
     hipEvent_t e0 = nullptr, e1 = nullptr;

@@ -14,6 +14,7 @@
 //                     MFMA operand registers, S = I + Z_I Z_I^T on the matrix cores, Cholesky + two
 //                     triangular solves with one lane per row of S, then r = Z_I^T t
 //   transform_kernel  X = R L^{-1}   (rows r -> L^{-T} r), rounding to the table's element type
+#include <cstdlib>
 #include <type_traits>
 
 #include "als_internal.h"
@@ -157,17 +158,18 @@ template <int N> __device__ __forceinline__ float add_row_ror(float x) {
     return x + __int_as_float(r);
 }
 
-template <int D, int K> struct DualCfg {
+template <int D, int K, bool RG> struct DualCfg {
     static constexpr int KT = K / 16;                       // 16-entry tiles per row
     static constexpr int GW = K <= 16 ? 16 : (K <= 32 ? 32 : 64);  // lanes that share one row's k x k system
     static constexpr int RPW = 64 / GW;                     // rows per wavefront
     static constexpr int KP = K + 4;                        // LDS row stride of S (keeps rows 16-byte aligned)
     static constexpr int NJ = D / 16;                       // float4 loads per lane and entry
-    static constexpr bool ZBUF = K <= 32;                   // r = Z_I^T t through an LDS copy of Z_I
+    static constexpr bool ZBUF = !RG && K <= 32;            // r = Z_I^T t through an LDS copy of Z_I
     static constexpr int ZLD = D + 4;
     static constexpr int SB_FLOATS = RPW * K * KP;
     static constexpr int ZB_FLOATS = ZBUF ? K * ZLD : 0;
-    static constexpr int LDS_FLOATS = (SB_FLOATS > ZB_FLOATS ? SB_FLOATS : ZB_FLOATS) + 64;
+    static constexpr int TAIL = 64 + 128 + 4;             // tbuf[64], colbuf[2][64], ybuf[2][2]
+    static constexpr int LDS_FLOATS = (SB_FLOATS > ZB_FLOATS ? SB_FLOATS : ZB_FLOATS) + TAIL;
 };
 
 // One wavefront (= one workgroup) solves RPW rows taken from `list` (row ids relative to r0), all
@@ -180,17 +182,17 @@ template <int D, int K> struct DualCfg {
 //      broadcast inside the group, then L w = y, then L^T t = w with L read back transposed;
 //   3. r = Z_I^T t, either from an LDS copy of Z_I with one lane per output column pair, or (K > 32)
 //      by a cross-lane reduction of the lanes' own pieces.
-template <int D, int K>
+template <int D, int K, bool RG>
 __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict__ indptr,
                                                        const int32_t *__restrict__ indices,
                                                        const float *__restrict__ values,
                                                        const float *__restrict__ Z, float *__restrict__ R,
                                                        int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
                                                        int count, int32_t *__restrict__ err_flag) {
-    using C = DualCfg<D, K>;
+    using C = DualCfg<D, K, RG>;
     constexpr int KT = C::KT, GW = C::GW, RPW = C::RPW, KP = C::KP, NJ = C::NJ, ZLD = C::ZLD;
     extern __shared__ float lds[];
-    float *sb = lds, *zb = lds, *tb = lds + (C::LDS_FLOATS - 64);
+    float *sb = lds, *zb = lds, *tb = lds + (C::LDS_FLOATS - C::TAIL);
     const int lane = threadIdx.x;
     const int a = lane & 15, q = lane >> 4;
     const int grp = lane / GW, gi = lane % GW;
@@ -276,49 +278,129 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
         }
     }
     wave_sync();
-    float myrinv = 1.f;
     bool bad = false;
-    static_for<0, K>([&](auto cc) {
-        constexpr int c = decltype(cc)::value;
-        if (c < kmax) {  // steps beyond every row's k only meet identity rows
-            const float pivot = group_bcast<GW, c>(s[c]);
-            bad |= !(pivot > 0.f);
-            float rinv = __builtin_amdgcn_rsqf(pivot);
-            rinv = rinv * (1.5f - 0.5f * pivot * rinv * rinv);  // one Newton step on the hardware estimate
-            const float lc = s[c] * rinv;
-            s[c] = lc;
-            myrinv = myrow == c ? rinv : myrinv;
-            static_for<c + 1, K>([&](auto ii) {
-                constexpr int i = decltype(ii)::value;
-                s[i] -= lc * group_bcast<GW, i>(lc);
-            });
-        }
-    });
-    if (bad && myk > 0) atomicOr(err_flag, 1);
-    static_for<0, K>([&](auto cc) {  // L w = y
-        constexpr int c = decltype(cc)::value;
-        if (c < kmax) {
-            const float wc = group_bcast<GW, c>(yv) * group_bcast<GW, c>(myrinv);
-            yv = myrow > c ? yv - s[c] * wc : (myrow == c ? wc : yv);
-        }
-    });
-    {
-        float4 *row = (float4 *)(sb + (grp * K + myrow) * KP);
+    if constexpr (GW == 16) {
+        // k <= 16: Cholesky S = L L^T, column broadcast by DPP inside the 16-lane group
+        float myrinv = 1.f;
+        static_for<0, K>([&](auto cc) {
+            constexpr int c = decltype(cc)::value;
+            if (c < kmax) {  // steps beyond every row's k only meet identity rows
+                const float pivot = group_bcast<GW, c>(s[c]);
+                bad |= !(pivot > 0.f);
+                float rinv = __builtin_amdgcn_rsqf(pivot);
+                rinv = rinv * (1.5f - 0.5f * pivot * rinv * rinv);  // one Newton step on the hardware estimate
+                const float lc = s[c] * rinv;
+                s[c] = lc;
+                myrinv = myrow == c ? rinv : myrinv;
+                static_for<c + 1, K>([&](auto ii) {
+                    constexpr int i = decltype(ii)::value;
+                    s[i] -= lc * group_bcast<GW, i>(lc);
+                });
+            }
+        });
+        static_for<0, K>([&](auto cc) {  // L w = y
+            constexpr int c = decltype(cc)::value;
+            if (c < kmax) {
+                const float wc = group_bcast<GW, c>(yv) * group_bcast<GW, c>(myrinv);
+                yv = myrow > c ? yv - s[c] * wc : (myrow == c ? wc : yv);
+            }
+        });
+        {
+            float4 *row = (float4 *)(sb + (grp * K + myrow) * KP);
 #pragma unroll
-        for (int c4 = 0; c4 < K / 4; ++c4) row[c4] = make_float4(s[4 * c4], s[4 * c4 + 1], s[4 * c4 + 2], s[4 * c4 + 3]);
-    }
-    wave_sync();
-    static_for<0, K>([&](auto cc) {  // L^T t = w
-        constexpr int c = K - 1 - decltype(cc)::value;
-        if (c < kmax) {
-            const float tc = group_bcast<GW, c>(yv) * group_bcast<GW, c>(myrinv);
-            const float lt = sb[(grp * K + c) * KP + myrow];  // L[c][myrow], meaningful for myrow <= c
-            yv = myrow < c ? yv - lt * tc : (myrow == c ? tc : yv);
+            for (int c4 = 0; c4 < K / 4; ++c4)
+                row[c4] = make_float4(s[4 * c4], s[4 * c4 + 1], s[4 * c4 + 2], s[4 * c4 + 3]);
         }
-    });
+        wave_sync();
+        static_for<0, K>([&](auto cc) {  // L^T t = w
+            constexpr int c = K - 1 - decltype(cc)::value;
+            if (c < kmax) {
+                const float tc = group_bcast<GW, c>(yv) * group_bcast<GW, c>(myrinv);
+                const float lt = sb[(grp * K + c) * KP + myrow];  // L[c][myrow], meaningful for myrow <= c
+                yv = myrow < c ? yv - lt * tc : (myrow == c ? tc : yv);
+            }
+        });
+    } else {
+        // 16 < k <= 64: S = M D M^T (M unit lower, D the pivots), one column per step.  Every lane
+        // publishes its entry of the column in LDS (double-buffered by step parity), then reads the
+        // pivot and the whole column back with broadcast reads; u = M^{-1} y rides along.
+        float *colbuf = tb + 64, *yb = tb + 64 + 128;
+        float rp_mine = 1.f;
+        static_for<0, K>([&](auto cc) {
+            constexpr int c = decltype(cc)::value;
+            if (c < kmax) {
+                float *cb = colbuf + (c & 1) * 64;
+                cb[lane] = s[c];  // S'[row][c] as it stands (column c is final)
+                if (gi == c) yb[(c & 1) * 2 + grp] = yv;
+                wave_sync();
+                const float pivot = cb[grp * GW + c];
+                const float uc = yb[(c & 1) * 2 + grp];
+                bad |= !(pivot > 0.f);
+                float rp = __builtin_amdgcn_rcpf(pivot);
+                rp = rp * (2.f - pivot * rp);  // one Newton step on the hardware reciprocal
+                rp_mine = myrow == c ? rp : rp_mine;
+                const float f = myrow > c ? s[c] * rp : 0.f;  // M[row][c]; rows above stay as they are
+                yv -= f * uc;
+                static_for<(c + 1) / 4, K / 4>([&](auto jj) {
+                    constexpr int j4 = decltype(jj)::value;
+                    const float4 col = *(const float4 *)(cb + grp * GW + 4 * j4);
+                    if constexpr (4 * j4 + 0 > c) s[4 * j4 + 0] -= f * col.x;
+                    if constexpr (4 * j4 + 1 > c) s[4 * j4 + 1] -= f * col.y;
+                    if constexpr (4 * j4 + 2 > c) s[4 * j4 + 2] -= f * col.z;
+                    if constexpr (4 * j4 + 3 > c) s[4 * j4 + 3] -= f * col.w;
+                });
+            }
+        });
+        // t_c = (u_c - sum_{R>c} S'[R][c] t_R) / pivot_c with lane c owning unknown c: the factor is
+        // read back transposed through LDS, t_c is broadcast inside the group
+        {
+            float4 *row = (float4 *)(sb + (grp * K + myrow) * KP);
+#pragma unroll
+            for (int c4 = 0; c4 < K / 4; ++c4)
+                row[c4] = make_float4(s[4 * c4], s[4 * c4 + 1], s[4 * c4 + 2], s[4 * c4 + 3]);
+        }
+        wave_sync();
+#pragma unroll
+        for (int c = 0; c < K; ++c) s[c] = sb[(grp * K + c) * KP + myrow];  // S'[c][myrow], used for myrow < c
+        static_for<0, K>([&](auto cc) {
+            constexpr int c = K - 1 - decltype(cc)::value;
+            if (c < kmax) {
+                const float tc = group_bcast<GW, c>(yv * rp_mine);
+                yv = myrow < c ? yv - s[c] * tc : (myrow == c ? tc : yv);
+            }
+        });
+    }
+    if (bad && myk > 0) atomicOr(err_flag, 1);
 
     // ---- 3. r = Z_I^T t
-    if constexpr (C::ZBUF) {
+    if constexpr (RG) {
+        // gather the row's entries a second time (they are still in the caches), one lane per pair of
+        // output columns, so that no copy of Z_I has to stay in registers or LDS during the solve
+        constexpr int CPL = D >= 128 ? 2 : 1;
+        tb[lane] = yv;  // lane grp*GW + i holds t_i
+        wave_sync();
+#pragma unroll
+        for (int p = 0; p < RPW; ++p) {
+            if (u[p] >= 0 && lane * CPL < D) {
+                float r0v = 0.f, r1v = 0.f;
+                const int32_t *ix = indices + b[p];
+#pragma unroll 8
+                for (int e = 0; e < k[p]; ++e) {
+                    const float te = tb[p * GW + e];
+                    const float *zr = Z + (int64_t)ix[e] * D + CPL * lane;
+                    if constexpr (CPL == 2) {
+                        const float2 zz = *(const float2 *)zr;
+                        r0v += te * zz.x;
+                        r1v += te * zz.y;
+                    } else {
+                        r0v += te * zr[0];
+                    }
+                }
+                if constexpr (CPL == 2) *(float2 *)(R + u[p] * ldr + 2 * lane) = make_float2(r0v, r1v);
+                else R[u[p] * ldr + lane] = r0v;
+            }
+        }
+    } else if constexpr (C::ZBUF) {
         constexpr int CPL = D >= 128 ? 2 : 1;  // output columns per lane
         tb[lane] = yv;                         // K <= 32: lane == grp*K + row
 #pragma unroll
@@ -544,13 +626,29 @@ __global__ __launch_bounds__(64 * KT) void dual_big_kernel(const int64_t *__rest
 // ---------------------------------------------------------------------------------------------- launchers
 int dual_supported_max_k(int d) { return d < 128 ? (d < 64 ? d : 64) : 128; }
 
+static bool regather_default(int K) {
+    // bit i set = class i (K = 16*(i+1)) gathers its entries a second time for r = Z_I^T t instead of
+    // keeping them in registers; measured faster only for K = 64 (register pressure).  The
+    // environment variable is a tuning knob for experiments.
+    const char *e = getenv("ALS_DUAL_REGATHER");
+    const int mask = e ? atoi(e) : 8;
+    return (mask >> (K / 16 - 1)) & 1;
+}
+
 template <int D, int K>
 static void launch_dual_class(const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0,
                               const int32_t *list, int count, int32_t *err, hipStream_t s) {
     if (count <= 0) return;
-    using C = DualCfg<D, K>;
+    if (regather_default(K)) {
+        using C = DualCfg<D, K, true>;
+        const unsigned blocks = (unsigned)((count + C::RPW - 1) / C::RPW);
+        hipLaunchKernelGGL((dual_rows_kernel<D, K, true>), dim3(blocks), dim3(64), C::LDS_FLOATS * sizeof(float), s,
+                           Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count, err);
+        return;
+    }
+    using C = DualCfg<D, K, false>;
     const unsigned blocks = (unsigned)((count + C::RPW - 1) / C::RPW);
-    hipLaunchKernelGGL((dual_rows_kernel<D, K>), dim3(blocks), dim3(64), C::LDS_FLOATS * sizeof(float), s, Y->indptr,
+    hipLaunchKernelGGL((dual_rows_kernel<D, K, false>), dim3(blocks), dim3(64), C::LDS_FLOATS * sizeof(float), s, Y->indptr,
                        Y->indices, Y->values, Z, R, ldr, r0, list, count, err);
 }
 
@@ -609,21 +707,22 @@ static als_status dual_rows_typed(als_ctx *ctx, const als_csr *Y, als_table *X, 
     const float *Linv = (const float *)((char *)ctx->small.p + SM_FACTOR);
     int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
     const float *Z = (const float *)ctx->ztable.p;
-    auto k1 = dual_rows_kernel<D, 16>;
-    auto k2 = dual_rows_kernel<D, 32>;
-    auto k3 = dual_rows_kernel<D, 48>;
-    auto k4 = dual_rows_kernel<D, 64>;
-    (void)k1; (void)k2; (void)k3; (void)k4;
-    timer_begin(ctx, T_DUAL, s);
-    launch_dual_class<D, 16>(Y, Z, R, ldr, r0, lists[0], counts[0], err, s);
-    launch_dual_class<D, 32>(Y, Z, R, ldr, r0, lists[1], counts[1], err, s);
-    launch_dual_class<D, 48>(Y, Z, R, ldr, r0, lists[2], counts[2], err, s);
-    launch_dual_class<D, 64>(Y, Z, R, ldr, r0, lists[3], counts[3], err, s);
-    als_status stb = launch_big_class<D, 5>(ctx, Y, Z, R, ldr, r0, lists[4], counts[4], err, s);
-    if (stb == ALS_OK) stb = launch_big_class<D, 6>(ctx, Y, Z, R, ldr, r0, lists[5], counts[5], err, s);
-    if (stb == ALS_OK) stb = launch_big_class<D, 7>(ctx, Y, Z, R, ldr, r0, lists[6], counts[6], err, s);
-    if (stb == ALS_OK) stb = launch_big_class<D, 8>(ctx, Y, Z, R, ldr, r0, lists[7], counts[7], err, s);
-    timer_end(ctx, s);
+    als_status stb = ALS_OK;
+#define ALS_TIMED_CLASS(cls, call)                  \
+    if (counts[cls] > 0 && stb == ALS_OK) {         \
+        timer_begin(ctx, T_DUAL_CLASS0 + cls, s);   \
+        call;                                       \
+        timer_end(ctx, s);                          \
+    }
+    ALS_TIMED_CLASS(0, (launch_dual_class<D, 16>(Y, Z, R, ldr, r0, lists[0], counts[0], err, s)))
+    ALS_TIMED_CLASS(1, (launch_dual_class<D, 32>(Y, Z, R, ldr, r0, lists[1], counts[1], err, s)))
+    ALS_TIMED_CLASS(2, (launch_dual_class<D, 48>(Y, Z, R, ldr, r0, lists[2], counts[2], err, s)))
+    ALS_TIMED_CLASS(3, (launch_dual_class<D, 64>(Y, Z, R, ldr, r0, lists[3], counts[3], err, s)))
+    ALS_TIMED_CLASS(4, (stb = launch_big_class<D, 5>(ctx, Y, Z, R, ldr, r0, lists[4], counts[4], err, s)))
+    ALS_TIMED_CLASS(5, (stb = launch_big_class<D, 6>(ctx, Y, Z, R, ldr, r0, lists[5], counts[5], err, s)))
+    ALS_TIMED_CLASS(6, (stb = launch_big_class<D, 7>(ctx, Y, Z, R, ldr, r0, lists[6], counts[6], err, s)))
+    ALS_TIMED_CLASS(7, (stb = launch_big_class<D, 8>(ctx, Y, Z, R, ldr, r0, lists[7], counts[7], err, s)))
+#undef ALS_TIMED_CLASS
     if (stb != ALS_OK) return stb;
     timer_begin(ctx, T_TRANSFORM, s);
     const unsigned xblocks = (unsigned)std::min<int64_t>(2048, std::max<int64_t>(1, (r1 - r0 + 63) / 64));

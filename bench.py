@@ -84,6 +84,8 @@ def main():
     ap.add_argument("--rows", type=int, default=0, help="override the node count (debugging only; invalidates the line)")
     ap.add_argument("--path", default="auto", choices=["auto", "primal"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="run the library's plain copy kernel on this many MiB first (counter calibration when profiling)")
     ap.add_argument("--cpu-sample-rows", type=int, default=50000)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -117,6 +119,13 @@ def main():
     als.als_check_csr(ctx, Y)
     als.als_check_csr(ctx, Yt)
 
+    if args.copy_probe_mib > 0:
+        src = torch.ones(args.copy_probe_mib * (1 << 18), dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        als.als_copy_probe(ctx, src, dst)
+        torch.cuda.synchronize()
+        assert bool(torch.equal(src, dst))
+        del src, dst
     for i in range(args.warmup):
         als.als_epoch(ctx, Y, Yt, W, H, prm)
         torch.cuda.synchronize()

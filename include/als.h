@@ -42,8 +42,9 @@ typedef enum { ALS_F32 = 0, ALS_BF16 = 1 } als_dtype;
  *   ALS_PATH_PRIMAL : every row forms and solves the d x d normal equations of
  *                     Eq. 4 (Algorithm 1 lines 4-10 literally).
  *   ALS_PATH_DUAL   : as AUTO (kept distinct so callers can state intent).
- * Both formulations reach the same minimiser of Eq. 3; see DESIGN notes in the
- * source for the algebra. */
+ * Both formulations reach the same minimiser of Eq. 3 (the algebra is in the header
+ * comment of csrc/rows_dual.hip).  The dual form is available for k <= min(d, 64),
+ * and for k <= 128 when d = 128. */
 typedef enum { ALS_PATH_AUTO = 0, ALS_PATH_PRIMAL = 1, ALS_PATH_DUAL = 2 } als_path;
 
 /* Sparse label matrix in CSR form (Section 3: the training set S as a matrix Y).
@@ -71,7 +72,8 @@ typedef struct {
     float alpha;        /* weight of the all-pairs term of Eq. 3, >= 0                         */
     float lambda;       /* L2 weight of Eq. 3, > 0 (keeps every system positive definite)      */
     int32_t path;       /* als_path                                                             */
-    int32_t dual_max_k; /* 0 = library default; largest k solved in the dual form (<= 128)      */
+    int32_t dual_max_k; /* 0 = library default (the largest supported); largest k solved in the dual
+                           form, clipped to what the table's d supports                          */
     int32_t split_nnz;  /* 0 = library default; rows longer than this are cut into segments whose
                            partial statistics are summed (Section 4.3's row splitting)           */
 } als_params;
@@ -125,6 +127,11 @@ als_status als_status_sync(als_ctx *ctx, void *stream);
  * ALS_OK, or ALS_EINVAL if indptr is not monotone from 0 to nnz or a column id
  * is out of range.  Synchronises `stream`. */
 als_status als_check_csr(als_ctx *ctx, const als_csr *Y, void *stream);
+
+/* Profiling aid: a plain device-to-device copy kernel of known size (`bytes`, a multiple of 16, both
+ * pointers device and 16-byte aligned).  Hardware traffic counters (FETCH_SIZE, WRITE_SIZE) read for
+ * this kernel give the scale factor applied to the counters of the other kernels. */
+als_status als_copy_probe(als_ctx *ctx, const void *src, void *dst, int64_t bytes, void *stream);
 
 /* Accumulated GPU time in milliseconds (HIP events on the call's stream) of the kernels launched by
  * the most recent als_gramian / als_solve_rows / als_epoch / als_loss, by stage:

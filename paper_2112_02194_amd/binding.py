@@ -22,8 +22,8 @@ ALS_F32, ALS_BF16 = 0, 1
 PATH_AUTO, PATH_PRIMAL, PATH_DUAL = 0, 1, 2
 
 EXPORTS = ["als_create", "als_destroy", "als_gramian", "als_solve_rows", "als_epoch", "als_loss",
-           "als_status_sync", "als_check_csr", "als_set_timing", "als_get_timing", "als_strerror",
-           "als_last_error"]
+           "als_status_sync", "als_check_csr", "als_copy_probe", "als_set_timing", "als_get_timing",
+           "als_strerror", "als_last_error"]
 
 
 class c_als_csr(ctypes.Structure):
@@ -70,7 +70,8 @@ def load_library(path: str = LIB_PATH):
     lib.als_check_csr.argtypes = [vp, P(c_als_csr), vp]
     lib.als_set_timing.argtypes = [vp, i32]
     lib.als_get_timing.argtypes = [vp, P(ctypes.c_double)]
-    for name in EXPORTS[:10]:
+    lib.als_copy_probe.argtypes = [vp, vp, vp, i64, vp]
+    for name in EXPORTS[:11]:
         getattr(lib, name).restype = i32
     lib.als_strerror.argtypes = [i32]
     lib.als_strerror.restype = ctypes.c_char_p
@@ -195,6 +196,12 @@ def als_status_sync(ctx: Context) -> None:
 def als_check_csr(ctx: Context, Y: Csr) -> None:
     cy = Y.c()
     ctx._check(ctx.lib.als_check_csr(ctx.handle, ctypes.byref(cy), _stream()))
+
+
+def als_copy_probe(ctx: Context, src: torch.Tensor, dst: torch.Tensor) -> None:
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes and src.is_contiguous() and dst.is_contiguous()
+    ctx._check(ctx.lib.als_copy_probe(ctx.handle, src.data_ptr(), dst.data_ptr(), nbytes, _stream()))
 
 
 def als_set_timing(ctx: Context, enabled: bool) -> None:

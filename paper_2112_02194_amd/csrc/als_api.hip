@@ -256,6 +256,13 @@ als_status als_check_csr(als_ctx *ctx, const als_csr *Y, void *stream) {
     return ALS_OK;
 }
 
+als_status als_copy_probe(als_ctx *ctx, const void *src, void *dst, int64_t bytes, void *stream) {
+    if (!ctx) return ALS_EINVAL;
+    if (!src || !dst || bytes < 0 || bytes % 16 != 0 || ((uintptr_t)src % 16) || ((uintptr_t)dst % 16))
+        return fail(ctx, ALS_EINVAL, "copy probe needs 16-byte aligned buffers and a size that is a multiple of 16");
+    return launch_copy_probe(ctx, src, dst, bytes, (hipStream_t)stream);
+}
+
 als_status als_set_timing(als_ctx *ctx, int enabled) {
     if (!ctx) return ALS_EINVAL;
     ctx->timing = enabled != 0;

@@ -183,5 +183,6 @@ als_status launch_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V,
 als_status launch_loss(als_ctx *ctx, const als_csr *Y, const als_table *W, const als_table *H,
                        const float *GW, const float *GH, const als_params *prm, double *out_dev, hipStream_t s);
 als_status launch_check_csr(als_ctx *ctx, const als_csr *Y, int32_t *flag_dev, hipStream_t s);
+als_status launch_copy_probe(als_ctx *ctx, const void *src, void *dst, int64_t bytes, hipStream_t s);
 
 }  // namespace als

@@ -78,6 +78,22 @@ __global__ __launch_bounds__(256) void loss_final_kernel(const double *__restric
     if (threadIdx.x == 0) out[0] = red[0];
 }
 
+// Plain device-to-device copy of `bytes` bytes (a multiple of 16): the known-size kernel against
+// which hardware traffic counters are calibrated when profiling.
+__global__ __launch_bounds__(256) void copy_probe_kernel(const float4 *__restrict__ src, float4 *__restrict__ dst,
+                                                         int64_t n16) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+als_status launch_copy_probe(als_ctx *ctx, const void *src, void *dst, int64_t bytes, hipStream_t s) {
+    const int64_t n16 = bytes / 16;
+    const unsigned blocks = (unsigned)std::min<int64_t>(8192, std::max<int64_t>(1, (n16 + 255) / 256));
+    hipLaunchKernelGGL(copy_probe_kernel, dim3(blocks), dim3(256), 0, s, (const float4 *)src, (float4 *)dst, n16);
+    ALS_HIP(ctx, hipGetLastError());
+    return ALS_OK;
+}
+
 template <int D, bool BF16>
 static als_status loss_typed(als_ctx *ctx, const als_csr *Y, const als_table *W, const als_table *H,
                              const float *GW, const float *GH, const als_params *prm, double *out_dev,

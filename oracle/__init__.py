@@ -88,6 +88,17 @@ def gramian(V):
     return G
 
 
+def gramian_matmul(V, chunk: int = 1 << 20):
+    """G = V^T V with the library matmul in fp64, chunked over rows: the same definition as
+    ``gramian`` with a library primitive as the step, for tables too large for the plain loop."""
+    d = V.shape[1]
+    G = np.zeros((d, d), dtype=np.float64)
+    for r0 in range(0, V.shape[0], chunk):
+        blk = np.asarray(V[r0:r0 + chunk], dtype=np.float64)
+        G += blk.T @ blk
+    return G
+
+
 def solve_rows(indptr, indices, values, V, G, alpha, lam, row_ids=None, storage="f64"):
     """Eq. 4 for the listed rows (all rows if ``row_ids`` is None) -> [nrows x d] fp64."""
     ip, ix, vv = _csr(indptr, indices, values)

@@ -8,6 +8,7 @@ from .matrices import (  # noqa: F401
     CONFIGS,
     SparseProblem,
     csr_from_edges,
+    extract_rows,
     hash_u64,
     init_table,
     make_problem,

@@ -302,3 +302,21 @@ def make_problem(kind: str, device="cpu", rows: Optional[int] = None, cols: Opti
     H0 = init_table(cols, d, seed, 13, device=device, dtype=tdt)
     return SparseProblem(kind, rows, cols, d, cfg["alpha"], cfg["lam"], cfg["epochs"], tdt,
                          indptr, indices, vals, t_indptr, t_indices, t_vals, W0, H0)
+
+
+def extract_rows(indptr: torch.Tensor, indices: torch.Tensor, values: Optional[torch.Tensor], rows: torch.Tensor):
+    """Sub-matrix made of the listed rows, with its column ids renumbered densely.
+
+    Returns (sub_indptr, sub_indices, sub_values, used_cols): row r of the result is row ``rows[r]``
+    of the input and refers to column ``used_cols[sub_indices[p]]``.  Pure index plumbing, used to
+    hand a sample of a large problem (and only the table rows it touches) to the CPU.
+    """
+    rows = rows.to(torch.int64)
+    starts, lens = indptr[rows], indptr[rows + 1] - indptr[rows]
+    sub_ptr = torch.zeros(rows.numel() + 1, dtype=torch.int64, device=indptr.device)
+    torch.cumsum(lens, 0, out=sub_ptr[1:])
+    total = int(sub_ptr[-1])
+    pos = torch.repeat_interleave(starts - sub_ptr[:-1], lens) + torch.arange(total, device=indptr.device)
+    used, inv = torch.unique(indices[pos], return_inverse=True)
+    vals = None if values is None else values[pos].contiguous()
+    return sub_ptr, inv.to(torch.int32).contiguous(), vals, used.to(torch.int64)

@@ -171,6 +171,12 @@ def test_gramian_invariants_and_library_matmul():
     assert np.array_equal(oracle.gramian(V2), np.array([[1, 2, 3], [2, 5, 6], [3, 6, 9.0]]))
 
 
+def test_matmul_gramian_equals_plain_loop_gramian():
+    V = RNG.normal(0, 1, (5000, 12)).astype(np.float32)
+    a, b = oracle.gramian(V), oracle.gramian_matmul(V, chunk=777)
+    assert np.abs(a - b).max() <= 1e-11 * np.abs(a).max()
+
+
 def test_solution_is_linear_in_labels_and_order_free():
     alpha, lam = 0.1, 0.01
     indptr, indices, values, H = random_problem(12, 30, 6)

@@ -85,3 +85,15 @@ def test_values_option_and_transpose_carries_values():
     rt = np.repeat(np.arange(p.cols), np.diff(p.t_indptr.numpy()))
     bwd = {(b, a): v for a, b, v in zip(rt.tolist(), p.t_indices.tolist(), p.t_values.tolist())}
     assert fwd == bwd
+
+
+def test_extract_rows_is_a_faithful_submatrix():
+    from synth import extract_rows
+    p = make_problem("c1", rows=300, cols=250, values="uniform")
+    pick = torch.tensor([7, 0, 299, 41, 41])
+    sp, si, sv, used = extract_rows(p.indptr, p.indices, p.values, pick)
+    assert sp[0] == 0 and sp.numel() == 6
+    for r, u in enumerate(pick.tolist()):
+        a, b = int(p.indptr[u]), int(p.indptr[u + 1])
+        assert torch.equal(used[si[sp[r]:sp[r + 1]].long()], p.indices[a:b].long())
+        assert torch.equal(sv[sp[r]:sp[r + 1]], p.values[a:b])

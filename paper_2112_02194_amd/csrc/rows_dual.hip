@@ -73,55 +73,88 @@ __global__ __launch_bounds__(256) void factor_kernel(const float *__restrict__ G
 
 // ---------------------------------------------------------------------------------------------- transform
 // Out[r][:] = In[r][:] * M for rows r in [r0, r1) (only rows with 0 < k <= k_max stored entries when
-// indptr is given), M fp32 [D x D] row-major.  In may be bf16 or
-// fp32, Out fp32 or bf16; Out may be the same buffer as In (a workgroup reads its whole row tile
-// into LDS before it writes).  Wavefront w owns output column tile w % NCT for the row sub-tiles
-// of its group and keeps its slice of M in registers.
-template <int D, bool IN_BF16, bool OUT_BF16>
+// indptr is given), M fp32 [D x D] row-major and triangular: UPPER = true means M[j][c] = 0 for j > c
+// (M = L^{-T}), UPPER = false means M[j][c] = 0 for j < c (M = L^{-1}).  In may be bf16 or fp32, Out
+// fp32 or bf16; Out may be the same buffer as In (a wavefront reads its rows completely before it
+// writes them, and no other wavefront touches them).
+//
+// A wavefront owns TM table rows at a time and all D output columns.  Lane (m, kq) streams along row
+// m: for the contraction block kb (TM input columns) it holds the BW = TM/KS consecutive columns
+// TM*kb + BW*kq .. of its row, loaded straight from global memory as 16-byte pieces; step i of the
+// block contracts column TM*kb + BW*kq + i (A and B operands only have to agree on that mapping).
+// The transposed matrix sits in LDS (one copy per workgroup, MT[c][j], padded rows) and supplies the
+// B operands; blocks that only meet zeros of the triangular matrix are skipped.
+template <int D> struct XfCfg {
+    using GE = Geo<D>;
+    static constexpr int TM = GE::TM, KS = GE::KS, NB = D / TM, BW = TM / KS, MLD = D + 4;
+    static constexpr size_t LDS_BYTES = (size_t)D * MLD * sizeof(float);
+};
+
+template <int D, bool IN_BF16, bool OUT_BF16, bool UPPER>
 __global__ __launch_bounds__(256) void transform_kernel(const void *__restrict__ In, int64_t ldi,
                                                         void *__restrict__ Out, int64_t ldo,
                                                         const float *__restrict__ M, int64_t r0, int64_t r1,
                                                         const int64_t *__restrict__ indptr, int64_t k_max) {
-    using GE = Geo<D>;
-    constexpr int TM = GE::TM, KS = GE::KS, ACC = GE::ACC;
-    constexpr int NCT = D / TM, RG = 4 / NCT, RT = 64, NSUB = RT / TM, LD = D + 1, NS = D / KS;
+    using C = XfCfg<D>;
+    constexpr int TM = C::TM, NB = C::NB, BW = C::BW, MLD = C::MLD, ACC = Geo<D>::ACC;
     typedef typename AccT<ACC>::type acc_t;
-    __shared__ float At[RT * LD];
+    extern __shared__ float MT[];  // MT[c * MLD + j] = M[j][c]
+    for (int e = threadIdx.x; e < D * D; e += 256) {
+        const int j = e / D, c = e % D;
+        MT[c * MLD + j] = M[e];
+    }
+    __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane % TM, kq = lane / TM;
-    const int J = wave % NCT, rg = wave / NCT;
-    float breg[NS];
+    const int64_t ntiles = (r1 - r0 + TM - 1) / TM;
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < ntiles; tile += nwaves) {
+        const int64_t base = r0 + tile * TM, row = base + m;
+        float a[NB][BW];
 #pragma unroll
-    for (int s = 0; s < NS; ++s) breg[s] = M[(KS * s + kq) * D + TM * J + m];
-
-    const int64_t ntiles = (r1 - r0 + RT - 1) / RT;
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t base = r0 + tile * RT;
-        __syncthreads();  // previous tile's operand reads are done
-        for (int e = threadIdx.x; e < RT * (D / 4); e += 256) {
-            const int row = e / (D / 4), c4 = e % (D / 4);
-            float x[4] = {0.f, 0.f, 0.f, 0.f};
-            if (base + row < r1) load_vec<4, IN_BF16>(In, (base + row) * ldi + 4 * c4, x);
+        for (int kb = 0; kb < NB; ++kb)
 #pragma unroll
-            for (int c = 0; c < 4; ++c) At[row * LD + 4 * c4 + c] = x[c];
+            for (int i4 = 0; i4 < BW / 4; ++i4) {
+                float x[4] = {0.f, 0.f, 0.f, 0.f};
+                if (row < r1) load_vec<4, IN_BF16>(In, row * ldi + TM * kb + BW * kq + 4 * i4, x);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) a[kb][4 * i4 + c] = x[c];
+            }
+        // which of this lane's ACC output rows are written (only rows solved in the dual form)
+        bool keep[ACC];
+#pragma unroll
+        for (int v = 0; v < ACC; ++v) {
+            const int64_t r = base + acc_row<D>(v, lane);
+            keep[v] = r < r1;
+            if (keep[v] && indptr) {
+                const int64_t k = indptr[r + 1] - indptr[r];
+                keep[v] = k > 0 && k <= k_max;
+            }
         }
-        __syncthreads();
-        for (int sub = rg; sub < NSUB; sub += RG) {
+#pragma unroll
+        for (int J = 0; J < NB; ++J) {
             acc_t acc;
 #pragma unroll
             for (int v = 0; v < ACC; ++v) acc[v] = 0.f;
 #pragma unroll
-            for (int s = 0; s < NS; ++s) acc = mfma<D>(At[(sub * TM + m) * LD + KS * s + kq], breg[s], acc);
+            for (int kb = 0; kb < NB; ++kb) {
+                if (UPPER ? (kb <= J) : (kb >= J)) {  // compile-time after unrolling
+                    const float *bp = MT + (TM * J + m) * MLD + TM * kb + BW * kq;
 #pragma unroll
-            for (int v = 0; v < ACC; ++v) {
-                const int64_t r = base + sub * TM + acc_row<D>(v, lane);
-                bool keep = r < r1;
-                if (keep && indptr) {  // only rows solved in the dual form (0 < k <= k_max) are rewritten
-                    const int64_t k = indptr[r + 1] - indptr[r];
-                    keep = k > 0 && k <= k_max;
+                    for (int i4 = 0; i4 < BW / 4; ++i4) {
+                        const float4 b = *(const float4 *)(bp + 4 * i4);
+                        acc = mfma<D>(a[kb][4 * i4 + 0], b.x, acc);
+                        acc = mfma<D>(a[kb][4 * i4 + 1], b.y, acc);
+                        acc = mfma<D>(a[kb][4 * i4 + 2], b.z, acc);
+                        acc = mfma<D>(a[kb][4 * i4 + 3], b.w, acc);
+                    }
                 }
-                if (keep) store_elem<OUT_BF16>(Out, r * ldo + TM * J + m, acc[v]);
             }
+            // acc[v] = Out[base + acc_row(v)][TM*J + m]
+#pragma unroll
+            for (int v = 0; v < ACC; ++v)
+                if (keep[v]) store_elem<OUT_BF16>(Out, (base + acc_row<D>(v, lane)) * ldo + TM * J + m, acc[v]);
+            __builtin_amdgcn_sched_barrier(0);  // keep the next column tile's operand reads from piling up
         }
     }
 }
@@ -168,7 +201,8 @@ template <int D, int K, bool RG> struct DualCfg {
     static constexpr int ZLD = D + 4;
     static constexpr int SB_FLOATS = RPW * K * KP;
     static constexpr int ZB_FLOATS = ZBUF ? K * ZLD : 0;
-    static constexpr int TAIL = 64 + 128 + 4;             // tbuf[64], colbuf[2][64], ybuf[2][2]
+    static constexpr int TAIL = 64 + 128 + 4 + (RG ? 64 * (K / 16 > 1 ? K / 16 : 1) : 0);  // tbuf[64], colbuf[2][64],
+                                                                                          // ybuf[2][2], ids (RG)
     static constexpr int LDS_FLOATS = (SB_FLOATS > ZB_FLOATS ? SB_FLOATS : ZB_FLOATS) + TAIL;
 };
 
@@ -220,6 +254,9 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
         for (int t = 0; t < KT; ++t) {
             const int e = 16 * t + a;
             const int64_t idx = e < k[p] ? (int64_t)indices[b[p] + e] : -1;
+            if constexpr (RG) {
+                if (q == 0) ((int32_t *)(tb + 196))[p * K + e] = (int32_t)idx;  // kept for the second gather
+            }
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
                 if (idx >= 0) z[p][t][j] = *(const float4 *)(Z + idx * D + (4 * j + q) * 4);
@@ -383,17 +420,23 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
         for (int p = 0; p < RPW; ++p) {
             if (u[p] >= 0 && lane * CPL < D) {
                 float r0v = 0.f, r1v = 0.f;
-                const int32_t *ix = indices + b[p];
-#pragma unroll 8
-                for (int e = 0; e < k[p]; ++e) {
-                    const float te = tb[p * GW + e];
-                    const float *zr = Z + (int64_t)ix[e] * D + CPL * lane;
-                    if constexpr (CPL == 2) {
-                        const float2 zz = *(const float2 *)zr;
-                        r0v += te * zz.x;
-                        r1v += te * zz.y;
-                    } else {
-                        r0v += te * zr[0];
+                const int32_t *ix = (const int32_t *)(tb + 196) + p * K;
+                const int kp8 = (k[p] + 7) & ~7;  // padded entries have t = 0 and id -1 (row 0 is read instead)
+                for (int e0 = 0; e0 < kp8; e0 += 8) {
+                    float2 zz[8];
+                    float te[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int id = ix[e0 + i];
+                        te[i] = tb[p * GW + e0 + i];
+                        const float *zr = Z + (int64_t)(id < 0 ? 0 : id) * D + CPL * lane;
+                        if constexpr (CPL == 2) zz[i] = *(const float2 *)zr;
+                        else zz[i] = make_float2(zr[0], 0.f);
+                    }
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        r0v += te[i] * zz[i].x;
+                        r1v += te[i] * zz[i].y;
                     }
                 }
                 if constexpr (CPL == 2) *(float2 *)(R + u[p] * ldr + 2 * lane) = make_float2(r0v, r1v);
@@ -587,19 +630,33 @@ __global__ __launch_bounds__(64 * KT) void dual_big_kernel(const int64_t *__rest
     }
     __syncthreads();
     {
-        float accv = 0.f, rpiv = 0.f;
+        // unknown c belongs to thread c; a wavefront solves its 64 unknowns with wavefront-level steps
+        // (the value just found is read from its lane, no workgroup barrier), the highest chunk first,
+        // and the wavefronts below fold a finished chunk into their right-hand sides
+        constexpr int NW = (K + 63) / 64;
+        float accv = 0.f, rpiv = 0.f, tmine = 0.f;
         if (tid < K) {
             accv = ubuf[tid];
             rpiv = 1.0f / pbuf[tid];
-            if (tid >= k) tbuf[tid] = 0.f;
         }
-        for (int Rr = k - 1; Rr >= 0; --Rr) {
-            if (tid == Rr) tbuf[Rr] = accv * rpiv;
+        for (int chunk = NW - 1; chunk >= 0; --chunk) {
+            const int lo = 64 * chunk, hi = (k < lo + 64 ? k : lo + 64) - 1;
+            if (w == chunk) {
+#pragma unroll 4
+                for (int Rr = hi; Rr >= lo; --Rr) {
+                    const float tR = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(accv * rpiv), Rr - lo));
+                    tmine = tid == Rr ? tR : tmine;
+                    if (tid < Rr) accv -= mb[Rr * MLD + tid] * tR;
+                }
+                tbuf[tid] = tmine;  // zero for unknowns at or beyond k
+            }
             __syncthreads();
-            if (tid < Rr) accv -= mb[Rr * MLD + tid] * tbuf[Rr];
+            if (w < chunk) {
+#pragma unroll 4
+                for (int Rr = hi; Rr >= lo; --Rr) accv -= mb[Rr * MLD + tid] * tbuf[Rr];
+            }
         }
     }
-    __syncthreads();
 
     // ---- 4. r = Z_I^T t
     {
@@ -666,8 +723,10 @@ static als_status dual_prepare_typed(als_ctx *ctx, const als_table *V, const flo
     timer_begin(ctx, T_TRANSFORM, s);
     hipLaunchKernelGGL(factor_kernel<D>, dim3(1), dim3(256), factor_lds, s, G, prm->alpha, prm->lambda, Linv, LinvT,
                        err);
-    const unsigned tblocks = (unsigned)std::min<int64_t>(2048, std::max<int64_t>(1, (V->rows + 63) / 64));
-    hipLaunchKernelGGL((transform_kernel<D, BF16, false>), dim3(tblocks), dim3(256), 0, s, V->data, V->ld,
+    const unsigned tblocks = (unsigned)std::min<int64_t>(1024, std::max<int64_t>(1, (V->rows + 127) / 128));
+    ALS_HIP(ctx, hipFuncSetAttribute((const void *)transform_kernel<D, BF16, false, true>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)XfCfg<D>::LDS_BYTES));
+    hipLaunchKernelGGL((transform_kernel<D, BF16, false, true>), dim3(tblocks), dim3(256), XfCfg<D>::LDS_BYTES, s, V->data, V->ld,
                        ctx->ztable.p, (int64_t)D, (const float *)LinvT, (int64_t)0, V->rows,
                        (const int64_t *)nullptr, (int64_t)0);
     timer_end(ctx, s);
@@ -725,8 +784,10 @@ static als_status dual_rows_typed(als_ctx *ctx, const als_csr *Y, als_table *X, 
 #undef ALS_TIMED_CLASS
     if (stb != ALS_OK) return stb;
     timer_begin(ctx, T_TRANSFORM, s);
-    const unsigned xblocks = (unsigned)std::min<int64_t>(2048, std::max<int64_t>(1, (r1 - r0 + 63) / 64));
-    hipLaunchKernelGGL((transform_kernel<D, false, BF16>), dim3(xblocks), dim3(256), 0, s, (const void *)R, ldr,
+    const unsigned xblocks = (unsigned)std::min<int64_t>(1024, std::max<int64_t>(1, (r1 - r0 + 127) / 128));
+    ALS_HIP(ctx, hipFuncSetAttribute((const void *)transform_kernel<D, false, BF16, false>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)XfCfg<D>::LDS_BYTES));
+    hipLaunchKernelGGL((transform_kernel<D, false, BF16, false>), dim3(xblocks), dim3(256), XfCfg<D>::LDS_BYTES, s, (const void *)R, ldr,
                        X->data, X->ld, Linv, r0, r1, Y->indptr, (int64_t)dual_max);
     timer_end(ctx, s);
     ALS_HIP(ctx, hipGetLastError());

@@ -14,6 +14,8 @@
 // Rows longer than `split` are cut into segments (the counterpart of the paper's Section 4.3 row
 // splitting): each segment's partial statistics go to a workspace and a second kernel sums them
 // in a fixed order before the same factorisation.
+#include <type_traits>
+
 #include "als_internal.h"
 
 namespace als {
@@ -22,7 +24,7 @@ template <int D> struct Team {
     static constexpr int WAVES = Geo<D>::NC;      // one wavefront per tile-row
     static constexpr int THREADS = 64 * WAVES;
     static constexpr int LD = D + 1;              // LDS leading dimension (odd: conflict-free both ways)
-    static constexpr size_t LDS_BYTES = (size_t)(D * LD + 4 * D) * sizeof(float);
+    static constexpr size_t LDS_BYTES = (size_t)(D * LD + 6 * D + 8) * sizeof(float);
 };
 
 // ---------------------------------------------------------------------------------------------- accumulate
@@ -124,6 +126,131 @@ __device__ __forceinline__ void cholesky_solve_lds(float *a, float *aux, int32_t
     }
 }
 
+// ---------------------------------------------------------------------------------------------- register solve
+template <int B, int E, class F> __device__ __forceinline__ void static_for_p(F &&f) {
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for_p<B + 1, E>(f);
+    }
+}
+
+// Same system as cholesky_solve_lds, for D >= 64 with 2*D <= blockDim threads: the matrix lives in
+// registers.  Thread (R = tid % D, h = tid / D) holds the CW = D/2 columns [CW*h, CW*h + CW) of row R.
+// Elimination A = M P M^T (M unit lower, P the pivots) one column per step: the owners publish the
+// column in LDS (double-buffered by step parity), one workgroup barrier, every thread reads the pivot
+// and the column back with broadcast reads and updates its registers; u = M^{-1} b rides along.  The
+// back-substitution gives unknown c to thread c and works through it 64 unknowns at a time with
+// wavefront-level steps (factor read transposed from LDS).  On entry a[c*LD + r] holds entry (r, c)
+// (full matrix) and aux + 3*D the right-hand side; on exit aux + 2*D holds the solution.
+template <int D>
+__device__ __forceinline__ void solve_rowsplit(float *a, float *aux, int32_t *err_flag) {
+    constexpr int LD = Team<D>::LD, CW = D / 2, NG = D / 4;
+    float *xout = aux + 2 * D, *bvec = aux + 3 * D, *colbuf = aux + 4 * D, *yb = aux + 6 * D;
+    float *pbuf = aux, *ubuf = aux + D;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const bool active = tid < 2 * D;
+    const int R = tid % D, h = active ? tid / D : 0;  // h is uniform inside a wavefront (D >= 64)
+    float s[CW];
+#pragma unroll
+    for (int i = 0; i < CW; ++i) s[i] = a[(CW * h + i) * LD + R];
+    float yv = bvec[R], mypiv = 1.f;
+    bool bad = false;
+    static_for_p<0, NG>([&](auto gg) {
+        constexpr int g = decltype(gg)::value;
+        constexpr int ho = (4 * g) / CW, lb = 4 * g - CW * ho;  // owner half and local index of the group
+#pragma unroll 1
+        for (int v = 0; v < 4; ++v) {
+            const int c = 4 * g + v;
+            float *cb = colbuf + (c & 1) * D;
+            if (active && h == ho) {
+                const float mine = v == 0 ? s[lb] : (v == 1 ? s[lb + 1] : (v == 2 ? s[lb + 2] : s[lb + 3]));
+                cb[R] = mine;  // entry (R, c) as it stands (column c is final)
+                if (R == c) yb[c & 1] = yv;
+            }
+            __syncthreads();
+            if (active && h >= ho) {
+                const float pivot = cb[c];
+                const float uc = yb[c & 1];
+                const float mine = cb[R];
+                bad |= !(pivot > 0.f);
+                float rp = __builtin_amdgcn_rcpf(pivot);
+                rp = rp * (2.f - pivot * rp);  // one Newton step on the hardware reciprocal
+                mypiv = R == c ? pivot : mypiv;
+                const float f = R > c ? mine * rp : 0.f;  // M[R][c]; rows above stay as they are
+                if (h == ho) yv -= f * uc;                 // the owner half carries the right-hand side
+                if (h == ho) {
+                    static_for_p<lb / 4, CW / 4>([&](auto ii) {
+                        constexpr int i4 = decltype(ii)::value;
+                        const float4 col = *(const float4 *)(cb + CW * ho + 4 * i4);
+                        if constexpr (i4 == lb / 4) {  // the group's own columns: only those right of c
+                            if (0 > v) s[4 * i4 + 0] -= f * col.x;
+                            if (1 > v) s[4 * i4 + 1] -= f * col.y;
+                            if (2 > v) s[4 * i4 + 2] -= f * col.z;
+                            if (3 > v) s[4 * i4 + 3] -= f * col.w;
+                        } else {
+                            s[4 * i4 + 0] -= f * col.x; s[4 * i4 + 1] -= f * col.y;
+                            s[4 * i4 + 2] -= f * col.z; s[4 * i4 + 3] -= f * col.w;
+                        }
+                    });
+                } else {  // h > ho: every column of this half lies right of c
+                    yv -= f * uc;
+#pragma unroll
+                    for (int i4 = 0; i4 < CW / 4; ++i4) {
+                        const float4 col = *(const float4 *)(cb + CW * h + 4 * i4);
+                        s[4 * i4 + 0] -= f * col.x; s[4 * i4 + 1] -= f * col.y;
+                        s[4 * i4 + 2] -= f * col.z; s[4 * i4 + 3] -= f * col.w;
+                    }
+                }
+            }
+        }
+    });
+    if (bad && tid == 0) atomicOr(err_flag, 1);
+    // factor back to LDS (same places: a[c*LD + R] = entry (R, c)), pivots and u for the owners of the unknowns
+    if (active) {
+#pragma unroll
+        for (int i = 0; i < CW; ++i) a[(CW * h + i) * LD + R] = s[i];
+        if (h == 1) {  // the second half saw every column, so its copy of u is complete
+            ubuf[R] = yv;
+            pbuf[R] = mypiv;
+        }
+    }
+    __syncthreads();
+    {
+        constexpr int NW = D / 64;
+        float accv = 0.f, rpiv = 0.f, tmine = 0.f;
+        if (tid < D) {
+            accv = ubuf[tid];
+            rpiv = 1.0f / pbuf[tid];
+        }
+        for (int chunk = NW - 1; chunk >= 0; --chunk) {
+            const int lo = 64 * chunk;
+            if (w == chunk) {
+#pragma unroll 4
+                for (int Rr = lo + 63; Rr >= lo; --Rr) {
+                    const float tR = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(accv * rpiv), Rr - lo));
+                    tmine = tid == Rr ? tR : tmine;
+                    if (tid < Rr) accv -= a[tid * LD + Rr] * tR;  // entry (Rr, tid)
+                }
+                xout[tid] = tmine;
+            }
+            __syncthreads();
+            if (w < chunk) {
+#pragma unroll 4
+                for (int Rr = lo + 63; Rr >= lo; --Rr) accv -= a[tid * LD + Rr] * xout[Rr];
+            }
+        }
+    }
+    (void)lane;
+}
+
+template <int D> __device__ __forceinline__ void solve_spd_lds(float *a, float *aux, int32_t *err_flag) {
+    if constexpr (D >= 64) {
+        solve_rowsplit<D>(a, aux, err_flag);
+    } else {
+        cholesky_solve_lds<D>(a, aux, err_flag);
+    }
+}
+
 // ---------------------------------------------------------------------------------------------- kernels
 enum PrimalMode { MODE_FUSED = 0, MODE_SEGMENT = 1 };
 
@@ -131,7 +258,7 @@ enum PrimalMode { MODE_FUSED = 0, MODE_SEGMENT = 1 };
 // MODE_SEGMENT: work item = segment `item` of segs[]; raw partial statistics are written to
 //               partials[item][D*D + D] (row-major D x D, then b).
 template <int D, bool BF16, int MODE>
-__global__ __launch_bounds__(Team<D>::THREADS) void primal_kernel(
+__global__ __launch_bounds__(Team<D>::THREADS, 2) void primal_kernel(
     const int64_t *__restrict__ indptr, const int32_t *__restrict__ indices, const float *__restrict__ values,
     const void *__restrict__ V, int64_t ldv, const float *__restrict__ G, float alpha, float lambda,
     void *__restrict__ X, int64_t ldx, int64_t row_begin, const int32_t *__restrict__ row_list,
@@ -195,7 +322,7 @@ __global__ __launch_bounds__(Team<D>::THREADS) void primal_kernel(
             for (int j = 0; j < NC; ++j) bvec[NC * m + j] = bsum[j];
         }
         __syncthreads();
-        cholesky_solve_lds<D>(a, aux, err_flag);
+        solve_spd_lds<D>(a, aux, err_flag);
         const float *xout = aux + 2 * D;
         for (int c = threadIdx.x; c < D; c += Team<D>::THREADS) store_elem<BF16>(X, u * ldx + c, xout[c]);
     }
@@ -242,7 +369,7 @@ __global__ __launch_bounds__(Team<D>::THREADS) void reduce_solve_kernel(
         }
     }
     __syncthreads();
-    cholesky_solve_lds<D>(a, aux, err_flag);
+    solve_spd_lds<D>(a, aux, err_flag);
     const float *xout = aux + 2 * D;
     for (int c = threadIdx.x; c < D; c += T) store_elem<BF16>(X, lr.row * ldx + c, xout[c]);
 }

@@ -20,6 +20,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# HBM bytes per launch measured with rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by the copy-probe factors);
+# source: profiles/c3_epoch_hbm_traffic.md.  Keyed by (workload, kernel as named in the roofline object).
+MEASURED_TRAFFIC_BYTES = {
+    ("c3", "dual_rows_kernel<128, 32>"): 25.27e9,
+    ("c3", "dual_rows_kernel<128, 16>"): 24.92e9,
+}
 HBM_PEAK_GBS = 8000.0
 MFMA_F32_PEAK_TFLOPS = 157.3
 
@@ -197,6 +203,8 @@ def main():
         ach = work / (dom_ms * 1e-3) / 1e12
         roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": ach / MFMA_F32_PEAK_TFLOPS, "traffic": None}
+    if not args.rows:
+        roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((args.workload, dom))
     roof["avg_launch_ms"] = dom_ms
     roof["launches"] = dom_launches
     roof["share_of_epoch"] = dom_ms_total / nsteps / ms_per_step

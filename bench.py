@@ -180,7 +180,7 @@ def main():
     for c in range(8):
         ms, launches = stage_ms.get(f"dual_k{16 * (c + 1)}", 0.0), stage_ms.get(f"launches_k{16 * (c + 1)}", 0.0)
         if launches > 0:
-            kname = (f"dual_rows_kernel<{d}, {16 * (c + 1)}>" if c < 4 else f"dual_big_kernel<{d}, {c + 1}>")
+            kname = (f"dual_rows_kernel<{d}, {16 * (c + 1)}>" if c < 4 else f"dual_wide_kernel<{d}, {c + 1}>")
             per_launch = nsteps * (cls_nnz[c] * (4 * d + 4) + cls_rows[c] * (4 * d + 12)) / launches
             cand[kname] = (ms, launches, "hbm", per_launch)
     if stage_ms.get("primal", 0) > 0:

@@ -1,5 +1,6 @@
 // C-ABI entry points of libals: argument validation, context and workspace management, and the
 // epoch / loss glue.  All arithmetic of the method lives in the kernel translation units.
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -47,6 +48,18 @@ void timer_begin(als_ctx *ctx, int slot, hipStream_t s) {
 void timer_end(als_ctx *ctx, hipStream_t s) {
     if (!ctx->timing || ctx->timers.empty()) return;
     (void)hipEventRecord(ctx->timers.back().e1, s);
+}
+
+als_status side_fork(als_ctx *ctx, hipStream_t s) {
+    ALS_HIP(ctx, hipEventRecord(ctx->fork_ev, s));
+    for (int i = 0; i < 3; ++i) ALS_HIP(ctx, hipStreamWaitEvent(ctx->side[i], ctx->fork_ev, 0));
+    return ALS_OK;
+}
+
+als_status side_join(als_ctx *ctx, int i, hipStream_t s) {
+    ALS_HIP(ctx, hipEventRecord(ctx->join_ev[i], ctx->side[i]));
+    ALS_HIP(ctx, hipStreamWaitEvent(s, ctx->join_ev[i], 0));
+    return ALS_OK;
 }
 
 static void timers_reset(als_ctx *ctx) {
@@ -141,6 +154,14 @@ als_status als_create(als_ctx **out, int device) {
     if (st == ALS_OK && hipHostMalloc((void **)&ctx->host_counters, 16 * sizeof(int32_t)) != hipSuccess) st = ALS_ENOMEM;
     if (st == ALS_OK && hipHostMalloc((void **)&ctx->host_scalar, 2 * sizeof(double)) != hipSuccess) st = ALS_ENOMEM;
     if (st == ALS_OK && hipMemset(ctx->small.p, 0, ctx->small.bytes) != hipSuccess) st = ALS_EHIP;
+    for (int i = 0; i < 3 && st == ALS_OK; ++i) {
+        if (hipStreamCreateWithFlags(&ctx->side[i], hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&ctx->join_ev[i], hipEventDisableTiming) != hipSuccess)
+            st = ALS_EHIP;
+    }
+    if (st == ALS_OK && hipEventCreateWithFlags(&ctx->fork_ev, hipEventDisableTiming) != hipSuccess) st = ALS_EHIP;
+    // opt-in: measured no gain on MI355X (the row kernels are instruction-issue bound, not latency bound)
+    if (const char *e = getenv("ALS_SIDE_STREAMS")) ctx->use_side_streams = atoi(e) != 0;
     if (st != ALS_OK) {
         als_destroy(ctx);
         return st;
@@ -157,6 +178,11 @@ als_status als_destroy(als_ctx *ctx) {
                       &ctx->loss_partials, &ctx->gram_w, &ctx->gram_h};
     for (DevBuf *b : bufs)
         if (b->p) (void)hipFree(b->p);
+    for (int i = 0; i < 3; ++i) {
+        if (ctx->side[i]) (void)hipStreamDestroy(ctx->side[i]);
+        if (ctx->join_ev[i]) (void)hipEventDestroy(ctx->join_ev[i]);
+    }
+    if (ctx->fork_ev) (void)hipEventDestroy(ctx->fork_ev);
     if (ctx->host_counters) (void)hipHostFree(ctx->host_counters);
     if (ctx->host_scalar) (void)hipHostFree(ctx->host_scalar);
     for (auto &t : ctx->timers) { (void)hipEventDestroy(t.e0); (void)hipEventDestroy(t.e1); }

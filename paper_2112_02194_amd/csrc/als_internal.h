@@ -142,6 +142,10 @@ struct als_ctx {
     als::DevBuf gram_w, gram_h; // fp32 [d*d] Gramians used by als_epoch / als_loss
     int32_t *host_counters = nullptr;  // pinned, 16 ints
     double *host_scalar = nullptr;     // pinned, 2 doubles
+    // side streams (default priority) on which kernels of independent row classes run concurrently
+    hipStream_t side[3] = {nullptr, nullptr, nullptr};
+    hipEvent_t fork_ev = nullptr, join_ev[3] = {nullptr, nullptr, nullptr};
+    bool use_side_streams = false;
     bool timing = false;
     std::vector<als::Timer> timers;
     std::vector<als::Timer> free_timers;
@@ -168,6 +172,9 @@ als_status fail(als_ctx *ctx, als_status st, const std::string &msg);
 als_status ensure(als_ctx *ctx, DevBuf &b, size_t bytes);
 void timer_begin(als_ctx *ctx, int slot, hipStream_t s);
 void timer_end(als_ctx *ctx, hipStream_t s);
+// Make side stream i wait for everything enqueued on `s` so far / make `s` wait for side stream i.
+als_status side_fork(als_ctx *ctx, hipStream_t s);
+als_status side_join(als_ctx *ctx, int i, hipStream_t s);
 
 #define ALS_HIP(ctx, expr)                                                                      \
     do {                                                                                        \

@@ -13,6 +13,8 @@
 //   dual_rows_kernel  one wavefront per 4 / 2 / 1 rows (k <= 16 / 32 / 64): gather Z_I straight into
 //                     MFMA operand registers, S = I + Z_I Z_I^T on the matrix cores, Cholesky + two
 //                     triangular solves with one lane per row of S, then r = Z_I^T t
+//   dual_wide_kernel  one wavefront per row with 64 < k <= 128 (d = 128 only): S tile by tile into a
+//                     packed triangle in LDS, elimination with two rows of S per lane
 //   transform_kernel  X = R L^{-1}   (rows r -> L^{-T} r), rounding to the table's element type
 #include <cstdlib>
 #include <type_traits>
@@ -497,186 +499,198 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
 }
 
 // ---------------------------------------------------------------------------------------------- dual rows, 64 < k <= 128
-// One workgroup of KT wavefronts per row (k <= K = 16*KT).  Wavefront w owns rows R = 16w + a of S;
-// lane (a, q) keeps S[R][c] for the columns c = 16*t2 + 4q + v (t2 <= w, v < 4) in acc[t2][v], which
-// is exactly where v_mfma_f32_16x16x4 leaves them when tile t2 is the A operand and the wavefront's
-// own tile the B operand (S is symmetric), so S never moves between the MFMA and the factorisation.
-//   1. every wavefront gathers its 16 entries into registers and into LDS; S tiles from LDS (A) and
-//      registers (B);
-//   2. right-looking elimination S = M D M^T (M unit lower, D the pivots), one column per step: the
-//      owners publish the column in LDS, one workgroup barrier, everybody updates; the forward
-//      substitution u = M^{-1} y rides along;
-//   3. M^T t = D^{-1} u column by column with one thread per unknown (factor read back transposed
-//      from LDS);
-//   4. r = Z_I^T t: per wavefront a cross-lane reduction of its 16 entries, then a sum over wavefronts.
-template <int D, int KT> struct BigCfg {
-    static constexpr int K = 16 * KT, ZLD = D + 4, MLD = K + 1;
-    static constexpr int MAIN = K * ZLD > K * MLD ? K * ZLD : K * MLD;  // zb, later the transposed factor
-    static constexpr int OFF_COL = MAIN;                                // colbuf[2][K]
-    static constexpr int OFF_Y = OFF_COL + 2 * K;                       // ybuf[4]
-    static constexpr int OFF_U = OFF_Y + 4;                             // ubuf[K]
-    static constexpr int OFF_P = OFF_U + K;                             // pbuf[K]
-    static constexpr int OFF_T = OFF_P + K;                             // tbuf[K]
-    static constexpr int OFF_R = OFF_T + K;                             // rbuf[KT][D]
-    static constexpr int LDS_FLOATS = OFF_R + KT * D;
+// One wavefront per row with k <= K = 16*KT entries (KT = 5..8).
+//   1. S = I + Z_I Z_I^T tile by tile: the wavefront keeps the 16 entries of tile t1 in registers (B
+//      operand) and streams the tiles t2 <= t1 past them (A operand, fetched again from the caches);
+//      each finished 16x16 tile goes to LDS, where S is kept as a packed lower triangle.
+//   2. Elimination S = M P M^T with lane i owning rows i and 64+i (columns 0..63 of the first, all of
+//      the second, in registers): per step the column is published in LDS and read back by broadcast,
+//      pivot and right-hand-side entry come straight from the owning lane; u = M^{-1} y rides along.
+//   3. Back-substitution with the factor read transposed from LDS, the value just found taken from
+//      its lane.
+//   4. r = Z_I^T t with one lane per pair of output columns, gathering the entries a second time.
+template <int D, int KT> struct WideCfg {
+    static constexpr int K = 16 * KT;
+    static constexpr int TRI = K * (K + 1) / 2;      // packed lower triangle
+    static constexpr int OFF_COL = TRI;              // colbuf[2][K]
+    static constexpr int OFF_T = OFF_COL + 2 * K;    // tbuf[K]
+    static constexpr int OFF_ID = OFF_T + K;         // ids[K]
+    static constexpr int LDS_FLOATS = OFF_ID + K;
 };
 
 template <int D, int KT>
-__global__ __launch_bounds__(64 * KT) void dual_big_kernel(const int64_t *__restrict__ indptr,
-                                                           const int32_t *__restrict__ indices,
-                                                           const float *__restrict__ values,
-                                                           const float *__restrict__ Z, float *__restrict__ R,
-                                                           int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
-                                                           int32_t *__restrict__ err_flag) {
-    using C = BigCfg<D, KT>;
-    constexpr int K = C::K, NJ = D / 16, ZLD = C::ZLD, MLD = C::MLD;
+__global__ __launch_bounds__(64) void dual_wide_kernel(const int64_t *__restrict__ indptr,
+                                                       const int32_t *__restrict__ indices,
+                                                       const float *__restrict__ values,
+                                                       const float *__restrict__ Z, float *__restrict__ R,
+                                                       int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
+                                                       int32_t *__restrict__ err_flag) {
+    using C = WideCfg<D, KT>;
+    constexpr int K = C::K, NJ = D / 16, K1 = K - 64;  // K1 = rows held as "second row" of a lane
     extern __shared__ float lds[];
-    float *zb = lds, *mb = lds, *colbuf = lds + C::OFF_COL, *ybuf = lds + C::OFF_Y, *ubuf = lds + C::OFF_U,
-          *pbuf = lds + C::OFF_P, *tbuf = lds + C::OFF_T, *rbuf = lds + C::OFF_R;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int a = lane & 15, q = lane >> 4;
-    const int myR = 16 * w + a;
+    float *tri = lds, *colbuf = lds + C::OFF_COL, *tbuf = lds + C::OFF_T;
+    int32_t *ids = (int32_t *)(lds + C::OFF_ID);
+    const int lane = threadIdx.x, a = lane & 15, q = lane >> 4;
     const int64_t u = r0 + list[blockIdx.x];
     const int64_t b = indptr[u];
     const int k = (int)(indptr[u + 1] - b);  // <= K by the list's class
 
-    // ---- 1. gather, S rows
-    float4 z[NJ];
-    {
-        const int64_t idx = myR < k ? (int64_t)indices[b + myR] : -1;
+    // ---- 1. S tiles
+    int32_t myid[KT];
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+        const int e = 16 * t + a;
+        myid[t] = e < k ? indices[b + e] : -1;
+        if (q == 0) ids[e] = myid[t];
+    }
+    // the first RT tiles stay in registers for the whole phase (one round of loads, all in flight
+    // together); later tiles are fetched when they are needed
+    constexpr int RT = KT < 5 ? KT : 5;
+    float4 zres[RT][NJ];
+#pragma unroll
+    for (int t = 0; t < RT; ++t)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+            zres[t][j] = myid[t] >= 0 ? *(const float4 *)(Z + (int64_t)myid[t] * D + (4 * j + q) * 4)
+                                      : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int t1 = 0; t1 < KT; ++t1) {
+        float4 zb[NJ];
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
-            z[j] = idx >= 0 ? *(const float4 *)(Z + idx * D + (4 * j + q) * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
-            *(float4 *)(zb + myR * ZLD + (4 * j + q) * 4) = z[j];
+            if (t1 < RT) zb[j] = zres[t1 < RT ? t1 : 0][j];
+            else zb[j] = myid[t1] >= 0 ? *(const float4 *)(Z + (int64_t)myid[t1] * D + (4 * j + q) * 4)
+                                       : make_float4(0.f, 0.f, 0.f, 0.f);
         }
-    }
-    float yv = 0.f;  // every lane of row R carries y_R, later u_R
-    if (myR < k) yv = values ? values[b + myR] : 1.f;
-    __syncthreads();
-    floatx4 acc[KT];
 #pragma unroll
-    for (int t2 = 0; t2 < KT; ++t2) {
-        acc[t2] = floatx4{0.f, 0.f, 0.f, 0.f};
-        if (t2 <= w) {
+        for (int t2 = 0; t2 <= t1; ++t2) {
+            floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
-                const float4 za = *(const float4 *)(zb + (16 * t2 + a) * ZLD + (4 * j + q) * 4);
-                acc[t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(za.x, z[j].x, acc[t2], 0, 0, 0);
-                acc[t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(za.y, z[j].y, acc[t2], 0, 0, 0);
-                acc[t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(za.z, z[j].z, acc[t2], 0, 0, 0);
-                acc[t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(za.w, z[j].w, acc[t2], 0, 0, 0);
+                float4 za;
+                if (t2 == t1) za = zb[j];
+                else if (t2 < RT) za = zres[t2 < RT ? t2 : 0][j];
+                else za = myid[t2] >= 0 ? *(const float4 *)(Z + (int64_t)myid[t2] * D + (4 * j + q) * 4)
+                                        : make_float4(0.f, 0.f, 0.f, 0.f);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(za.x, zb[j].x, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(za.y, zb[j].y, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(za.z, zb[j].z, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(za.w, zb[j].w, acc, 0, 0, 0);
             }
-            if (t2 == w) {
+            // acc[v] = S[Rr][c], Rr = 16*t1 + a, c = 16*t2 + 4q + v (S is symmetric); keep c <= Rr
+            const int Rr = 16 * t1 + a;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) acc[t2][v] += (4 * q + v == a) ? 1.f : 0.f;  // S = I + Z Z^T
+            for (int v = 0; v < 4; ++v) {
+                const int c = 16 * t2 + 4 * q + v;
+                if (c <= Rr) tri[Rr * (Rr + 1) / 2 + c] = acc[v] + (c == Rr ? 1.f : 0.f);
             }
         }
     }
-    __syncthreads();  // zb is dead from here on (its space becomes mb in step 3)
+    wave_sync();
 
-    // ---- 2. elimination with the forward substitution riding along
-    float mypiv = 1.f;
+    // ---- 2. elimination; lane i owns rows i (columns 0..63) and 64+i (all columns, if 64+i < K)
+    const int ra = lane, rb = 64 + lane;
+    const bool hasb = rb < K;
+    float s0[64], s1[K];
+#pragma unroll
+    for (int c = 0; c < 64; ++c) s0[c] = c <= ra ? tri[ra * (ra + 1) / 2 + c] : 0.f;
+#pragma unroll
+    for (int c = 0; c < K; ++c) s1[c] = (hasb && c <= rb) ? tri[rb * (rb + 1) / 2 + c] : 0.f;
+    float y0 = 0.f, y1 = 0.f;
+    if (ra < k) y0 = values ? values[b + ra] : 1.f;
+    if (rb < k) y1 = values ? values[b + rb] : 1.f;
+    float rp0 = 1.f, rp1 = 1.f;
     bool bad = false;
+    wave_sync();
     static_for<0, K>([&](auto cc) {
         constexpr int c = decltype(cc)::value;
-        constexpr int tc = c / 16, qc = (c % 16) / 4, vc = c % 4;
         if (c < k) {  // the remaining rows are identity rows with zero right-hand side
-            float *buf = colbuf + (c & 1) * K;
-            if (w >= tc) {
-                if (q == qc) buf[myR] = acc[tc][vc];  // S'[R][c] as it stands (column c is final)
-                if (myR == c && q == qc) ybuf[c & 1] = yv;
+            float *cb = colbuf + (c & 1) * K;
+            float pivot, uc;
+            if constexpr (c < 64) {
+                cb[lane] = s0[c];
+                if (hasb) cb[64 + lane] = s1[c];
+                pivot = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s0[c]), c));
+                uc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(y0), c));
+            } else {
+                if (hasb) cb[64 + lane] = s1[c];
+                pivot = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s1[c]), c - 64));
+                uc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(y1), c - 64));
             }
-            __syncthreads();
-            if (w >= tc) {
-                const float pivot = buf[c];
-                const float uc = ybuf[c & 1];
-                bad |= !(pivot > 0.f);
-                float rp = __builtin_amdgcn_rcpf(pivot);
-                rp = rp * (2.f - pivot * rp);  // one Newton step on the hardware reciprocal
-                mypiv = myR == c ? pivot : mypiv;
-                const float f = myR > c ? buf[myR] * rp : 0.f;  // M[R][c]; rows above stay as they are
-                yv -= f * uc;
-#pragma unroll
-                for (int t2 = tc; t2 < KT; ++t2) {
-                    if (t2 <= w) {
-                        const float4 col = *(const float4 *)(buf + 16 * t2 + 4 * q);
-                        if (t2 == tc) {  // same tile as column c: only columns right of c change
-                            if (4 * q + 0 > 4 * qc + vc) acc[t2][0] -= f * col.x;
-                            if (4 * q + 1 > 4 * qc + vc) acc[t2][1] -= f * col.y;
-                            if (4 * q + 2 > 4 * qc + vc) acc[t2][2] -= f * col.z;
-                            if (4 * q + 3 > 4 * qc + vc) acc[t2][3] -= f * col.w;
-                        } else {
-                            acc[t2][0] -= f * col.x; acc[t2][1] -= f * col.y;
-                            acc[t2][2] -= f * col.z; acc[t2][3] -= f * col.w;
-                        }
-                    }
-                }
+            bad |= !(pivot > 0.f);
+            float rp = __builtin_amdgcn_rcpf(pivot);
+            rp = rp * (2.f - pivot * rp);  // one Newton step on the hardware reciprocal
+            float f0 = 0.f;
+            if constexpr (c < 64) {
+                rp0 = ra == c ? rp : rp0;
+                f0 = ra > c ? s0[c] * rp : 0.f;
+                y0 -= f0 * uc;
             }
+            rp1 = rb == c ? rp : rp1;
+            const float f1 = rb > c ? s1[c] * rp : 0.f;  // lanes without a second row hold zeros in s1
+            y1 -= f1 * uc;
+            wave_sync();
+            static_for<(c + 1) / 4, K / 4>([&](auto jj) {
+                constexpr int j4 = decltype(jj)::value;
+                const float4 col = *(const float4 *)(cb + 4 * j4);
+                if constexpr (4 * j4 + 0 > c) { if constexpr (4 * j4 + 0 < 64 && c < 64) s0[4 * j4 + 0] -= f0 * col.x; s1[4 * j4 + 0] -= f1 * col.x; }
+                if constexpr (4 * j4 + 1 > c) { if constexpr (4 * j4 + 1 < 64 && c < 64) s0[4 * j4 + 1] -= f0 * col.y; s1[4 * j4 + 1] -= f1 * col.y; }
+                if constexpr (4 * j4 + 2 > c) { if constexpr (4 * j4 + 2 < 64 && c < 64) s0[4 * j4 + 2] -= f0 * col.z; s1[4 * j4 + 2] -= f1 * col.z; }
+                if constexpr (4 * j4 + 3 > c) { if constexpr (4 * j4 + 3 < 64 && c < 64) s0[4 * j4 + 3] -= f0 * col.w; s1[4 * j4 + 3] -= f1 * col.w; }
+            });
         }
     });
-    if (bad && tid == 0) atomicOr(err_flag, 1);
+    if (bad && lane == 0) atomicOr(err_flag, 1);
 
-    // ---- 3. back substitution: t_c = (u_c - sum_{R>c} S'[R][c] t_R) / pivot_c, one thread per c
+    // ---- 3. t_c = (u_c - sum_{Rr>c} S'[Rr][c] t_Rr) / pivot_c; the factor goes back to the packed triangle
 #pragma unroll
-    for (int t2 = 0; t2 < KT; ++t2) {
-        if (t2 <= w) {
+    for (int c = 0; c < 64; ++c)
+        if (c <= ra) tri[ra * (ra + 1) / 2 + c] = s0[c];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) mb[myR * MLD + 16 * t2 + 4 * q + v] = acc[t2][v];
-        }
-    }
-    if (q == 0) {
-        ubuf[myR] = yv;
-        pbuf[myR] = mypiv;
-    }
-    __syncthreads();
+    for (int c = 0; c < K; ++c)
+        if (hasb && c <= rb) tri[rb * (rb + 1) / 2 + c] = s1[c];
+    wave_sync();
     {
-        // unknown c belongs to thread c; a wavefront solves its 64 unknowns with wavefront-level steps
-        // (the value just found is read from its lane, no workgroup barrier), the highest chunk first,
-        // and the wavefronts below fold a finished chunk into their right-hand sides
-        constexpr int NW = (K + 63) / 64;
-        float accv = 0.f, rpiv = 0.f, tmine = 0.f;
-        if (tid < K) {
-            accv = ubuf[tid];
-            rpiv = 1.0f / pbuf[tid];
-        }
-        for (int chunk = NW - 1; chunk >= 0; --chunk) {
-            const int lo = 64 * chunk, hi = (k < lo + 64 ? k : lo + 64) - 1;
-            if (w == chunk) {
+        float t0 = 0.f, t1v = 0.f;
 #pragma unroll 4
-                for (int Rr = hi; Rr >= lo; --Rr) {
-                    const float tR = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(accv * rpiv), Rr - lo));
-                    tmine = tid == Rr ? tR : tmine;
-                    if (tid < Rr) accv -= mb[Rr * MLD + tid] * tR;
-                }
-                tbuf[tid] = tmine;  // zero for unknowns at or beyond k
-            }
-            __syncthreads();
-            if (w < chunk) {
-#pragma unroll 4
-                for (int Rr = hi; Rr >= lo; --Rr) accv -= mb[Rr * MLD + tid] * tbuf[Rr];
-            }
+        for (int Rr = (k < K ? k : K) - 1; Rr >= 64; --Rr) {
+            const float tR = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(y1 * rp1), Rr - 64));
+            t1v = rb == Rr ? tR : t1v;
+            const int base = Rr * (Rr + 1) / 2;
+            if (rb < Rr) y1 -= tri[base + rb] * tR;
+            y0 -= tri[base + ra] * tR;
         }
+#pragma unroll 4
+        for (int Rr = (k < 64 ? k : 64) - 1; Rr >= 0; --Rr) {
+            const float tR = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(y0 * rp0), Rr));
+            t0 = ra == Rr ? tR : t0;
+            if (ra < Rr) y0 -= tri[Rr * (Rr + 1) / 2 + ra] * tR;
+        }
+        tbuf[ra] = t0;
+        if (hasb) tbuf[rb] = t1v;
     }
+    wave_sync();
 
-    // ---- 4. r = Z_I^T t
+    // ---- 4. r = Z_I^T t, one lane per pair of output columns (second gather of the row's entries)
     {
-        const float te = tbuf[myR];
+        float r0v = 0.f, r1v = 0.f;
+        const int kp8 = (k + 7) & ~7;  // padded entries have t = 0 and id -1 (row 0 is read instead)
+        for (int e0 = 0; e0 < kp8; e0 += 8) {
+            float2 zz[8];
+            float te[8];
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-            float4 v = make_float4(te * z[j].x, te * z[j].y, te * z[j].z, te * z[j].w);
-            v.x = add_row_ror<8>(v.x); v.y = add_row_ror<8>(v.y); v.z = add_row_ror<8>(v.z); v.w = add_row_ror<8>(v.w);
-            v.x = add_row_ror<4>(v.x); v.y = add_row_ror<4>(v.y); v.z = add_row_ror<4>(v.z); v.w = add_row_ror<4>(v.w);
-            v.x = add_row_ror<2>(v.x); v.y = add_row_ror<2>(v.y); v.z = add_row_ror<2>(v.z); v.w = add_row_ror<2>(v.w);
-            v.x = add_row_ror<1>(v.x); v.y = add_row_ror<1>(v.y); v.z = add_row_ror<1>(v.z); v.w = add_row_ror<1>(v.w);
-            if (a == j) *(float4 *)(rbuf + w * D + (4 * j + q) * 4) = v;
+            for (int i = 0; i < 8; ++i) {
+                const int id = ids[e0 + i];
+                te[i] = tbuf[e0 + i];
+                zz[i] = *(const float2 *)(Z + (int64_t)(id < 0 ? 0 : id) * D + 2 * lane);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                r0v += te[i] * zz[i].x;
+                r1v += te[i] * zz[i].y;
+            }
         }
-    }
-    __syncthreads();
-    if (tid < D) {
-        float r = 0.f;
-#pragma unroll
-        for (int ww = 0; ww < KT; ++ww) r += rbuf[ww * D + tid];
-        R[u * ldr + tid] = r;
+        *(float2 *)(R + u * ldr + 2 * lane) = make_float2(r0v, r1v);
     }
 }
 
@@ -740,11 +754,11 @@ static als_status launch_big_class(als_ctx *ctx, const als_csr *Y, const float *
                                    const int32_t *list, int count, int32_t *err, hipStream_t s) {
     if (count <= 0) return ALS_OK;
     if constexpr (D == 128) {
-        using C = BigCfg<D, KT>;
-        auto kern = dual_big_kernel<D, KT>;
+        using C = WideCfg<D, KT>;
+        auto kern = dual_wide_kernel<D, KT>;
         ALS_HIP(ctx, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                          (int)(C::LDS_FLOATS * sizeof(float))));
-        hipLaunchKernelGGL(kern, dim3((unsigned)count), dim3(64 * KT), C::LDS_FLOATS * sizeof(float), s, Y->indptr,
+        hipLaunchKernelGGL(kern, dim3((unsigned)count), dim3(64), C::LDS_FLOATS * sizeof(float), s, Y->indptr,
                            Y->indices, Y->values, Z, R, ldr, r0, list, err);
         return ALS_OK;
     } else {
@@ -766,22 +780,30 @@ static als_status dual_rows_typed(als_ctx *ctx, const als_csr *Y, als_table *X, 
     const float *Linv = (const float *)((char *)ctx->small.p + SM_FACTOR);
     int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
     const float *Z = (const float *)ctx->ztable.p;
+    // Independent classes run concurrently: the two largest on the caller's stream, 32 < k <= 64 on
+    // side stream 0, the workgroup kernels (k > 64) on side stream 1.  The caller has forked the side
+    // streams; they are joined before the closing transform, which reads every class's result.
     als_status stb = ALS_OK;
-#define ALS_TIMED_CLASS(cls, call)                  \
+    const bool side = ctx->use_side_streams;
+    hipStream_t s_mid = side ? ctx->side[0] : s, s_big = side ? ctx->side[1] : s;
+#define ALS_TIMED_CLASS(cls, strm, call)            \
     if (counts[cls] > 0 && stb == ALS_OK) {         \
-        timer_begin(ctx, T_DUAL_CLASS0 + cls, s);   \
+        hipStream_t cs = strm;                      \
+        timer_begin(ctx, T_DUAL_CLASS0 + cls, cs);  \
         call;                                       \
-        timer_end(ctx, s);                          \
+        timer_end(ctx, cs);                         \
     }
-    ALS_TIMED_CLASS(0, (launch_dual_class<D, 16>(Y, Z, R, ldr, r0, lists[0], counts[0], err, s)))
-    ALS_TIMED_CLASS(1, (launch_dual_class<D, 32>(Y, Z, R, ldr, r0, lists[1], counts[1], err, s)))
-    ALS_TIMED_CLASS(2, (launch_dual_class<D, 48>(Y, Z, R, ldr, r0, lists[2], counts[2], err, s)))
-    ALS_TIMED_CLASS(3, (launch_dual_class<D, 64>(Y, Z, R, ldr, r0, lists[3], counts[3], err, s)))
-    ALS_TIMED_CLASS(4, (stb = launch_big_class<D, 5>(ctx, Y, Z, R, ldr, r0, lists[4], counts[4], err, s)))
-    ALS_TIMED_CLASS(5, (stb = launch_big_class<D, 6>(ctx, Y, Z, R, ldr, r0, lists[5], counts[5], err, s)))
-    ALS_TIMED_CLASS(6, (stb = launch_big_class<D, 7>(ctx, Y, Z, R, ldr, r0, lists[6], counts[6], err, s)))
-    ALS_TIMED_CLASS(7, (stb = launch_big_class<D, 8>(ctx, Y, Z, R, ldr, r0, lists[7], counts[7], err, s)))
+    ALS_TIMED_CLASS(1, s, (launch_dual_class<D, 32>(Y, Z, R, ldr, r0, lists[1], counts[1], err, cs)))
+    ALS_TIMED_CLASS(0, s, (launch_dual_class<D, 16>(Y, Z, R, ldr, r0, lists[0], counts[0], err, cs)))
+    ALS_TIMED_CLASS(2, s_mid, (launch_dual_class<D, 48>(Y, Z, R, ldr, r0, lists[2], counts[2], err, cs)))
+    ALS_TIMED_CLASS(3, s_mid, (launch_dual_class<D, 64>(Y, Z, R, ldr, r0, lists[3], counts[3], err, cs)))
+    ALS_TIMED_CLASS(4, s_big, (stb = launch_big_class<D, 5>(ctx, Y, Z, R, ldr, r0, lists[4], counts[4], err, cs)))
+    ALS_TIMED_CLASS(5, s_big, (stb = launch_big_class<D, 6>(ctx, Y, Z, R, ldr, r0, lists[5], counts[5], err, cs)))
+    ALS_TIMED_CLASS(6, s_big, (stb = launch_big_class<D, 7>(ctx, Y, Z, R, ldr, r0, lists[6], counts[6], err, cs)))
+    ALS_TIMED_CLASS(7, s_big, (stb = launch_big_class<D, 8>(ctx, Y, Z, R, ldr, r0, lists[7], counts[7], err, cs)))
 #undef ALS_TIMED_CLASS
+    if (side && stb == ALS_OK) stb = side_join(ctx, 0, s);
+    if (side && stb == ALS_OK) stb = side_join(ctx, 1, s);
     if (stb != ALS_OK) return stb;
     timer_begin(ctx, T_TRANSFORM, s);
     const unsigned xblocks = (unsigned)std::min<int64_t>(1024, std::max<int64_t>(1, (r1 - r0 + 127) / 128));

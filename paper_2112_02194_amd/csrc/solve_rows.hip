@@ -148,6 +148,14 @@ als_status launch_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V,
     if (n_long > cap_long || n_seg > cap_seg)
         return fail(ctx, ALS_EINVAL, "CSR structure inconsistent with nnz (run als_check_csr)");
 
+    // From here on the work of the row classes is independent (disjoint output rows): the primal and
+    // long-row kernels go to side stream 2 while the dual classes use the caller's stream and side
+    // streams 0 and 1; everything is joined back into the caller's stream before returning.
+    const bool side = ctx->use_side_streams;
+    if (side && (st = side_fork(ctx, s)) != ALS_OK) return st;
+    hipStream_t s_primal = side ? ctx->side[2] : s;
+    if ((st = launch_primal_long(ctx, Y, V, G, prm, X, long_rows, n_long, segs, n_seg, s_primal)) != ALS_OK) return st;
+    if ((st = launch_primal_fused(ctx, Y, V, G, prm, X, r0, mid_list, n_mid, s_primal)) != ALS_OK) return st;
     if (dual_max > 0) {
         const int32_t *lists[8];
         int counts[8];
@@ -157,8 +165,8 @@ als_status launch_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V,
         }
         if ((st = launch_dual_rows(ctx, Y, X, r0, r1, dual_max, lists, counts, s)) != ALS_OK) return st;
     }
-    if ((st = launch_primal_fused(ctx, Y, V, G, prm, X, r0, mid_list, n_mid, s)) != ALS_OK) return st;
-    return launch_primal_long(ctx, Y, V, G, prm, X, long_rows, n_long, segs, n_seg, s);
+    if (side && (st = side_join(ctx, 2, s)) != ALS_OK) return st;
+    return ALS_OK;
 }
 
 // ---------------------------------------------------------------------------------------------- validation

@@ -68,6 +68,14 @@ typedef struct {
     als_dtype dtype; /* ALS_F32, or ALS_BF16 (Section 4.4: bf16 storage, fp32 arithmetic) */
 } als_table;
 
+/* How the d x d systems of the primal form are solved (Section 4.5 compares such solvers):
+ *   ALS_SOLVER_DIRECT : Cholesky-type factorisation (exact up to rounding).
+ *   ALS_SOLVER_CG     : conjugate gradients on the assembled system, started from the row's current
+ *                       content in X (warm start), stopped when |residual| <= cg_tol * |b| or after
+ *                       cg_max_iters iterations.  The paper's own choice on TPU.
+ * Rows solved in the dual (k x k) form always use the direct solver. */
+typedef enum { ALS_SOLVER_DIRECT = 0, ALS_SOLVER_CG = 1 } als_solver;
+
 typedef struct {
     float alpha;        /* weight of the all-pairs term of Eq. 3, >= 0                         */
     float lambda;       /* L2 weight of Eq. 3, > 0 (keeps every system positive definite)      */
@@ -76,6 +84,9 @@ typedef struct {
                            form, clipped to what the table's d supports                          */
     int32_t split_nnz;  /* 0 = library default; rows longer than this are cut into segments whose
                            partial statistics are summed (Section 4.3's row splitting)           */
+    int32_t solver;       /* als_solver, for rows taking the primal form                         */
+    int32_t cg_max_iters; /* 0 = library default (2*d)                                           */
+    float cg_tol;         /* 0 = library default (1e-6); relative residual at which CG stops     */
 } als_params;
 
 typedef struct als_ctx als_ctx;
@@ -95,7 +106,8 @@ als_status als_gramian(als_ctx *ctx, const als_table *V, float *G, void *stream)
 /* Row update of Eq. 4 (Algorithm 1 lines 3-10) for rows row_begin <= u < row_end of Y:
  *     X[u] = ( sum_{i in Y[u]} v_i (x) v_i + alpha*G + lambda*I )^{-1} sum_{i in Y[u]} y_ui v_i
  * with v_i the rows of the fixed table V (V->rows == Y->cols) and G = V^T V as
- * produced by als_gramian.  A row with no stored entry gets X[u] = 0.  X must
+ * produced by als_gramian.  A row with no stored entry gets X[u] = 0.  With
+ * ALS_SOLVER_CG the rows of X in the range are also read (start vectors).  X must
  * have Y->rows rows, the same d and dtype as V, and must not overlap V.  All
  * arithmetic is fp32 (fp64 for the one shared d x d factorisation); the result
  * is rounded once (to nearest even) to X's dtype.  Rows outside the range are

@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libals.so")
 ALS_OK, ALS_EINVAL, ALS_ESHAPE, ALS_EDTYPE, ALS_EALIAS, ALS_ENOTSPD, ALS_ENOMEM, ALS_EHIP = range(8)
 ALS_F32, ALS_BF16 = 0, 1
 PATH_AUTO, PATH_PRIMAL, PATH_DUAL = 0, 1, 2
+SOLVER_DIRECT, SOLVER_CG = 0, 1
 
 EXPORTS = ["als_create", "als_destroy", "als_gramian", "als_solve_rows", "als_epoch", "als_loss",
            "als_status_sync", "als_check_csr", "als_copy_probe", "als_set_timing", "als_get_timing",
@@ -38,7 +39,8 @@ class c_als_table(ctypes.Structure):
 
 class c_als_params(ctypes.Structure):
     _fields_ = [("alpha", ctypes.c_float), ("lambda_", ctypes.c_float), ("path", ctypes.c_int32),
-                ("dual_max_k", ctypes.c_int32), ("split_nnz", ctypes.c_int32)]
+                ("dual_max_k", ctypes.c_int32), ("split_nnz", ctypes.c_int32), ("solver", ctypes.c_int32),
+                ("cg_max_iters", ctypes.c_int32), ("cg_tol", ctypes.c_float)]
 
 
 class AlsError(RuntimeError):
@@ -153,8 +155,9 @@ class Context:
             raise AlsError(st, f"{self.lib.als_strerror(st).decode()}: {self.lib.als_last_error(self.handle).decode()}")
 
 
-def make_params(alpha: float, lam: float, path: int = PATH_AUTO, dual_max_k: int = 0, split_nnz: int = 0) -> c_als_params:
-    return c_als_params(alpha, lam, path, dual_max_k, split_nnz)
+def make_params(alpha: float, lam: float, path: int = PATH_AUTO, dual_max_k: int = 0, split_nnz: int = 0,
+                solver: int = 0, cg_max_iters: int = 0, cg_tol: float = 0.0) -> c_als_params:
+    return c_als_params(alpha, lam, path, dual_max_k, split_nnz, solver, cg_max_iters, cg_tol)
 
 
 def als_gramian(ctx: Context, V: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:

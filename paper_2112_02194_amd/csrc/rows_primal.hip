@@ -243,7 +243,73 @@ __device__ __forceinline__ void solve_rowsplit(float *a, float *aux, int32_t *er
     (void)lane;
 }
 
-template <int D> __device__ __forceinline__ void solve_spd_lds(float *a, float *aux, int32_t *err_flag) {
+// Conjugate gradients on the assembled system (the solver the paper settles on, Section 4.5), one
+// thread per unknown, all vectors in LDS.  a[c*LD + r] holds entry (r, c) of the full symmetric
+// matrix, aux + 3*D the right-hand side and aux + 2*D the start vector on entry, the solution on
+// exit.  Stops when |residual| <= tol * |b| (checked with the recurrence residual) or after
+// max_iters iterations.  Sums over the unknowns are fixed-order (wavefront shuffles, then wavefronts
+// in order), so the result is reproducible.
+template <int D>
+__device__ __forceinline__ float block_dot(float v, float *red /* [THREADS/64] */) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+    __syncthreads();  // red is free again
+    if (lane == 0) red[w] = v;
+    __syncthreads();
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < Team<D>::THREADS / 64; ++i) s += red[i];
+    return s;
+}
+
+template <int D>
+__device__ __forceinline__ void cg_solve_lds(const float *a, float *aux, int max_iters, float tol) {
+    constexpr int LD = Team<D>::LD;
+    float *rvec = aux, *pvec = aux + D, *xvec = aux + 2 * D, *bvec = aux + 3 * D, *red = aux + 4 * D;
+    const int i = threadIdx.x;
+    const bool mine = i < D;
+    auto matvec = [&](const float *v) {  // row i of A times v (A symmetric: read column i, contiguous in LDS)
+        float s = 0.f;
+        if (mine) {
+#pragma unroll 8
+            for (int j = 0; j < D; ++j) s += a[j * LD + i] * v[j];
+        }
+        return s;
+    };
+    float x = mine ? xvec[i] : 0.f;
+    const float b = mine ? bvec[i] : 0.f;
+    float r = b - matvec(xvec);
+    float pv = r;
+    const float bb = block_dot<D>(b * b, red);
+    float rs = block_dot<D>(r * r, red);
+    const float stop = tol * tol * bb;
+    for (int it = 0; it < max_iters && rs > stop; ++it) {
+        __syncthreads();
+        if (mine) pvec[i] = pv;
+        __syncthreads();
+        const float ap = matvec(pvec);
+        const float pap = block_dot<D>(pv * ap, red);
+        const float alpha = rs / pap;
+        x += alpha * pv;
+        r -= alpha * ap;
+        const float rs_new = block_dot<D>(r * r, red);
+        pv = r + (rs_new / rs) * pv;
+        rs = rs_new;
+    }
+    (void)rvec;
+    __syncthreads();
+    if (mine) xvec[i] = x;
+    __syncthreads();
+}
+
+template <int D>
+__device__ __forceinline__ void solve_spd_lds(float *a, float *aux, int32_t *err_flag, int solver, int cg_iters,
+                                              float cg_tol) {
+    if (solver == ALS_SOLVER_CG) {  // uniform for the launch
+        cg_solve_lds<D>(a, aux, cg_iters, cg_tol);
+        return;
+    }
     if constexpr (D >= 64) {
         solve_rowsplit<D>(a, aux, err_flag);
     } else {
@@ -263,7 +329,7 @@ __global__ __launch_bounds__(Team<D>::THREADS, 2) void primal_kernel(
     const void *__restrict__ V, int64_t ldv, const float *__restrict__ G, float alpha, float lambda,
     void *__restrict__ X, int64_t ldx, int64_t row_begin, const int32_t *__restrict__ row_list,
     const Segment *__restrict__ segs, float *__restrict__ partials,
-    int32_t *__restrict__ err_flag) {
+    int32_t *__restrict__ err_flag, int solver, int cg_iters, float cg_tol) {
     using GE = Geo<D>;
     constexpr int NC = GE::NC, TM = GE::TM, ACC = GE::ACC, LD = Team<D>::LD;
     typedef typename AccT<ACC>::type acc_t;
@@ -321,8 +387,11 @@ __global__ __launch_bounds__(Team<D>::THREADS, 2) void primal_kernel(
 #pragma unroll
             for (int j = 0; j < NC; ++j) bvec[NC * m + j] = bsum[j];
         }
+        if (solver == ALS_SOLVER_CG) {  // warm start from the row's current content
+            for (int c = threadIdx.x; c < D; c += Team<D>::THREADS) aux[2 * D + c] = load_elem<BF16>(X, u * ldx + c);
+        }
         __syncthreads();
-        solve_spd_lds<D>(a, aux, err_flag);
+        solve_spd_lds<D>(a, aux, err_flag, solver, cg_iters, cg_tol);
         const float *xout = aux + 2 * D;
         for (int c = threadIdx.x; c < D; c += Team<D>::THREADS) store_elem<BF16>(X, u * ldx + c, xout[c]);
     }
@@ -353,7 +422,8 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const LongRow *__r
 template <int D, bool BF16>
 __global__ __launch_bounds__(Team<D>::THREADS) void reduce_solve_kernel(
     const LongRow *__restrict__ long_rows, const float *__restrict__ partials, const float *__restrict__ G,
-    float alpha, float lambda, void *__restrict__ X, int64_t ldx, int32_t *__restrict__ err_flag) {
+    float alpha, float lambda, void *__restrict__ X, int64_t ldx, int32_t *__restrict__ err_flag, int solver,
+    int cg_iters, float cg_tol) {
     constexpr int LD = Team<D>::LD, T = Team<D>::THREADS;
     extern __shared__ float lds[];
     float *a = lds, *aux = lds + D * LD, *bvec = aux + 3 * D;
@@ -368,8 +438,11 @@ __global__ __launch_bounds__(Team<D>::THREADS) void reduce_solve_kernel(
             bvec[e - D * D] = s;
         }
     }
+    if (solver == ALS_SOLVER_CG) {
+        for (int c = threadIdx.x; c < D; c += T) aux[2 * D + c] = load_elem<BF16>(X, lr.row * ldx + c);
+    }
     __syncthreads();
-    solve_spd_lds<D>(a, aux, err_flag);
+    solve_spd_lds<D>(a, aux, err_flag, solver, cg_iters, cg_tol);
     const float *xout = aux + 2 * D;
     for (int c = threadIdx.x; c < D; c += T) store_elem<BF16>(X, lr.row * ldx + c, xout[c]);
 }
@@ -381,13 +454,15 @@ static als_status primal_typed(als_ctx *ctx, const als_csr *Y, const als_table *
                                int64_t nitems, hipStream_t s) {
     if (nitems <= 0) return ALS_OK;
     int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
+    const int cg_iters = prm->cg_max_iters > 0 ? prm->cg_max_iters : 2 * D;
+    const float cg_tol = prm->cg_tol > 0.f ? prm->cg_tol : 1e-6f;
     auto kern = primal_kernel<D, BF16, MODE_FUSED>;
     ALS_HIP(ctx, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)Team<D>::LDS_BYTES));
     timer_begin(ctx, T_PRIMAL, s);
     hipLaunchKernelGGL(kern, dim3((unsigned)nitems), dim3(Team<D>::THREADS), Team<D>::LDS_BYTES, s, Y->indptr,
                        Y->indices, Y->values, V->data, V->ld, G, prm->alpha, prm->lambda, X->data, X->ld, r0,
-                       row_list, (const Segment *)nullptr, (float *)nullptr, err);
+                       row_list, (const Segment *)nullptr, (float *)nullptr, err, prm->solver, cg_iters, cg_tol);
     timer_end(ctx, s);
     ALS_HIP(ctx, hipGetLastError());
     return ALS_OK;
@@ -401,6 +476,8 @@ static als_status long_typed(als_ctx *ctx, const als_csr *Y, const als_table *V,
     als_status st = ensure(ctx, ctx->seg_partials, (size_t)n_seg * (D * D + D) * sizeof(float));
     if (st != ALS_OK) return st;
     int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
+    const int cg_iters = prm->cg_max_iters > 0 ? prm->cg_max_iters : 2 * D;
+    const float cg_tol = prm->cg_tol > 0.f ? prm->cg_tol : 1e-6f;
     auto kseg = primal_kernel<D, BF16, MODE_SEGMENT>;
     auto kred = reduce_solve_kernel<D, BF16>;
     ALS_HIP(ctx, hipFuncSetAttribute((const void *)kred, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -408,13 +485,14 @@ static als_status long_typed(als_ctx *ctx, const als_csr *Y, const als_table *V,
     timer_begin(ctx, T_SEGMENT, s);
     hipLaunchKernelGGL(kseg, dim3((unsigned)n_seg), dim3(Team<D>::THREADS), 0, s, Y->indptr, Y->indices, Y->values,
                        V->data, V->ld, G, prm->alpha, prm->lambda, X->data, X->ld, (int64_t)0,
-                       (const int32_t *)nullptr, segs, (float *)ctx->seg_partials.p, err);
+                       (const int32_t *)nullptr, segs, (float *)ctx->seg_partials.p, err, 0, 0, 0.f);
     timer_end(ctx, s);
     timer_begin(ctx, T_REDUCE, s);
     hipLaunchKernelGGL(reduce_partials_kernel<D>, dim3((unsigned)n_long, (D * D + D + 255) / 256), dim3(256), 0, s,
                        long_rows, (float *)ctx->seg_partials.p);
     hipLaunchKernelGGL(kred, dim3((unsigned)n_long), dim3(Team<D>::THREADS), Team<D>::LDS_BYTES, s, long_rows,
-                       (const float *)ctx->seg_partials.p, G, prm->alpha, prm->lambda, X->data, X->ld, err);
+                       (const float *)ctx->seg_partials.p, G, prm->alpha, prm->lambda, X->data, X->ld, err, prm->solver,
+                       cg_iters, cg_tol);
     timer_end(ctx, s);
     ALS_HIP(ctx, hipGetLastError());
     return ALS_OK;

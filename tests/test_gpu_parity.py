@@ -39,13 +39,14 @@ def test_gramian_matches_oracle(ctx, gpu_device, d, dtype, rows):
     assert np.abs(got - ref).max() <= 1e-5 * max(np.abs(ref).max(), 1e-30)
 
 
-def _solve_case(ctx, dev, p, path, split=0, row_range=None, scale_v=1.0, dual_max_k=0):
+def _solve_case(ctx, dev, p, path, split=0, row_range=None, scale_v=1.0, dual_max_k=0, solver=0, cg_tol=0.0):
     Y, _ = to_dev(p, dev)
     V = (p.H0.float() * scale_v).to(p.table_dtype)
     Vd = V.to(dev)
     G = als.als_gramian(ctx, Vd)
     X = torch.full((p.rows, p.d), 7.0, dtype=p.table_dtype, device=dev)
-    prm = als.make_params(p.alpha, p.lam, path=path, split_nnz=split, dual_max_k=dual_max_k)
+    prm = als.make_params(p.alpha, p.lam, path=path, split_nnz=split, dual_max_k=dual_max_k, solver=solver,
+                          cg_tol=cg_tol)
     r0, r1 = row_range or (0, p.rows)
     als.als_solve_rows(ctx, Y, Vd, G, prm, X, r0, r1)
     als.als_status_sync(ctx)
@@ -118,6 +119,33 @@ def test_dual_ill_conditioned_gramian(ctx, gpu_device):
     p.lam = 1e-4
     for path in (als.PATH_AUTO, als.PATH_PRIMAL):
         _solve_case(ctx, gpu_device, p, path)
+
+
+@pytest.mark.parametrize("d", [16, 32, 64, 128])
+def test_cg_solver_matches_oracle(ctx, gpu_device, d):
+    """Conjugate gradients (the paper's solver choice) on the primal systems, cold start, against the exact
+    oracle; long rows go through segments (split = 40)."""
+    say(f"solve_rows primal CG d={d}")
+    p = make_problem("c1", rows=500, cols=700, d=d, values="uniform")
+    got_cg, ref = _solve_case(ctx, gpu_device, p, als.PATH_PRIMAL, split=40, scale_v=8.0, solver=als.SOLVER_CG,
+                              cg_tol=1e-7)
+    # in the default path CG only applies to the rows beyond the dual range
+    _solve_case(ctx, gpu_device, p, als.PATH_AUTO, scale_v=8.0, solver=als.SOLVER_CG, cg_tol=1e-7, dual_max_k=16)
+
+
+def test_cg_warm_start_from_the_solution_changes_nothing(ctx, gpu_device):
+    say("solve_rows CG warm start")
+    p = make_problem("c1", rows=300, cols=400, d=64)
+    Y, _ = to_dev(p, gpu_device)
+    V = (p.H0 * 8.0).to(gpu_device)
+    G = als.als_gramian(ctx, V)
+    X = torch.zeros(p.rows, p.d, device=gpu_device)
+    als.als_solve_rows(ctx, Y, V, G, als.make_params(p.alpha, p.lam, path=als.PATH_PRIMAL), X)
+    X2 = X.clone()
+    als.als_solve_rows(ctx, Y, V, G, als.make_params(p.alpha, p.lam, path=als.PATH_PRIMAL, solver=als.SOLVER_CG,
+                                                     cg_tol=1e-5), X2)
+    als.als_status_sync(ctx)
+    assert rel_fro(f64(X2), f64(X)) <= 2e-6
 
 
 @pytest.mark.parametrize("d,split", [(16, 5), (64, 7), (128, 16), (128, 33)])

@@ -1,25 +1,68 @@
-"""Compile libals.so for gfx950 with hipcc (cross-compiles without a GPU)."""
+"""Compile libals.so for gfx950 with hipcc (cross-compiles without a GPU).
+
+Every translation unit is compiled on its own (in parallel) and the objects are linked into one
+shared library.  Some sources are compiled several times with a different -D each: one object per
+row class, so that the long unrolled solver kernels build side by side.
+"""
 from __future__ import annotations
 
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libals.so")
-SOURCES = ["als_api.hip", "gramian.hip", "rows_primal.hip", "rows_dual.hip", "solve_rows.hip", "loss.hip"]
+OBJDIR = os.path.join(HERE, "_build")
+
+# (source, object name, extra defines)
+UNITS = [
+    ("als_api.hip", "als_api", []),
+    ("gramian.hip", "gramian", []),
+    ("rows_primal.hip", "rows_primal", []),
+    ("solve_rows.hip", "solve_rows", []),
+    ("loss.hip", "loss", []),
+    ("dual_prepare.hip", "dual_prepare", []),
+    ("dual_rows.hip", "dual_rows_k16", ["-DROWS_K=16"]),
+    ("dual_rows.hip", "dual_rows_k64", ["-DROWS_K=64"]),
+    ("dual_multi.hip", "dual_multi_m2", ["-DMULTI_M=2"]),
+    ("dual_multi.hip", "dual_multi_m3", ["-DMULTI_M=3"]),
+    ("dual_wide.hip", "dual_wide_5", ["-DWIDE_KT=5"]),
+    ("dual_wide.hip", "dual_wide_6", ["-DWIDE_KT=6"]),
+    ("dual_wide.hip", "dual_wide_7", ["-DWIDE_KT=7"]),
+    ("dual_wide.hip", "dual_wide_8", ["-DWIDE_KT=8"]),
+]
+
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE, "-I" + CSRC,
+         # packed fp32 instructions are kept out of the generated code on purpose
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def build_library(verbose: bool = False) -> str:
-    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-I" + INCLUDE,
-           # packed fp32 instructions are kept out of the generated code on purpose
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+def _run(cmd):
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in res.stdout.splitlines() if "is not a recognized feature for this target" not in l)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
-    if verbose and out.strip():
-        print(out)
+        raise RuntimeError("command failed: " + " ".join(cmd) + "\n" + out)
+    return out
+
+
+def build_library(verbose: bool = False, jobs: int = 8) -> str:
+    os.makedirs(OBJDIR, exist_ok=True)
+
+    def compile_unit(unit):
+        src, name, defs = unit
+        obj = os.path.join(OBJDIR, name + ".o")
+        return obj, _run(["hipcc"] + FLAGS + defs + ["-c", os.path.join(CSRC, src), "-o", obj])
+
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        results = list(pool.map(compile_unit, UNITS))
+    objs = [o for o, _ in results]
+    out = _run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
+    if verbose:
+        for _, log in results:
+            if log.strip():
+                print(log)
+        if out.strip():
+            print(out)
     return LIB

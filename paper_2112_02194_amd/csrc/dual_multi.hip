@@ -1,0 +1,235 @@
+// Dual row update for 16 < k <= 48, compiled once per class with -DMULTI_M=2 (k <= 32) and -DMULTI_M=3
+// (k <= 48).  The algebra is in the header comment of dual_prepare.hip.
+#include "dual_common.h"
+
+#ifndef MULTI_M
+#error "compile with -DMULTI_M=2 or -DMULTI_M=3"
+#endif
+
+namespace als {
+
+// Four rows per wavefront, one per group of 16 lanes; lane i of a group owns the M rows i, 16+i, ..
+// of its row's k x k system (k <= K = 16*M), so every broadcast of the elimination stays inside a DPP
+// row and needs no LDS.
+//   1. per row: gather its M tiles into registers, S = I + Z_I Z_I^T tile by tile, packed lower
+//      triangle to LDS; the column ids go to LDS for the second gather;
+//   2. lanes load their rows; elimination S = M P M^T (unit lower M, pivots P) one column per step with
+//      u = M^{-1} y riding along;
+//   3. the factor goes back to LDS and is read transposed; back-substitution column by column;
+//   4. r = Z_I^T t with one lane per pair of output columns, gathering the entries a second time.
+template <int C> __device__ __forceinline__ float bcast16(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x150 + C, 0xf, 0xf, true));
+}
+
+template <int D, int M> struct MultiCfg {
+    static constexpr int K = 16 * M, TRI = K * (K + 1) / 2;
+    static constexpr int OFF_T = 4 * TRI, OFF_ID = OFF_T + 4 * K, LDS_FLOATS = OFF_ID + 4 * K;
+};
+
+template <int D, int M>
+__global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restrict__ indptr,
+                                                        const int32_t *__restrict__ indices,
+                                                        const float *__restrict__ values,
+                                                        const float *__restrict__ Z, float *__restrict__ R,
+                                                        int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
+                                                        int count, int32_t *__restrict__ err_flag) {
+    using C = MultiCfg<D, M>;
+    constexpr int K = C::K, TRI = C::TRI, NJ = D / 16, CPL = D >= 128 ? 2 : 1;
+    extern __shared__ float lds[];
+    float *tri = lds, *tbuf = lds + C::OFF_T;
+    int32_t *ids = (int32_t *)(lds + C::OFF_ID);
+    const int lane = threadIdx.x, a = lane & 15, q = lane >> 4;  // MFMA view: entry a of a tile, column group q
+    const int g = lane >> 4, i = lane & 15;                       // solver view: system g, lane i of its group
+
+    int64_t u[4], b[4];
+    int k[4], kmax = 0;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int item = blockIdx.x * 4 + p;
+        u[p] = -1; b[p] = 0; k[p] = 0;
+        if (item < count) {
+            u[p] = r0 + list[item];
+            b[p] = indptr[u[p]];
+            k[p] = (int)(indptr[u[p] + 1] - b[p]);
+        }
+        kmax = k[p] > kmax ? k[p] : kmax;
+    }
+
+    // ---- 1. S of every row, packed lower triangle in LDS
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        float4 z[M][NJ];
+#pragma unroll
+        for (int t = 0; t < M; ++t) {
+            const int e = 16 * t + a;
+            const int32_t id = e < k[p] ? indices[b[p] + e] : -1;
+            if (q == 0) ids[p * K + e] = id;
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+                z[t][j] = id >= 0 ? *(const float4 *)(Z + (int64_t)id * D + (4 * j + q) * 4)
+                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int t1 = 0; t1 < M; ++t1)
+#pragma unroll
+            for (int t2 = 0; t2 <= t1; ++t2) {
+                floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[t2][j].x, z[t1][j].x, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[t2][j].y, z[t1][j].y, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[t2][j].z, z[t1][j].z, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[t2][j].w, z[t1][j].w, acc, 0, 0, 0);
+                }
+                // acc[v] = S[Rr][c], Rr = 16*t1 + a, c = 16*t2 + 4q + v (S is symmetric); keep c <= Rr
+                const int Rr = 16 * t1 + a;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int c = 16 * t2 + 4 * q + v;
+                    if (c <= Rr) tri[p * TRI + Rr * (Rr + 1) / 2 + c] = acc[v] + (c == Rr ? 1.f : 0.f);
+                }
+            }
+    }
+    wave_sync();
+
+    // ---- 2. elimination, lane i of group g owns rows 16*bk + i of system g
+    float s[M][K], y[M], rpm[M];
+    int myk = 0;
+    int64_t myb = 0;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        myk = g == p ? k[p] : myk;
+        myb = g == p ? b[p] : myb;
+    }
+#pragma unroll
+    for (int bk = 0; bk < M; ++bk) {
+        const int Rr = 16 * bk + i;
+#pragma unroll
+        for (int c = 0; c < 16 * (bk + 1); ++c) s[bk][c] = c <= Rr ? tri[g * TRI + Rr * (Rr + 1) / 2 + c] : 0.f;
+        y[bk] = 0.f;
+        if (Rr < myk) y[bk] = values ? values[myb + Rr] : 1.f;
+        rpm[bk] = 1.f;
+    }
+    bool bad = false;
+    static_for<0, K>([&](auto cc) {
+        constexpr int c = decltype(cc)::value;
+        constexpr int cb = c / 16, ci = c % 16;
+        if (c < kmax) {  // steps beyond every row's k only meet identity rows
+            const float pivot = bcast16<ci>(s[cb][c]);
+            const float uc = bcast16<ci>(y[cb]);
+            bad |= !(pivot > 0.f);
+            float rp = __builtin_amdgcn_rcpf(pivot);
+            rp = rp * (2.f - pivot * rp);  // one Newton step on the hardware reciprocal
+            float f[M];
+            static_for<cb, M>([&](auto bb) {
+                constexpr int bk = decltype(bb)::value;
+                const int Rr = 16 * bk + i;
+                rpm[bk] = Rr == c ? rp : rpm[bk];
+                f[bk] = Rr > c ? s[bk][c] * rp : 0.f;  // M[Rr][c]; rows above stay as they are
+                y[bk] -= f[bk] * uc;
+            });
+            static_for<c + 1, K>([&](auto jj) {
+                constexpr int j = decltype(jj)::value;
+                constexpr int jb = j / 16, ji = j % 16;
+                const float cj = bcast16<ji>(s[jb][c]);  // S'[j][c]
+                static_for<jb, M>([&](auto bb) {
+                    constexpr int bk = decltype(bb)::value;
+                    s[bk][j] -= f[bk] * cj;
+                });
+            });
+        }
+    });
+    if (bad && myk > 0) atomicOr(err_flag, 1);
+
+    // ---- 3. factor back to LDS, read transposed (lt[bk][Rr] = S'[Rr][16*bk + i]), back-substitution
+#pragma unroll
+    for (int bk = 0; bk < M; ++bk) {
+        const int Rr = 16 * bk + i;
+#pragma unroll
+        for (int c = 0; c < 16 * (bk + 1); ++c)
+            if (c <= Rr) tri[g * TRI + Rr * (Rr + 1) / 2 + c] = s[bk][c];
+    }
+    wave_sync();
+#pragma unroll
+    for (int bk = 0; bk < M; ++bk) {
+        const int col = 16 * bk + i;
+#pragma unroll
+        for (int Rr = 16 * bk; Rr < K; ++Rr) s[bk][Rr] = Rr > col ? tri[g * TRI + Rr * (Rr + 1) / 2 + col] : 0.f;
+    }
+    float t[M];
+#pragma unroll
+    for (int bk = 0; bk < M; ++bk) t[bk] = 0.f;
+    static_for<0, K>([&](auto cc) {
+        constexpr int c = K - 1 - decltype(cc)::value;
+        constexpr int cb = c / 16, ci = c % 16;
+        if (c < kmax) {
+            const float tc = bcast16<ci>(y[cb] * rpm[cb]);
+            t[cb] = i == ci ? tc : t[cb];
+            static_for<0, cb + 1>([&](auto bb) {
+                constexpr int bk = decltype(bb)::value;
+                y[bk] -= s[bk][c] * tc;  // zero unless row c lies below column 16*bk + i
+            });
+        }
+    });
+#pragma unroll
+    for (int bk = 0; bk < M; ++bk) tbuf[g * K + 16 * bk + i] = t[bk];
+    wave_sync();
+
+    // ---- 4. r = Z_I^T t (second gather of the row's entries)
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        if (u[p] >= 0 && lane * CPL < D) {
+            float r0v = 0.f, r1v = 0.f;
+            const int kp8 = (k[p] + 7) & ~7;  // padded entries have t = 0 and id -1 (row 0 is read instead)
+            for (int e0 = 0; e0 < kp8; e0 += 8) {
+                float2 zz[8];
+                float te[8];
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    const int id = ids[p * K + e0 + x];
+                    te[x] = tbuf[p * K + e0 + x];
+                    const float *zr = Z + (int64_t)(id < 0 ? 0 : id) * D + CPL * lane;
+                    if constexpr (CPL == 2) zz[x] = *(const float2 *)zr;
+                    else zz[x] = make_float2(zr[0], 0.f);
+                }
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    r0v += te[x] * zz[x].x;
+                    r1v += te[x] * zz[x].y;
+                }
+            }
+            if constexpr (CPL == 2) *(float2 *)(R + u[p] * ldr + 2 * lane) = make_float2(r0v, r1v);
+            else R[u[p] * ldr + lane] = r0v;
+        }
+    }
+}
+
+
+template <int D>
+static void launch_multi_typed(const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0,
+                               const int32_t *list, int count, int32_t *err, hipStream_t s) {
+    using C = MultiCfg<D, MULTI_M>;
+    hipLaunchKernelGGL((dual_multi_kernel<D, MULTI_M>), dim3((unsigned)((count + 3) / 4)), dim3(64),
+                       C::LDS_FLOATS * sizeof(float), s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count, err);
+}
+
+#if MULTI_M == 2
+void launch_dual_multi2(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
+                        int count, int32_t *err, hipStream_t s) {
+    switch (d) {  // the dual form stops at k = d
+        case 32: launch_multi_typed<32>(Y, Z, R, ldr, r0, list, count, err, s); break;
+        case 64: launch_multi_typed<64>(Y, Z, R, ldr, r0, list, count, err, s); break;
+        case 128: launch_multi_typed<128>(Y, Z, R, ldr, r0, list, count, err, s); break;
+    }
+}
+#else
+void launch_dual_multi3(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
+                        int count, int32_t *err, hipStream_t s) {
+    switch (d) {
+        case 64: launch_multi_typed<64>(Y, Z, R, ldr, r0, list, count, err, s); break;
+        case 128: launch_multi_typed<128>(Y, Z, R, ldr, r0, list, count, err, s); break;
+    }
+}
+#endif
+
+}  // namespace als

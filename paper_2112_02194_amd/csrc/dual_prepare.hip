@@ -1,0 +1,277 @@
+// Dual (k x k) form of the row update of the paper's Eq. 4 for rows with few stored entries.
+//
+// With B = alpha*G + lambda*I = L L^T (one shared d x d factorisation per half-epoch) and
+// z_i = L^{-1} v_i, the normal equations of a row with entries I (|I| = k) become
+//     A = B + V_I^T V_I = L (I_d + Z_I^T Z_I) L^T ,
+// and the push-through identity (I_d + Z^T Z)^{-1} Z^T = Z^T (I_k + Z Z^T)^{-1} gives
+//     x_u = A^{-1} V_I^T y = L^{-T} Z_I^T t ,   (I_k + Z_I Z_I^T) t = y .
+// This is the same minimiser of Eq. 3 as the d x d system (exact algebra, no approximation), but
+// costs O(k^2 d + k^3) per row instead of O(k d^2 + d^3), and the k x k matrix has eigenvalues in
+// [1, 1 + k/alpha], so fp32 is comfortable.  Steps:
+//   factor_kernel     B -> L^{-1} in fp64 (one workgroup), stored fp32
+//   transform_kernel  Z = V L^{-T}   (fp32 MFMA, table-sized workspace)
+//   row kernels       by class of k (fixed by measurement on MI355X): all gather Z_I straight into MFMA
+//                     operand registers, form S = I + Z_I Z_I^T on the matrix cores, solve the k x k
+//                     system on the vector ALU, then r = Z_I^T t
+//       dual_rows_kernel   k <= 16: four rows per wavefront, one lane per row of S, DPP broadcasts;
+//                          48 < k <= 64: one row per wavefront, column broadcast through LDS
+//       dual_multi_kernel  16 < k <= 48: four rows per wavefront, 2-3 rows of S per lane, DPP only
+//       dual_wide_kernel   64 < k <= 128 (d = 128): one row per wavefront, S as a packed triangle in
+//                          LDS, two rows of S per lane
+//   transform_kernel  X = R L^{-1}   (rows r -> L^{-T} r), rounding to the table's element type
+#include "dual_common.h"
+
+namespace als {
+
+void launch_dual_multi2(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
+                        int count, int32_t *err, hipStream_t s);
+void launch_dual_multi3(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
+                        int count, int32_t *err, hipStream_t s);
+#define ALS_DECL_WIDE(kt)                                                                                         \
+    als_status launch_dual_wide##kt(als_ctx *ctx, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, \
+                                    const int32_t *list, int count, int32_t *err, hipStream_t s);
+ALS_DECL_WIDE(5) ALS_DECL_WIDE(6) ALS_DECL_WIDE(7) ALS_DECL_WIDE(8)
+#undef ALS_DECL_WIDE
+
+// ---------------------------------------------------------------------------------------------- factor
+// One workgroup.  a (fp64, LDS): entry (r,c) at a[c*LD + r].  Outputs Linv (row-major, zeros above
+// the diagonal) and its transpose LinvT, both fp32 [D*D].
+template <int D>
+__global__ __launch_bounds__(256) void factor_kernel(const float *__restrict__ G, float alpha, float lambda,
+                                                     float *__restrict__ Linv, float *__restrict__ LinvT,
+                                                     int32_t *__restrict__ err_flag) {
+    constexpr int LD = D + 1, T = 256;
+    extern __shared__ double fa[];
+    double *a = fa, *col = fa + D * LD;
+    const int t = threadIdx.x, tx = t & 31, ty = t >> 5;
+    for (int e = t; e < D * D; e += T) {
+        const int r = e / D, c = e % D;
+        a[c * LD + r] = (double)alpha * (double)G[e] + (r == c ? (double)lambda : 0.0);
+    }
+    __syncthreads();
+    for (int k = 0; k < D; ++k) {
+        const double pivot = a[k * LD + k];
+        if (t == 0 && !(pivot > 0.0)) atomicOr(err_flag, 1);
+        const double rinv = 1.0 / sqrt(pivot);
+        __syncthreads();
+        for (int i = k + t; i < D; i += T) a[k * LD + i] = (i == k) ? sqrt(pivot) : a[k * LD + i] * rinv;
+        __syncthreads();
+        for (int j = k + 1 + ty; j < D; j += T / 32) {
+            const double cj = a[k * LD + j];
+            for (int i = j + tx; i < D; i += 32) a[j * LD + i] -= a[k * LD + i] * cj;
+        }
+        __syncthreads();
+    }
+    // in-place inverse of the lower triangle, last column first:
+    //   inv[j][j] = 1/L[j][j];  inv[i][j] = -( sum_{p=j+1..i} inv[i][p] * L[p][j] ) * inv[j][j]   (i > j)
+    for (int j = D - 1; j >= 0; --j) {
+        for (int i = j + t; i < D; i += T) col[i] = a[j * LD + i];
+        __syncthreads();
+        const double dj = 1.0 / col[j];
+        for (int i = j + t; i < D; i += T) {
+            double s = 0.0;
+            for (int p = j + 1; p <= i; ++p) s += a[p * LD + i] * col[p];
+            a[j * LD + i] = (i == j) ? dj : -s * dj;
+        }
+        __syncthreads();
+    }
+    for (int e = t; e < D * D; e += T) {
+        const int r = e / D, c = e % D;
+        const float v = r >= c ? (float)a[c * LD + r] : 0.f;
+        Linv[r * D + c] = v;
+        LinvT[c * D + r] = v;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------- transform
+// Out[r][:] = In[r][:] * M for rows r in [r0, r1) (only rows with 0 < k <= k_max stored entries when
+// indptr is given), M fp32 [D x D] row-major and triangular: UPPER = true means M[j][c] = 0 for j > c
+// (M = L^{-T}), UPPER = false means M[j][c] = 0 for j < c (M = L^{-1}).  In may be bf16 or fp32, Out
+// fp32 or bf16; Out may be the same buffer as In (a wavefront reads its rows completely before it
+// writes them, and no other wavefront touches them).
+//
+// A wavefront owns TM table rows at a time and all D output columns.  Lane (m, kq) streams along row
+// m: for the contraction block kb (TM input columns) it holds the BW = TM/KS consecutive columns
+// TM*kb + BW*kq .. of its row, loaded straight from global memory as 16-byte pieces; step i of the
+// block contracts column TM*kb + BW*kq + i (A and B operands only have to agree on that mapping).
+// The transposed matrix sits in LDS (one copy per workgroup, MT[c][j], padded rows) and supplies the
+// B operands; blocks that only meet zeros of the triangular matrix are skipped.
+template <int D> struct XfCfg {
+    using GE = Geo<D>;
+    static constexpr int TM = GE::TM, KS = GE::KS, NB = D / TM, BW = TM / KS, MLD = D + 4;
+    static constexpr size_t LDS_BYTES = (size_t)D * MLD * sizeof(float);
+};
+
+template <int D, bool IN_BF16, bool OUT_BF16, bool UPPER>
+__global__ __launch_bounds__(256) void transform_kernel(const void *__restrict__ In, int64_t ldi,
+                                                        void *__restrict__ Out, int64_t ldo,
+                                                        const float *__restrict__ M, int64_t r0, int64_t r1,
+                                                        const int64_t *__restrict__ indptr, int64_t k_max) {
+    using C = XfCfg<D>;
+    constexpr int TM = C::TM, NB = C::NB, BW = C::BW, MLD = C::MLD, ACC = Geo<D>::ACC;
+    typedef typename AccT<ACC>::type acc_t;
+    extern __shared__ float MT[];  // MT[c * MLD + j] = M[j][c]
+    for (int e = threadIdx.x; e < D * D; e += 256) {
+        const int j = e / D, c = e % D;
+        MT[c * MLD + j] = M[e];
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane % TM, kq = lane / TM;
+    const int64_t ntiles = (r1 - r0 + TM - 1) / TM;
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < ntiles; tile += nwaves) {
+        const int64_t base = r0 + tile * TM, row = base + m;
+        float a[NB][BW];
+#pragma unroll
+        for (int kb = 0; kb < NB; ++kb)
+#pragma unroll
+            for (int i4 = 0; i4 < BW / 4; ++i4) {
+                float x[4] = {0.f, 0.f, 0.f, 0.f};
+                if (row < r1) load_vec<4, IN_BF16>(In, row * ldi + TM * kb + BW * kq + 4 * i4, x);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) a[kb][4 * i4 + c] = x[c];
+            }
+        // which of this lane's ACC output rows are written (only rows solved in the dual form)
+        bool keep[ACC];
+#pragma unroll
+        for (int v = 0; v < ACC; ++v) {
+            const int64_t r = base + acc_row<D>(v, lane);
+            keep[v] = r < r1;
+            if (keep[v] && indptr) {
+                const int64_t k = indptr[r + 1] - indptr[r];
+                keep[v] = k > 0 && k <= k_max;
+            }
+        }
+#pragma unroll
+        for (int J = 0; J < NB; ++J) {
+            acc_t acc;
+#pragma unroll
+            for (int v = 0; v < ACC; ++v) acc[v] = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < NB; ++kb) {
+                if (UPPER ? (kb <= J) : (kb >= J)) {  // compile-time after unrolling
+                    const float *bp = MT + (TM * J + m) * MLD + TM * kb + BW * kq;
+#pragma unroll
+                    for (int i4 = 0; i4 < BW / 4; ++i4) {
+                        const float4 b = *(const float4 *)(bp + 4 * i4);
+                        acc = mfma<D>(a[kb][4 * i4 + 0], b.x, acc);
+                        acc = mfma<D>(a[kb][4 * i4 + 1], b.y, acc);
+                        acc = mfma<D>(a[kb][4 * i4 + 2], b.z, acc);
+                        acc = mfma<D>(a[kb][4 * i4 + 3], b.w, acc);
+                    }
+                }
+            }
+            // acc[v] = Out[base + acc_row(v)][TM*J + m]
+#pragma unroll
+            for (int v = 0; v < ACC; ++v)
+                if (keep[v]) store_elem<OUT_BF16>(Out, (base + acc_row<D>(v, lane)) * ldo + TM * J + m, acc[v]);
+            __builtin_amdgcn_sched_barrier(0);  // keep the next column tile's operand reads from piling up
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------- launchers
+int dual_supported_max_k(int d) { return d < 128 ? (d < 64 ? d : 64) : 128; }
+
+// Part 1 (needs no row classification): factorise B and build Z = V L^{-T}.
+template <int D, bool BF16>
+static als_status dual_prepare_typed(als_ctx *ctx, const als_table *V, const float *G, const als_params *prm,
+                                     hipStream_t s) {
+    als_status st = ensure(ctx, ctx->ztable, (size_t)V->rows * D * sizeof(float));
+    if (st != ALS_OK) return st;
+    float *Linv = (float *)((char *)ctx->small.p + SM_FACTOR), *LinvT = Linv + 128 * 128;
+    int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
+    constexpr size_t factor_lds = (size_t)(D * (D + 1) + D) * sizeof(double);
+    ALS_HIP(ctx, hipFuncSetAttribute((const void *)factor_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)factor_lds));
+    timer_begin(ctx, T_TRANSFORM, s);
+    hipLaunchKernelGGL(factor_kernel<D>, dim3(1), dim3(256), factor_lds, s, G, prm->alpha, prm->lambda, Linv, LinvT,
+                       err);
+    const unsigned tblocks = (unsigned)std::min<int64_t>(1024, std::max<int64_t>(1, (V->rows + 127) / 128));
+    ALS_HIP(ctx, hipFuncSetAttribute((const void *)transform_kernel<D, BF16, false, true>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)XfCfg<D>::LDS_BYTES));
+    hipLaunchKernelGGL((transform_kernel<D, BF16, false, true>), dim3(tblocks), dim3(256), XfCfg<D>::LDS_BYTES, s, V->data, V->ld,
+                       ctx->ztable.p, (int64_t)D, (const float *)LinvT, (int64_t)0, V->rows,
+                       (const int64_t *)nullptr, (int64_t)0);
+    timer_end(ctx, s);
+    ALS_HIP(ctx, hipGetLastError());
+    return ALS_OK;
+}
+
+// Part 2: the row kernels of the four k-classes, then X = R L^{-1} on the rows they solved.
+template <int D, bool BF16>
+static als_status dual_rows_typed(als_ctx *ctx, const als_csr *Y, als_table *X, int64_t r0, int64_t r1,
+                                  int dual_max, const int32_t *const lists[8], const int counts[8], hipStream_t s) {
+    float *R = (float *)X->data;
+    int64_t ldr = X->ld;
+    if (BF16) {
+        als_status st = ensure(ctx, ctx->rtable, (size_t)(r1 - r0) * D * sizeof(float));
+        if (st != ALS_OK) return st;
+        R = (float *)ctx->rtable.p - r0 * D;  // row u lives at rtable[(u - r0) * D]
+        ldr = D;
+    }
+    const float *Linv = (const float *)((char *)ctx->small.p + SM_FACTOR);
+    int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
+    const float *Z = (const float *)ctx->ztable.p;
+    // Independent classes run concurrently: the two largest on the caller's stream, 32 < k <= 64 on
+    // side stream 0, the workgroup kernels (k > 64) on side stream 1.  The caller has forked the side
+    // streams; they are joined before the closing transform, which reads every class's result.
+    als_status stb = ALS_OK;
+    const bool side = ctx->use_side_streams;
+    hipStream_t s_mid = side ? ctx->side[0] : s, s_big = side ? ctx->side[1] : s;
+#define ALS_TIMED_CLASS(cls, strm, call)            \
+    if (counts[cls] > 0 && stb == ALS_OK) {         \
+        hipStream_t cs = strm;                      \
+        timer_begin(ctx, T_DUAL_CLASS0 + cls, cs);  \
+        call;                                       \
+        timer_end(ctx, cs);                         \
+    }
+    ALS_TIMED_CLASS(1, s, (launch_dual_multi2(D, Y, Z, R, ldr, r0, lists[1], counts[1], err, cs)))
+    ALS_TIMED_CLASS(0, s, (launch_dual_k16(D, Y, Z, R, ldr, r0, lists[0], counts[0], err, cs)))
+    ALS_TIMED_CLASS(2, s_mid, (launch_dual_multi3(D, Y, Z, R, ldr, r0, lists[2], counts[2], err, cs)))
+    ALS_TIMED_CLASS(3, s_mid, (launch_dual_k64(D, Y, Z, R, ldr, r0, lists[3], counts[3], err, cs)))
+    ALS_TIMED_CLASS(4, s_big, (stb = launch_dual_wide5(ctx, Y, Z, R, ldr, r0, lists[4], counts[4], err, cs)))
+    ALS_TIMED_CLASS(5, s_big, (stb = launch_dual_wide6(ctx, Y, Z, R, ldr, r0, lists[5], counts[5], err, cs)))
+    ALS_TIMED_CLASS(6, s_big, (stb = launch_dual_wide7(ctx, Y, Z, R, ldr, r0, lists[6], counts[6], err, cs)))
+    ALS_TIMED_CLASS(7, s_big, (stb = launch_dual_wide8(ctx, Y, Z, R, ldr, r0, lists[7], counts[7], err, cs)))
+#undef ALS_TIMED_CLASS
+    if (side && stb == ALS_OK) stb = side_join(ctx, 0, s);
+    if (side && stb == ALS_OK) stb = side_join(ctx, 1, s);
+    if (stb != ALS_OK) return stb;
+    timer_begin(ctx, T_TRANSFORM, s);
+    const unsigned xblocks = (unsigned)std::min<int64_t>(1024, std::max<int64_t>(1, (r1 - r0 + 127) / 128));
+    ALS_HIP(ctx, hipFuncSetAttribute((const void *)transform_kernel<D, false, BF16, false>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)XfCfg<D>::LDS_BYTES));
+    hipLaunchKernelGGL((transform_kernel<D, false, BF16, false>), dim3(xblocks), dim3(256), XfCfg<D>::LDS_BYTES, s, (const void *)R, ldr,
+                       X->data, X->ld, Linv, r0, r1, Y->indptr, (int64_t)dual_max);
+    timer_end(ctx, s);
+    ALS_HIP(ctx, hipGetLastError());
+    return ALS_OK;
+}
+
+als_status launch_dual_prepare(als_ctx *ctx, const als_table *V, const float *G, const als_params *prm,
+                               hipStream_t s) {
+    const bool bf = V->dtype == ALS_BF16;
+    switch (V->d) {
+        case 16: return bf ? dual_prepare_typed<16, true>(ctx, V, G, prm, s) : dual_prepare_typed<16, false>(ctx, V, G, prm, s);
+        case 32: return bf ? dual_prepare_typed<32, true>(ctx, V, G, prm, s) : dual_prepare_typed<32, false>(ctx, V, G, prm, s);
+        case 64: return bf ? dual_prepare_typed<64, true>(ctx, V, G, prm, s) : dual_prepare_typed<64, false>(ctx, V, G, prm, s);
+        case 128: return bf ? dual_prepare_typed<128, true>(ctx, V, G, prm, s) : dual_prepare_typed<128, false>(ctx, V, G, prm, s);
+    }
+    return fail(ctx, ALS_EDTYPE, "unsupported d");
+}
+
+als_status launch_dual_rows(als_ctx *ctx, const als_csr *Y, als_table *X, int64_t r0, int64_t r1, int dual_max,
+                            const int32_t *const lists[8], const int counts[8], hipStream_t s) {
+    const bool bf = X->dtype == ALS_BF16;
+    switch (X->d) {
+        case 16: return bf ? dual_rows_typed<16, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, s) : dual_rows_typed<16, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, s);
+        case 32: return bf ? dual_rows_typed<32, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, s) : dual_rows_typed<32, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, s);
+        case 64: return bf ? dual_rows_typed<64, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, s) : dual_rows_typed<64, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, s);
+        case 128: return bf ? dual_rows_typed<128, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, s) : dual_rows_typed<128, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, s);
+    }
+    return fail(ctx, ALS_EDTYPE, "unsupported d");
+}
+
+}  // namespace als

@@ -1,0 +1,221 @@
+// Dual row update for 64 < k <= 128 (d = 128 only), compiled once per class with -DWIDE_KT=5..8
+// (k <= 16*WIDE_KT).  The algebra is in the header comment of dual_prepare.hip.
+#include "dual_common.h"
+
+#ifndef WIDE_KT
+#error "compile with -DWIDE_KT=5, 6, 7 or 8"
+#endif
+
+namespace als {
+
+// One wavefront per row with k <= K = 16*KT entries (KT = 5..8).
+//   1. S = I + Z_I Z_I^T tile by tile: the wavefront keeps the 16 entries of tile t1 in registers (B
+//      operand) and streams the tiles t2 <= t1 past them (A operand, fetched again from the caches);
+//      each finished 16x16 tile goes to LDS, where S is kept as a packed lower triangle.
+//   2. Elimination S = M P M^T with lane i owning rows i and 64+i (columns 0..63 of the first, all of
+//      the second, in registers): per step the column is published in LDS and read back by broadcast,
+//      pivot and right-hand-side entry come straight from the owning lane; u = M^{-1} y rides along.
+//   3. Back-substitution with the factor read transposed from LDS, the value just found taken from
+//      its lane.
+//   4. r = Z_I^T t with one lane per pair of output columns, gathering the entries a second time.
+template <int D, int KT> struct WideCfg {
+    static constexpr int K = 16 * KT;
+    static constexpr int TRI = K * (K + 1) / 2;      // packed lower triangle
+    static constexpr int OFF_COL = TRI;              // colbuf[2][K]
+    static constexpr int OFF_T = OFF_COL + 2 * K;    // tbuf[K]
+    static constexpr int OFF_ID = OFF_T + K;         // ids[K]
+    static constexpr int LDS_FLOATS = OFF_ID + K;
+};
+
+template <int D, int KT>
+__global__ __launch_bounds__(64) void dual_wide_kernel(const int64_t *__restrict__ indptr,
+                                                       const int32_t *__restrict__ indices,
+                                                       const float *__restrict__ values,
+                                                       const float *__restrict__ Z, float *__restrict__ R,
+                                                       int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
+                                                       int32_t *__restrict__ err_flag) {
+    using C = WideCfg<D, KT>;
+    constexpr int K = C::K, NJ = D / 16, K1 = K - 64;  // K1 = rows held as "second row" of a lane
+    extern __shared__ float lds[];
+    float *tri = lds, *colbuf = lds + C::OFF_COL, *tbuf = lds + C::OFF_T;
+    int32_t *ids = (int32_t *)(lds + C::OFF_ID);
+    const int lane = threadIdx.x, a = lane & 15, q = lane >> 4;
+    const int64_t u = r0 + list[blockIdx.x];
+    const int64_t b = indptr[u];
+    const int k = (int)(indptr[u + 1] - b);  // <= K by the list's class
+
+    // ---- 1. S tiles
+    int32_t myid[KT];
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+        const int e = 16 * t + a;
+        myid[t] = e < k ? indices[b + e] : -1;
+        if (q == 0) ids[e] = myid[t];
+    }
+    // the first RT tiles stay in registers for the whole phase (one round of loads, all in flight
+    // together); later tiles are fetched when they are needed
+    constexpr int RT = KT < 5 ? KT : 5;
+    float4 zres[RT][NJ];
+#pragma unroll
+    for (int t = 0; t < RT; ++t)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+            zres[t][j] = myid[t] >= 0 ? *(const float4 *)(Z + (int64_t)myid[t] * D + (4 * j + q) * 4)
+                                      : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int t1 = 0; t1 < KT; ++t1) {
+        float4 zb[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            if (t1 < RT) zb[j] = zres[t1 < RT ? t1 : 0][j];
+            else zb[j] = myid[t1] >= 0 ? *(const float4 *)(Z + (int64_t)myid[t1] * D + (4 * j + q) * 4)
+                                       : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int t2 = 0; t2 <= t1; ++t2) {
+            floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                float4 za;
+                if (t2 == t1) za = zb[j];
+                else if (t2 < RT) za = zres[t2 < RT ? t2 : 0][j];
+                else za = myid[t2] >= 0 ? *(const float4 *)(Z + (int64_t)myid[t2] * D + (4 * j + q) * 4)
+                                        : make_float4(0.f, 0.f, 0.f, 0.f);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(za.x, zb[j].x, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(za.y, zb[j].y, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(za.z, zb[j].z, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(za.w, zb[j].w, acc, 0, 0, 0);
+            }
+            // acc[v] = S[Rr][c], Rr = 16*t1 + a, c = 16*t2 + 4q + v (S is symmetric); keep c <= Rr
+            const int Rr = 16 * t1 + a;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int c = 16 * t2 + 4 * q + v;
+                if (c <= Rr) tri[Rr * (Rr + 1) / 2 + c] = acc[v] + (c == Rr ? 1.f : 0.f);
+            }
+        }
+    }
+    wave_sync();
+
+    // ---- 2. elimination; lane i owns rows i (columns 0..63) and 64+i (all columns, if 64+i < K)
+    const int ra = lane, rb = 64 + lane;
+    const bool hasb = rb < K;
+    float s0[64], s1[K];
+#pragma unroll
+    for (int c = 0; c < 64; ++c) s0[c] = c <= ra ? tri[ra * (ra + 1) / 2 + c] : 0.f;
+#pragma unroll
+    for (int c = 0; c < K; ++c) s1[c] = (hasb && c <= rb) ? tri[rb * (rb + 1) / 2 + c] : 0.f;
+    float y0 = 0.f, y1 = 0.f;
+    if (ra < k) y0 = values ? values[b + ra] : 1.f;
+    if (rb < k) y1 = values ? values[b + rb] : 1.f;
+    float rp0 = 1.f, rp1 = 1.f;
+    bool bad = false;
+    wave_sync();
+    static_for<0, K>([&](auto cc) {
+        constexpr int c = decltype(cc)::value;
+        if (c < k) {  // the remaining rows are identity rows with zero right-hand side
+            float *cb = colbuf + (c & 1) * K;
+            float pivot, uc;
+            if constexpr (c < 64) {
+                cb[lane] = s0[c];
+                if (hasb) cb[64 + lane] = s1[c];
+                pivot = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s0[c]), c));
+                uc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(y0), c));
+            } else {
+                if (hasb) cb[64 + lane] = s1[c];
+                pivot = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s1[c]), c - 64));
+                uc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(y1), c - 64));
+            }
+            bad |= !(pivot > 0.f);
+            float rp = __builtin_amdgcn_rcpf(pivot);
+            rp = rp * (2.f - pivot * rp);  // one Newton step on the hardware reciprocal
+            float f0 = 0.f;
+            if constexpr (c < 64) {
+                rp0 = ra == c ? rp : rp0;
+                f0 = ra > c ? s0[c] * rp : 0.f;
+                y0 -= f0 * uc;
+            }
+            rp1 = rb == c ? rp : rp1;
+            const float f1 = rb > c ? s1[c] * rp : 0.f;  // lanes without a second row hold zeros in s1
+            y1 -= f1 * uc;
+            wave_sync();
+            static_for<(c + 1) / 4, K / 4>([&](auto jj) {
+                constexpr int j4 = decltype(jj)::value;
+                const float4 col = *(const float4 *)(cb + 4 * j4);
+                if constexpr (4 * j4 + 0 > c) { if constexpr (4 * j4 + 0 < 64 && c < 64) s0[4 * j4 + 0] -= f0 * col.x; s1[4 * j4 + 0] -= f1 * col.x; }
+                if constexpr (4 * j4 + 1 > c) { if constexpr (4 * j4 + 1 < 64 && c < 64) s0[4 * j4 + 1] -= f0 * col.y; s1[4 * j4 + 1] -= f1 * col.y; }
+                if constexpr (4 * j4 + 2 > c) { if constexpr (4 * j4 + 2 < 64 && c < 64) s0[4 * j4 + 2] -= f0 * col.z; s1[4 * j4 + 2] -= f1 * col.z; }
+                if constexpr (4 * j4 + 3 > c) { if constexpr (4 * j4 + 3 < 64 && c < 64) s0[4 * j4 + 3] -= f0 * col.w; s1[4 * j4 + 3] -= f1 * col.w; }
+            });
+        }
+    });
+    if (bad && lane == 0) atomicOr(err_flag, 1);
+
+    // ---- 3. t_c = (u_c - sum_{Rr>c} S'[Rr][c] t_Rr) / pivot_c; the factor goes back to the packed triangle
+#pragma unroll
+    for (int c = 0; c < 64; ++c)
+        if (c <= ra) tri[ra * (ra + 1) / 2 + c] = s0[c];
+#pragma unroll
+    for (int c = 0; c < K; ++c)
+        if (hasb && c <= rb) tri[rb * (rb + 1) / 2 + c] = s1[c];
+    wave_sync();
+    {
+        float t0 = 0.f, t1v = 0.f;
+#pragma unroll 4
+        for (int Rr = (k < K ? k : K) - 1; Rr >= 64; --Rr) {
+            const float tR = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(y1 * rp1), Rr - 64));
+            t1v = rb == Rr ? tR : t1v;
+            const int base = Rr * (Rr + 1) / 2;
+            if (rb < Rr) y1 -= tri[base + rb] * tR;
+            y0 -= tri[base + ra] * tR;
+        }
+#pragma unroll 4
+        for (int Rr = (k < 64 ? k : 64) - 1; Rr >= 0; --Rr) {
+            const float tR = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(y0 * rp0), Rr));
+            t0 = ra == Rr ? tR : t0;
+            if (ra < Rr) y0 -= tri[Rr * (Rr + 1) / 2 + ra] * tR;
+        }
+        tbuf[ra] = t0;
+        if (hasb) tbuf[rb] = t1v;
+    }
+    wave_sync();
+
+    // ---- 4. r = Z_I^T t, one lane per pair of output columns (second gather of the row's entries)
+    {
+        float r0v = 0.f, r1v = 0.f;
+        const int kp8 = (k + 7) & ~7;  // padded entries have t = 0 and id -1 (row 0 is read instead)
+        for (int e0 = 0; e0 < kp8; e0 += 8) {
+            float2 zz[8];
+            float te[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int id = ids[e0 + i];
+                te[i] = tbuf[e0 + i];
+                zz[i] = *(const float2 *)(Z + (int64_t)(id < 0 ? 0 : id) * D + 2 * lane);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                r0v += te[i] * zz[i].x;
+                r1v += te[i] * zz[i].y;
+            }
+        }
+        *(float2 *)(R + u * ldr + 2 * lane) = make_float2(r0v, r1v);
+    }
+}
+
+
+#define ALS_WIDE_NAME2(kt) launch_dual_wide##kt
+#define ALS_WIDE_NAME(kt) ALS_WIDE_NAME2(kt)
+
+als_status ALS_WIDE_NAME(WIDE_KT)(als_ctx *ctx, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0,
+                                  const int32_t *list, int count, int32_t *err, hipStream_t s) {
+    using C = WideCfg<128, WIDE_KT>;
+    auto kern = dual_wide_kernel<128, WIDE_KT>;
+    ALS_HIP(ctx, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)(C::LDS_FLOATS * sizeof(float))));
+    hipLaunchKernelGGL(kern, dim3((unsigned)count), dim3(64), C::LDS_FLOATS * sizeof(float), s, Y->indptr, Y->indices,
+                       Y->values, Z, R, ldr, r0, list, err);
+    return ALS_OK;
+}
+
+}  // namespace als

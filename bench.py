@@ -180,7 +180,8 @@ def main():
     for c in range(8):
         ms, launches = stage_ms.get(f"dual_k{16 * (c + 1)}", 0.0), stage_ms.get(f"launches_k{16 * (c + 1)}", 0.0)
         if launches > 0:
-            kname = (f"dual_rows_kernel<{d}, {16 * (c + 1)}>" if c < 4 else f"dual_wide_kernel<{d}, {c + 1}>")
+            kname = {0: f"dual_rows_kernel<{d}, 16>", 1: f"dual_multi_kernel<{d}, 2>", 2: f"dual_multi_kernel<{d}, 3>",
+                     3: f"dual_rows_kernel<{d}, 64>"}.get(c, f"dual_wide_kernel<{d}, {c + 1}>")
             per_launch = nsteps * (cls_nnz[c] * (4 * d + 4) + cls_rows[c] * (4 * d + 12)) / launches
             cand[kname] = (ms, launches, "hbm", per_launch)
     if stage_ms.get("primal", 0) > 0:

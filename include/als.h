@@ -43,7 +43,7 @@ typedef enum { ALS_F32 = 0, ALS_BF16 = 1 } als_dtype;
  *                     Eq. 4 (Algorithm 1 lines 4-10 literally).
  *   ALS_PATH_DUAL   : as AUTO (kept distinct so callers can state intent).
  * Both formulations reach the same minimiser of Eq. 3 (the algebra is in the header
- * comment of csrc/rows_dual.hip).  The dual form is available for k <= min(d, 64),
+ * comment of csrc/dual_prepare.hip).  The dual form is available for k <= min(d, 64),
  * and for k <= 128 when d = 128. */
 typedef enum { ALS_PATH_AUTO = 0, ALS_PATH_PRIMAL = 1, ALS_PATH_DUAL = 2 } als_path;
 

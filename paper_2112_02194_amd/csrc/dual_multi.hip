@@ -175,35 +175,45 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
     for (int bk = 0; bk < M; ++bk) tbuf[g * K + 16 * bk + i] = t[bk];
     wave_sync();
 
-    // ---- 4. r = Z_I^T t (second gather of the row's entries)
+    // ---- 4. r = Z_I^T t (second gather of the row's entries); the four rows advance together, eight
+    // entries each per round, so that 32 loads per lane are in flight
+    {
+        float r0v[4] = {0.f, 0.f, 0.f, 0.f}, r1v[4] = {0.f, 0.f, 0.f, 0.f};
+        const bool col_ok = lane * CPL < D;
+        const int kmax8 = (kmax + 7) & ~7;  // padded entries have t = 0 and id -1 (row 0 is read instead)
+        for (int e0 = 0; e0 < kmax8; e0 += 8) {
+            float2 zz[4][8];
+            float te[4][8];
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        if (u[p] >= 0 && lane * CPL < D) {
-            float r0v = 0.f, r1v = 0.f;
-            const int kp8 = (k[p] + 7) & ~7;  // padded entries have t = 0 and id -1 (row 0 is read instead)
-            for (int e0 = 0; e0 < kp8; e0 += 8) {
-                float2 zz[8];
-                float te[8];
+            for (int p = 0; p < 4; ++p)
 #pragma unroll
                 for (int x = 0; x < 8; ++x) {
                     const int id = ids[p * K + e0 + x];
-                    te[x] = tbuf[p * K + e0 + x];
+                    te[p][x] = tbuf[p * K + e0 + x];
                     const float *zr = Z + (int64_t)(id < 0 ? 0 : id) * D + CPL * lane;
-                    if constexpr (CPL == 2) zz[x] = *(const float2 *)zr;
-                    else zz[x] = make_float2(zr[0], 0.f);
+                    zz[p][x] = make_float2(0.f, 0.f);
+                    if (col_ok && e0 < k[p]) {
+                        if constexpr (CPL == 2) zz[p][x] = *(const float2 *)zr;
+                        else zz[p][x].x = zr[0];
+                    }
                 }
 #pragma unroll
+            for (int p = 0; p < 4; ++p)
+#pragma unroll
                 for (int x = 0; x < 8; ++x) {
-                    r0v += te[x] * zz[x].x;
-                    r1v += te[x] * zz[x].y;
+                    r0v[p] += te[p][x] * zz[p][x].x;
+                    r1v[p] += te[p][x] * zz[p][x].y;
                 }
+        }
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            if (u[p] >= 0 && col_ok) {
+                if constexpr (CPL == 2) *(float2 *)(R + u[p] * ldr + 2 * lane) = make_float2(r0v[p], r1v[p]);
+                else R[u[p] * ldr + lane] = r0v[p];
             }
-            if constexpr (CPL == 2) *(float2 *)(R + u[p] * ldr + 2 * lane) = make_float2(r0v, r1v);
-            else R[u[p] * ldr + lane] = r0v;
         }
     }
 }
-
 
 template <int D>
 static void launch_multi_typed(const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0,

@@ -23,8 +23,8 @@ if ROOT not in sys.path:
 # HBM bytes per launch measured with rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by the copy-probe factors);
 # source: profiles/c3_epoch_hbm_traffic.md.  Keyed by (workload, kernel as named in the roofline object).
 MEASURED_TRAFFIC_BYTES = {
-    ("c3", "dual_rows_kernel<128, 32>"): 25.27e9,
-    ("c3", "dual_rows_kernel<128, 16>"): 24.92e9,
+    ("c3", "dual_multi_kernel<128, 2>"): 2.0 * 24728475 * 1024 + 1516525 * 1024,   # 52.2 GB (second gather included)
+    ("c3", "dual_rows_kernel<128, 16>"): 2.0 * 10647019 * 1024 + 3047319 * 1024,   # 24.9 GB
 }
 HBM_PEAK_GBS = 8000.0
 MFMA_F32_PEAK_TFLOPS = 157.3

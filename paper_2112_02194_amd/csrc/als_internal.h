@@ -155,7 +155,7 @@ struct als_ctx {
 namespace als {
 
 // Layout of ctx->small (byte offsets).
-constexpr size_t SM_COUNTERS = 0;       // int32[16]: [0] n_long [1] n_seg [2] error flag [3] n_mid [4] csr check [8..15] dual classes
+constexpr size_t SM_COUNTERS = 0;       // int32[16]: [0] n_long [1] n_seg [2] error flag [3] n_mid [4] csr check [5] k<=4 [6] 5<=k<=8 [8..15] dual classes
 constexpr size_t SM_LOSS = 64;          // double[2]
 constexpr size_t SM_FACTOR = 256;       // fp32 [2][128*128]: L^{-1} and scratch for the dual form
 constexpr size_t SM_BYTES = SM_FACTOR + 2 * 128 * 128 * sizeof(float) + 128 * 128 * sizeof(double);

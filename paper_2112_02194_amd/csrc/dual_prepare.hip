@@ -23,6 +23,10 @@
 
 namespace als {
 
+void launch_dual_small4(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
+                        int count, int32_t *err, hipStream_t s);
+void launch_dual_small8(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
+                        int count, int32_t *err, hipStream_t s);
 void launch_dual_multi2(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
                         int count, int32_t *err, hipStream_t s);
 void launch_dual_multi3(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
@@ -202,7 +206,7 @@ static als_status dual_prepare_typed(als_ctx *ctx, const als_table *V, const flo
 // Part 2: the row kernels of the four k-classes, then X = R L^{-1} on the rows they solved.
 template <int D, bool BF16>
 static als_status dual_rows_typed(als_ctx *ctx, const als_csr *Y, als_table *X, int64_t r0, int64_t r1,
-                                  int dual_max, const int32_t *const lists[8], const int counts[8], hipStream_t s) {
+                                  int dual_max, const int32_t *const lists[10], const int counts[10], hipStream_t s) {
     float *R = (float *)X->data;
     int64_t ldr = X->ld;
     if (BF16) {
@@ -229,6 +233,16 @@ static als_status dual_rows_typed(als_ctx *ctx, const als_csr *Y, als_table *X, 
     }
     ALS_TIMED_CLASS(1, s, (launch_dual_multi2(D, Y, Z, R, ldr, r0, lists[1], counts[1], err, cs)))
     ALS_TIMED_CLASS(0, s, (launch_dual_k16(D, Y, Z, R, ldr, r0, lists[0], counts[0], err, cs)))
+    if (counts[9] > 0) {  // 5 <= k <= 8 and k <= 4: several rows per MFMA tile; timed with class 0
+        timer_begin(ctx, T_DUAL_CLASS0, s);
+        launch_dual_small8(D, Y, Z, R, ldr, r0, lists[9], counts[9], err, s);
+        timer_end(ctx, s);
+    }
+    if (counts[8] > 0) {
+        timer_begin(ctx, T_DUAL_CLASS0, s);
+        launch_dual_small4(D, Y, Z, R, ldr, r0, lists[8], counts[8], err, s);
+        timer_end(ctx, s);
+    }
     ALS_TIMED_CLASS(2, s_mid, (launch_dual_multi3(D, Y, Z, R, ldr, r0, lists[2], counts[2], err, cs)))
     ALS_TIMED_CLASS(3, s_mid, (launch_dual_k64(D, Y, Z, R, ldr, r0, lists[3], counts[3], err, cs)))
     ALS_TIMED_CLASS(4, s_big, (stb = launch_dual_wide5(ctx, Y, Z, R, ldr, r0, lists[4], counts[4], err, cs)))
@@ -263,7 +277,7 @@ als_status launch_dual_prepare(als_ctx *ctx, const als_table *V, const float *G,
 }
 
 als_status launch_dual_rows(als_ctx *ctx, const als_csr *Y, als_table *X, int64_t r0, int64_t r1, int dual_max,
-                            const int32_t *const lists[8], const int counts[8], hipStream_t s) {
+                            const int32_t *const lists[10], const int counts[10], hipStream_t s) {
     const bool bf = X->dtype == ALS_BF16;
     switch (X->d) {
         case 16: return bf ? dual_rows_typed<16, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, s) : dual_rows_typed<16, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, s);

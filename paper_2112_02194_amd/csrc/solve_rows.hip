@@ -14,7 +14,7 @@ als_status launch_primal_long(als_ctx *ctx, const als_csr *Y, const als_table *V
 als_status launch_dual_prepare(als_ctx *ctx, const als_table *V, const float *G, const als_params *prm,
                                hipStream_t s);
 als_status launch_dual_rows(als_ctx *ctx, const als_csr *Y, als_table *X, int64_t r0, int64_t r1, int dual_max,
-                            const int32_t *const lists[8], const int counts[8], hipStream_t s);
+                            const int32_t *const lists[10], const int counts[10], hipStream_t s);
 int dual_supported_max_k(int d);
 
 constexpr int DEFAULT_SPLIT = 512;
@@ -26,11 +26,12 @@ __global__ void clear_counters_kernel(int32_t *counters) {
 
 constexpr int CLS_THREADS = 256, CLS_RPT = 8, CLS_ROWS = CLS_THREADS * CLS_RPT;  // rows per workgroup
 constexpr int MAX_SEGS_PER_ROW = 128;
-struct ListOffsets { int64_t v[8]; };  // start of each dual class list, passed by value
+struct ListOffsets { int64_t v[10]; };  // start of each dual class list, passed by value
 
 // One workgroup per CLS_ROWS consecutive rows of [r0, r1):
 //   k = 0               X[u] = 0
-//   0 < k <= dual_max   appended to the dual list of its class ceil(k/16) in 1..8 (row id relative to r0)
+//   0 < k <= dual_max   appended to the dual list of its class: k <= 4, 5..8, else ceil(k/16) in 1..8
+//                       (row id relative to r0)
 //   dual_max < k <= split  appended to the mid list (primal, one workgroup per row)
 //   k > split           becomes a long row cut into balanced segments of about `split` entries
 //                       (at most MAX_SEGS_PER_ROW of them)
@@ -42,9 +43,9 @@ __global__ __launch_bounds__(CLS_THREADS) void classify_kernel(
     void *__restrict__ X, int64_t ldx, int32_t *__restrict__ counters, LongRow *__restrict__ long_rows,
     Segment *__restrict__ segs, int32_t *__restrict__ mid_list, int32_t *__restrict__ dual_lists,
     ListOffsets list_off) {
-    __shared__ int32_t cnt[9], base[9];
+    __shared__ int32_t cnt[11], base[11];
     const int t = threadIdx.x;
-    if (t < 9) cnt[t] = 0;
+    if (t < 11) cnt[t] = 0;
     __syncthreads();
     const int64_t u0 = r0 + (int64_t)blockIdx.x * CLS_ROWS;
     int cls[CLS_RPT], pos[CLS_RPT];
@@ -72,19 +73,20 @@ __global__ __launch_bounds__(CLS_THREADS) void classify_kernel(
                     segs[first + g].end = stop < e ? stop : e;
                 }
             } else {
-                cls[i] = k > dual_max ? 0 : (int)((k + 15) / 16);  // 0 = mid list, 1..8 = dual classes
+                // 0 = mid list, 1..8 = dual classes by ceil(k/16), 9 = k <= 4, 10 = 5 <= k <= 8
+                cls[i] = k > dual_max ? 0 : (k <= 4 ? 9 : (k <= 8 ? 10 : (int)((k + 15) / 16)));
                 pos[i] = atomicAdd(&cnt[cls[i]], 1);
             }
         }
     }
     __syncthreads();
-    if (t < 9 && cnt[t] > 0) base[t] = atomicAdd(&counters[t == 0 ? 3 : 8 + t - 1], cnt[t]);
+    if (t < 11 && cnt[t] > 0) base[t] = atomicAdd(&counters[t == 0 ? 3 : (t <= 8 ? 8 + t - 1 : t - 4)], cnt[t]);
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < CLS_RPT; ++i) {
         if (cls[i] < 0) continue;
         const int32_t rel = (int32_t)(u0 + (int64_t)i * CLS_THREADS + t - r0);
-        int32_t *list = cls[i] == 0 ? mid_list : dual_lists + list_off.v[cls[i] - 1];
+        int32_t *list = cls[i] == 0 ? mid_list : dual_lists + list_off.v[cls[i] - 1];  // class ids 1..10 -> lists 0..9
         list[base[cls[i]] + pos[i]] = rel;
     }
 }
@@ -105,17 +107,21 @@ als_status launch_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V,
     if (cap_seg > INT32_MAX) return fail(ctx, ALS_EINVAL, "split_nnz too small for this matrix");
     // list capacities: class c (k > 16(c-1)) holds at most nnz/(16(c-1)+1) rows, the mid list at most
     // nnz/(dual_max+1); offsets go to the device through a small table in the context's scratch
-    int64_t off[9];
+    int64_t off[11];  // lists 0..7: classes by ceil(k/16); list 8: k <= 4; list 9: 5 <= k <= 8
     off[0] = 0;
-    for (int c = 1; c <= 8; ++c) {
+    for (int c = 1; c <= 10; ++c) {
         int64_t cap = 0;
-        if (dual_max > 16 * (c - 1)) cap = std::min<int64_t>(nrows, Y->nnz / (16 * (c - 1) + 1) + 1);
+        if (c <= 8) {
+            if (dual_max > 16 * (c - 1)) cap = std::min<int64_t>(nrows, Y->nnz / (16 * (c - 1) + 1) + 1);
+        } else if (dual_max > 0) {
+            cap = std::min<int64_t>(nrows, Y->nnz / (c == 9 ? 1 : 5) + 1);
+        }
         off[c] = off[c - 1] + cap;
     }
     const int64_t cap_mid = std::min<int64_t>(nrows, Y->nnz / (dual_max + 1) + 1);
     const size_t off_seg = (size_t)cap_long * sizeof(LongRow);
     const size_t off_lists = off_seg + (size_t)cap_seg * sizeof(Segment);
-    als_status st = ensure(ctx, ctx->lists, off_lists + (size_t)(cap_mid + off[8]) * sizeof(int32_t));
+    als_status st = ensure(ctx, ctx->lists, off_lists + (size_t)(cap_mid + off[10]) * sizeof(int32_t));
     if (st != ALS_OK) return st;
     LongRow *long_rows = (LongRow *)ctx->lists.p;
     Segment *segs = (Segment *)((char *)ctx->lists.p + off_seg);
@@ -123,7 +129,7 @@ als_status launch_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V,
     int32_t *dual_lists = mid_list + cap_mid;
     int32_t *counters = (int32_t *)((char *)ctx->small.p + SM_COUNTERS);
     ListOffsets list_off;
-    for (int c = 0; c < 8; ++c) list_off.v[c] = off[c];
+    for (int c = 0; c < 10; ++c) list_off.v[c] = off[c];
 
     timer_begin(ctx, T_CLASSIFY, s);
     hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, s, counters);
@@ -157,11 +163,11 @@ als_status launch_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V,
     if ((st = launch_primal_long(ctx, Y, V, G, prm, X, long_rows, n_long, segs, n_seg, s_primal)) != ALS_OK) return st;
     if ((st = launch_primal_fused(ctx, Y, V, G, prm, X, r0, mid_list, n_mid, s_primal)) != ALS_OK) return st;
     if (dual_max > 0) {
-        const int32_t *lists[8];
-        int counts[8];
-        for (int c = 0; c < 8; ++c) {
+        const int32_t *lists[10];
+        int counts[10];
+        for (int c = 0; c < 10; ++c) {
             lists[c] = dual_lists + off[c];
-            counts[c] = ctx->host_counters[8 + c];
+            counts[c] = ctx->host_counters[c < 8 ? 8 + c : c - 3];  // [5], [6]: the two small classes
         }
         if ((st = launch_dual_rows(ctx, Y, X, r0, r1, dual_max, lists, counts, s)) != ALS_OK) return st;
     }

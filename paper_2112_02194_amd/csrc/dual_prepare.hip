@@ -13,7 +13,8 @@
 //   row kernels       by class of k (fixed by measurement on MI355X): all gather Z_I straight into MFMA
 //                     operand registers, form S = I + Z_I Z_I^T on the matrix cores, solve the k x k
 //                     system on the vector ALU, then r = Z_I^T t
-//       dual_rows_kernel   k <= 16: four rows per wavefront, one lane per row of S, DPP broadcasts;
+//       dual_small_kernel  k <= 4 and 5 <= k <= 8: several rows share one 16-entry MFMA tile
+//       dual_rows_kernel   8 < k <= 16: four rows per wavefront, one lane per row of S, DPP broadcasts;
 //                          48 < k <= 64: one row per wavefront, column broadcast through LDS
 //       dual_multi_kernel  16 < k <= 48: four rows per wavefront, 2-3 rows of S per lane, DPP only
 //       dual_wide_kernel   64 < k <= 128 (d = 128): one row per wavefront, S as a packed triangle in

@@ -1,4 +1,4 @@
-// Dual row update, one lane per row of the k x k system: the kernel of the classes k <= 16 (four rows
+// Dual row update, one lane per row of the k x k system: the kernel of the classes 8 < k <= 16 (four rows
 // per wavefront, gathered entries kept in registers and copied to LDS for r = Z_I^T t) and
 // 48 < k <= 64 (one row per wavefront, second gather instead of the copy).  Compiled once per class
 // with -DROWS_K=16 / -DROWS_K=64.  The algebra is in the header comment of dual_prepare.hip.
@@ -7,6 +7,7 @@
 #ifndef ROWS_K
 #error "compile with -DROWS_K=16 or -DROWS_K=64"
 #endif
+static_assert(ROWS_K == 16 || ROWS_K == 64, "only these two classes are built from this kernel");
 
 namespace als {
 

@@ -195,6 +195,30 @@ def test_c1_four_epochs_end_to_end(ctx, gpu_device):
         prev = lg
 
 
+def test_bf16_tables_with_small_lambda_track_the_oracle(ctx, gpu_device):
+    """Section 4.4's policy (bf16 storage, fp32 arithmetic, one rounding on store) over four epochs of a
+    configuration-1 shaped problem with a small regulariser: embeddings stay within the bf16 tolerance of the
+    oracle run with the same storage rounding, and the loss keeps falling."""
+    say("bf16 tables, lambda = 1e-4, four epochs")
+    p = make_problem("c1", rows=1200, cols=900, d=32, dtype="bf16")
+    lam = 1e-4
+    Y, Yt = to_dev(p, gpu_device)
+    W, H = p.W0.to(gpu_device), p.H0.to(gpu_device)
+    prm = als.make_params(p.alpha, lam)
+    Yh, Yth = host_csr(p.indptr, p.indices, None), host_csr(p.t_indptr, p.t_indices, None)
+    Wo, Ho = f64(p.W0), f64(p.H0)
+    prev = als.als_loss(ctx, Y, W, H, prm)
+    for ep in range(4):
+        als.als_epoch(ctx, Y, Yt, W, H, prm)
+        Wo, Ho = oracle.epoch(Yh, Yth, Wo, Ho, p.alpha, lam, storage="bf16")
+        lg, lo = als.als_loss(ctx, Y, W, H, prm), oracle.loss(Yh, Wo, Ho, p.alpha, lam)
+        say(f"  epoch {ep}: loss gpu {lg:.4f} oracle {lo:.4f} errW {rel_fro(f64(W), Wo):.2e} errH {rel_fro(f64(H), Ho):.2e}")
+        assert rel_fro(f64(W), Wo) <= 1e-2 and rel_fro(f64(H), Ho) <= 1e-2
+        assert abs(lg - lo) <= 1e-2 * abs(lo)
+        assert lg <= prev * 1.01  # storage rounding may cost a little of the exact decrease
+        prev = lg
+
+
 def test_loss_matches_oracle_general_labels_and_bf16(ctx, gpu_device):
     for d, dtype, values in ((16, "f32", "uniform"), (64, "f32", "ones"), (128, "bf16", "uniform"), (32, "bf16", "ones")):
         say(f"loss d={d} dtype={dtype} values={values}")

@@ -33,13 +33,6 @@ template <int GW, int C> __device__ __forceinline__ float group_bcast(float x) {
     }
 }
 
-// x + (x rotated by N lanes inside each row of 16 lanes)
-template <int N> __device__ __forceinline__ float add_row_ror(float x) {
-    const int r = __builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x120 + N, 0xf, 0xf, false);
-    return x + __int_as_float(r);
-}
-
-
 // per-class launchers, one translation unit each (they compile in parallel)
 void launch_dual_k16(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
                      int count, int32_t *err, hipStream_t s);

@@ -34,8 +34,8 @@ template <int D, int K, bool RG> struct DualCfg {
 //      S = I + Z_I Z_I^T goes to LDS;
 //   2. lane i of a row's group of GW lanes owns row i of S: right-looking Cholesky with the column
 //      broadcast inside the group, then L w = y, then L^T t = w with L read back transposed;
-//   3. r = Z_I^T t, either from an LDS copy of Z_I with one lane per output column pair, or (K > 32)
-//      by a cross-lane reduction of the lanes' own pieces.
+//   3. r = Z_I^T t with one lane per pair of output columns, either from an LDS copy of Z_I (RG = false,
+//      K <= 32) or by gathering the row's entries a second time (RG = true).
 template <int D, int K, bool RG>
 __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict__ indptr,
                                                        const int32_t *__restrict__ indices,
@@ -291,31 +291,9 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
             }
         }
     } else {
-        // scale this lane's pieces by t_e, add over the tiles, then over the 16 lanes a of each q
-        float4 rp[NJ];
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) rp[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-        for (int t = 0; t < KT; ++t) {
-            const float te = __shfl(yv, 16 * t + a);
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-                rp[j].x += te * z[0][t][j].x; rp[j].y += te * z[0][t][j].y;
-                rp[j].z += te * z[0][t][j].z; rp[j].w += te * z[0][t][j].w;
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-            float4 v = rp[j];
-            v.x = add_row_ror<8>(v.x); v.y = add_row_ror<8>(v.y); v.z = add_row_ror<8>(v.z); v.w = add_row_ror<8>(v.w);
-            v.x = add_row_ror<4>(v.x); v.y = add_row_ror<4>(v.y); v.z = add_row_ror<4>(v.z); v.w = add_row_ror<4>(v.w);
-            v.x = add_row_ror<2>(v.x); v.y = add_row_ror<2>(v.y); v.z = add_row_ror<2>(v.z); v.w = add_row_ror<2>(v.w);
-            v.x = add_row_ror<1>(v.x); v.y = add_row_ror<1>(v.y); v.z = add_row_ror<1>(v.z); v.w = add_row_ror<1>(v.w);
-            if (a == j && u[0] >= 0) *(float4 *)(R + u[0] * ldr + (4 * j + q) * 4) = v;
-        }
+        static_assert(RG || C::ZBUF, "r = Z_I^T t needs either the LDS copy (K <= 32) or the second gather");
     }
 }
-
 
 template <int D>
 static void launch_rows_typed(const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,

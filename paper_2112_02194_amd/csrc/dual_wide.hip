@@ -1,6 +1,7 @@
 // Dual row update for 64 < k <= 128 (d = 128 only), compiled once per class with -DWIDE_KT=5..8
 // (k <= 16*WIDE_KT).  The algebra is in the header comment of dual_prepare.hip.
 #include "dual_common.h"
+#include "tri_solve.h"
 
 #ifndef WIDE_KT
 #error "compile with -DWIDE_KT=5, 6, 7 or 8"
@@ -11,17 +12,13 @@ namespace als {
 // One wavefront per row with k <= K = 16*KT entries (KT = 5..8).
 //   1. S = I + Z_I Z_I^T tile by tile: the wavefront keeps the 16 entries of tile t1 in registers (B
 //      operand) and streams the tiles t2 <= t1 past them (A operand, fetched again from the caches);
-//      each finished 16x16 tile goes to LDS, where S is kept as a packed lower triangle.
-//   2. Elimination S = M P M^T with lane i owning rows i and 64+i (columns 0..63 of the first, all of
-//      the second, in registers): per step the column is published in LDS and read back by broadcast,
-//      pivot and right-hand-side entry come straight from the owning lane; u = M^{-1} y rides along.
-//   3. Back-substitution with the factor read transposed from LDS, the value just found taken from
-//      its lane.
+//      each finished 16x16 tile goes to LDS, where S is kept as a lower triangle.
+//   2./3. Block elimination S = M P M^T and back-substitution by the wavefront (tri_solve.h).
 //   4. r = Z_I^T t with one lane per pair of output columns, gathering the entries a second time.
 template <int D, int KT> struct WideCfg {
     static constexpr int K = 16 * KT;
-    static constexpr int TRI = K * (K + 1) / 2;      // packed lower triangle
-    static constexpr int OFF_COL = TRI;              // colbuf[2][K]
+    static constexpr int TRI = tri_row(K);           // lower triangle, rows padded (tri_solve.h)
+    static constexpr int OFF_COL = TRI;              // solver's auxiliary buffer (>= 128 floats)
     static constexpr int OFF_T = OFF_COL + 2 * K;    // tbuf[K]
     static constexpr int OFF_ID = OFF_T + K;         // ids[K]
     static constexpr int LDS_FLOATS = OFF_ID + K;
@@ -35,7 +32,7 @@ __global__ __launch_bounds__(64) void dual_wide_kernel(const int64_t *__restrict
                                                        int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
                                                        int32_t *__restrict__ err_flag) {
     using C = WideCfg<D, KT>;
-    constexpr int K = C::K, NJ = D / 16, K1 = K - 64;  // K1 = rows held as "second row" of a lane
+    constexpr int K = C::K, NJ = D / 16;
     extern __shared__ float lds[];
     float *tri = lds, *colbuf = lds + C::OFF_COL, *tbuf = lds + C::OFF_T;
     int32_t *ids = (int32_t *)(lds + C::OFF_ID);
@@ -91,94 +88,19 @@ __global__ __launch_bounds__(64) void dual_wide_kernel(const int64_t *__restrict
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int c = 16 * t2 + 4 * q + v;
-                if (c <= Rr) tri[Rr * (Rr + 1) / 2 + c] = acc[v] + (c == Rr ? 1.f : 0.f);
+                if (c <= Rr) tri[tri_row(Rr) + c] = acc[v] + (c == Rr ? 1.f : 0.f);
             }
         }
     }
     wave_sync();
 
-    // ---- 2. elimination; lane i owns rows i (columns 0..63) and 64+i (all columns, if 64+i < K)
-    const int ra = lane, rb = 64 + lane;
-    const bool hasb = rb < K;
-    float s0[64], s1[K];
-#pragma unroll
-    for (int c = 0; c < 64; ++c) s0[c] = c <= ra ? tri[ra * (ra + 1) / 2 + c] : 0.f;
-#pragma unroll
-    for (int c = 0; c < K; ++c) s1[c] = (hasb && c <= rb) ? tri[rb * (rb + 1) / 2 + c] : 0.f;
-    float y0 = 0.f, y1 = 0.f;
-    if (ra < k) y0 = values ? values[b + ra] : 1.f;
-    if (rb < k) y1 = values ? values[b + rb] : 1.f;
-    float rp0 = 1.f, rp1 = 1.f;
-    bool bad = false;
-    wave_sync();
-    static_for<0, K>([&](auto cc) {
-        constexpr int c = decltype(cc)::value;
-        if (c < k) {  // the remaining rows are identity rows with zero right-hand side
-            float *cb = colbuf + (c & 1) * K;
-            float pivot, uc;
-            if constexpr (c < 64) {
-                cb[lane] = s0[c];
-                if (hasb) cb[64 + lane] = s1[c];
-                pivot = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s0[c]), c));
-                uc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(y0), c));
-            } else {
-                if (hasb) cb[64 + lane] = s1[c];
-                pivot = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s1[c]), c - 64));
-                uc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(y1), c - 64));
-            }
-            bad |= !(pivot > 0.f);
-            float rp = __builtin_amdgcn_rcpf(pivot);
-            rp = rp * (2.f - pivot * rp);  // one Newton step on the hardware reciprocal
-            float f0 = 0.f;
-            if constexpr (c < 64) {
-                rp0 = ra == c ? rp : rp0;
-                f0 = ra > c ? s0[c] * rp : 0.f;
-                y0 -= f0 * uc;
-            }
-            rp1 = rb == c ? rp : rp1;
-            const float f1 = rb > c ? s1[c] * rp : 0.f;  // lanes without a second row hold zeros in s1
-            y1 -= f1 * uc;
-            wave_sync();
-            static_for<(c + 1) / 4, K / 4>([&](auto jj) {
-                constexpr int j4 = decltype(jj)::value;
-                const float4 col = *(const float4 *)(cb + 4 * j4);
-                if constexpr (4 * j4 + 0 > c) { if constexpr (4 * j4 + 0 < 64 && c < 64) s0[4 * j4 + 0] -= f0 * col.x; s1[4 * j4 + 0] -= f1 * col.x; }
-                if constexpr (4 * j4 + 1 > c) { if constexpr (4 * j4 + 1 < 64 && c < 64) s0[4 * j4 + 1] -= f0 * col.y; s1[4 * j4 + 1] -= f1 * col.y; }
-                if constexpr (4 * j4 + 2 > c) { if constexpr (4 * j4 + 2 < 64 && c < 64) s0[4 * j4 + 2] -= f0 * col.z; s1[4 * j4 + 2] -= f1 * col.z; }
-                if constexpr (4 * j4 + 3 > c) { if constexpr (4 * j4 + 3 < 64 && c < 64) s0[4 * j4 + 3] -= f0 * col.w; s1[4 * j4 + 3] -= f1 * col.w; }
-            });
-        }
-    });
-    if (bad && lane == 0) atomicOr(err_flag, 1);
-
-    // ---- 3. t_c = (u_c - sum_{Rr>c} S'[Rr][c] t_Rr) / pivot_c; the factor goes back to the packed triangle
-#pragma unroll
-    for (int c = 0; c < 64; ++c)
-        if (c <= ra) tri[ra * (ra + 1) / 2 + c] = s0[c];
-#pragma unroll
-    for (int c = 0; c < K; ++c)
-        if (hasb && c <= rb) tri[rb * (rb + 1) / 2 + c] = s1[c];
-    wave_sync();
+    // ---- 2./3. elimination and back-substitution (tri_solve.h); lane i holds the labels of entries i, 64+i
     {
-        float t0 = 0.f, t1v = 0.f;
-#pragma unroll 4
-        for (int Rr = (k < K ? k : K) - 1; Rr >= 64; --Rr) {
-            const float tR = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(y1 * rp1), Rr - 64));
-            t1v = rb == Rr ? tR : t1v;
-            const int base = Rr * (Rr + 1) / 2;
-            if (rb < Rr) y1 -= tri[base + rb] * tR;
-            y0 -= tri[base + ra] * tR;
-        }
-#pragma unroll 4
-        for (int Rr = (k < 64 ? k : 64) - 1; Rr >= 0; --Rr) {
-            const float tR = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(y0 * rp0), Rr));
-            t0 = ra == Rr ? tR : t0;
-            if (ra < Rr) y0 -= tri[Rr * (Rr + 1) / 2 + ra] * tR;
-        }
-        tbuf[ra] = t0;
-        if (hasb) tbuf[rb] = t1v;
+        float y0 = 0.f, y1 = 0.f;
+        if (lane < k) y0 = values ? values[b + lane] : 1.f;
+        if (64 + lane < k) y1 = values ? values[b + 64 + lane] : 1.f;
+        tri_solve<K>(tri, colbuf, tbuf, y0, y1, k, err_flag);
     }
-    wave_sync();
 
     // ---- 4. r = Z_I^T t, one lane per pair of output columns (second gather of the row's entries)
     {

@@ -17,6 +17,7 @@
 #include <type_traits>
 
 #include "als_internal.h"
+#include "tri_solve.h"
 
 namespace als {
 
@@ -126,129 +127,34 @@ __device__ __forceinline__ void cholesky_solve_lds(float *a, float *aux, int32_t
     }
 }
 
-// ---------------------------------------------------------------------------------------------- register solve
-template <int B, int E, class F> __device__ __forceinline__ void static_for_p(F &&f) {
-    if constexpr (B < E) {
-        f(std::integral_constant<int, B>{});
-        static_for_p<B + 1, E>(f);
-    }
+// ---------------------------------------------------------------------------------------------- one-wavefront solve
+// LDS layout of the direct solver for D >= 64: lower triangle, the solver's auxiliary and result
+// buffers (tri_solve.h), the right-hand side.
+template <int D> struct Packed {
+    static constexpr int TRI = tri_row(D);
+    static constexpr int OFF_COL = TRI;            // aux[2*D] (the solver needs 128 floats)
+    static constexpr int OFF_T = OFF_COL + 2 * D;  // tbuf[D]
+    static constexpr int OFF_RHS = OFF_T + D;      // rhs[D]
+    static constexpr size_t LDS_BYTES = (size_t)(OFF_RHS + D) * sizeof(float);
+};
+
+// Called by one wavefront after a workgroup barrier: solves the packed system and stores the row,
+// rounded once to the table's element type.  The other wavefronts of the workgroup may have exited.
+template <int D, bool BF16>
+__device__ __forceinline__ void packed_solve_store(float *lds, void *X, int64_t xoff, int32_t *err_flag) {
+    const int lane = threadIdx.x & 63;
+    float *tbuf = lds + Packed<D>::OFF_T;
+    const float *rhs = lds + Packed<D>::OFF_RHS;
+    const float y0 = lane < D ? rhs[lane] : 0.f;
+    const float y1 = (D > 64 && 64 + lane < D) ? rhs[64 + lane] : 0.f;
+    int k = D;
+    asm volatile("" : "+s"(k));  // opaque on purpose: with a compile-time step count the solver's steps merge
+                                 // into one block, whose scheduling runs out of registers
+    tri_solve<D>(lds, lds + Packed<D>::OFF_COL, tbuf, y0, y1, k, err_flag);
+    for (int c = lane; c < D; c += 64) store_elem<BF16>(X, xoff + c, tbuf[c]);
 }
 
-// Same system as cholesky_solve_lds, for D >= 64 with 2*D <= blockDim threads: the matrix lives in
-// registers.  Thread (R = tid % D, h = tid / D) holds the CW = D/2 columns [CW*h, CW*h + CW) of row R.
-// Elimination A = M P M^T (M unit lower, P the pivots) one column per step: the owners publish the
-// column in LDS (double-buffered by step parity), one workgroup barrier, every thread reads the pivot
-// and the column back with broadcast reads and updates its registers; u = M^{-1} b rides along.  The
-// back-substitution gives unknown c to thread c and works through it 64 unknowns at a time with
-// wavefront-level steps (factor read transposed from LDS).  On entry a[c*LD + r] holds entry (r, c)
-// (full matrix) and aux + 3*D the right-hand side; on exit aux + 2*D holds the solution.
-template <int D>
-__device__ __forceinline__ void solve_rowsplit(float *a, float *aux, int32_t *err_flag) {
-    constexpr int LD = Team<D>::LD, CW = D / 2, NG = D / 4;
-    float *xout = aux + 2 * D, *bvec = aux + 3 * D, *colbuf = aux + 4 * D, *yb = aux + 6 * D;
-    float *pbuf = aux, *ubuf = aux + D;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const bool active = tid < 2 * D;
-    const int R = tid % D, h = active ? tid / D : 0;  // h is uniform inside a wavefront (D >= 64)
-    float s[CW];
-#pragma unroll
-    for (int i = 0; i < CW; ++i) s[i] = a[(CW * h + i) * LD + R];
-    float yv = bvec[R], mypiv = 1.f;
-    bool bad = false;
-    static_for_p<0, NG>([&](auto gg) {
-        constexpr int g = decltype(gg)::value;
-        constexpr int ho = (4 * g) / CW, lb = 4 * g - CW * ho;  // owner half and local index of the group
-#pragma unroll 1
-        for (int v = 0; v < 4; ++v) {
-            const int c = 4 * g + v;
-            float *cb = colbuf + (c & 1) * D;
-            if (active && h == ho) {
-                const float mine = v == 0 ? s[lb] : (v == 1 ? s[lb + 1] : (v == 2 ? s[lb + 2] : s[lb + 3]));
-                cb[R] = mine;  // entry (R, c) as it stands (column c is final)
-                if (R == c) yb[c & 1] = yv;
-            }
-            __syncthreads();
-            if (active && h >= ho) {
-                const float pivot = cb[c];
-                const float uc = yb[c & 1];
-                const float mine = cb[R];
-                bad |= !(pivot > 0.f);
-                float rp = __builtin_amdgcn_rcpf(pivot);
-                rp = rp * (2.f - pivot * rp);  // one Newton step on the hardware reciprocal
-                mypiv = R == c ? pivot : mypiv;
-                const float f = R > c ? mine * rp : 0.f;  // M[R][c]; rows above stay as they are
-                if (h == ho) yv -= f * uc;                 // the owner half carries the right-hand side
-                if (h == ho) {
-                    static_for_p<lb / 4, CW / 4>([&](auto ii) {
-                        constexpr int i4 = decltype(ii)::value;
-                        const float4 col = *(const float4 *)(cb + CW * ho + 4 * i4);
-                        if constexpr (i4 == lb / 4) {  // the group's own columns: only those right of c
-                            if (0 > v) s[4 * i4 + 0] -= f * col.x;
-                            if (1 > v) s[4 * i4 + 1] -= f * col.y;
-                            if (2 > v) s[4 * i4 + 2] -= f * col.z;
-                            if (3 > v) s[4 * i4 + 3] -= f * col.w;
-                        } else {
-                            s[4 * i4 + 0] -= f * col.x; s[4 * i4 + 1] -= f * col.y;
-                            s[4 * i4 + 2] -= f * col.z; s[4 * i4 + 3] -= f * col.w;
-                        }
-                    });
-                } else {  // h > ho: every column of this half lies right of c
-                    yv -= f * uc;
-#pragma unroll
-                    for (int i4 = 0; i4 < CW / 4; ++i4) {
-                        const float4 col = *(const float4 *)(cb + CW * h + 4 * i4);
-                        s[4 * i4 + 0] -= f * col.x; s[4 * i4 + 1] -= f * col.y;
-                        s[4 * i4 + 2] -= f * col.z; s[4 * i4 + 3] -= f * col.w;
-                    }
-                }
-            }
-        }
-    });
-    if (bad && tid == 0) atomicOr(err_flag, 1);
-    // factor back to LDS (same places: a[c*LD + R] = entry (R, c)), pivots and u for the owners of the unknowns
-    if (active) {
-#pragma unroll
-        for (int i = 0; i < CW; ++i) a[(CW * h + i) * LD + R] = s[i];
-        if (h == 1) {  // the second half saw every column, so its copy of u is complete
-            ubuf[R] = yv;
-            pbuf[R] = mypiv;
-        }
-    }
-    __syncthreads();
-    {
-        constexpr int NW = D / 64;
-        float accv = 0.f, rpiv = 0.f, tmine = 0.f;
-        if (tid < D) {
-            accv = ubuf[tid];
-            rpiv = 1.0f / pbuf[tid];
-        }
-        for (int chunk = NW - 1; chunk >= 0; --chunk) {
-            const int lo = 64 * chunk;
-            if (w == chunk) {
-#pragma unroll 4
-                for (int Rr = lo + 63; Rr >= lo; --Rr) {
-                    const float tR = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(accv * rpiv), Rr - lo));
-                    tmine = tid == Rr ? tR : tmine;
-                    if (tid < Rr) accv -= a[tid * LD + Rr] * tR;  // entry (Rr, tid)
-                }
-                xout[tid] = tmine;
-            }
-            __syncthreads();
-            if (w < chunk) {
-#pragma unroll 4
-                for (int Rr = lo + 63; Rr >= lo; --Rr) accv -= a[tid * LD + Rr] * xout[Rr];
-            }
-        }
-    }
-    (void)lane;
-}
-
-// Conjugate gradients on the assembled system (the solver the paper settles on, Section 4.5), one
-// thread per unknown, all vectors in LDS.  a[c*LD + r] holds entry (r, c) of the full symmetric
-// matrix, aux + 3*D the right-hand side and aux + 2*D the start vector on entry, the solution on
-// exit.  Stops when |residual| <= tol * |b| (checked with the recurrence residual) or after
-// max_iters iterations.  Sums over the unknowns are fixed-order (wavefront shuffles, then wavefronts
-// in order), so the result is reproducible.
+// ---------------------------------------------------------------------------------------------- conjugate gradients
 template <int D>
 __device__ __forceinline__ float block_dot(float v, float *red /* [THREADS/64] */) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -310,11 +216,7 @@ __device__ __forceinline__ void solve_spd_lds(float *a, float *aux, int32_t *err
         cg_solve_lds<D>(a, aux, cg_iters, cg_tol);
         return;
     }
-    if constexpr (D >= 64) {
-        solve_rowsplit<D>(a, aux, err_flag);
-    } else {
-        cholesky_solve_lds<D>(a, aux, err_flag);
-    }
+    if constexpr (D < 64) cholesky_solve_lds<D>(a, aux, err_flag);  // D >= 64: packed path of the callers
 }
 
 // ---------------------------------------------------------------------------------------------- kernels
@@ -375,6 +277,29 @@ __global__ __launch_bounds__(Team<D>::THREADS, 2) void primal_kernel(
         }
         return;
     } else {
+        if constexpr (D >= 64) {
+            if (solver == ALS_SOLVER_DIRECT) {  // uniform for the launch
+                // lower triangle of A = alpha*G + lambda*I + V_I^T V_I, packed, then one wavefront solves
+                float *tri = lds, *rhs = lds + Packed<D>::OFF_RHS;
+#pragma unroll
+                for (int j = 0; j < NC; ++j)
+#pragma unroll
+                    for (int v = 0; v < ACC; ++v) {
+                        const int r = NC * acc_row<D>(v, lane) + wave, c = NC * m + j;
+                        if (c <= r)
+                            tri[tri_row(r) + c] = acc[j][v] + alpha * G[r * D + c] + (r == c ? lambda : 0.f);
+                    }
+                if (wave == 0 && kk == 0) {
+#pragma unroll
+                    for (int j = 0; j < NC; ++j) rhs[NC * m + j] = bsum[j];
+                }
+                __syncthreads();
+                // scalar test: the solver must not sit in (what looks like) divergent control flow
+                if (__builtin_amdgcn_readfirstlane(wave) != 0) return;
+                packed_solve_store<D, BF16>(lds, X, u * ldx, err_flag);
+                return;
+            }
+        }
         // A = alpha*G + lambda*I + V_I^T V_I into LDS (entry (r,c) at a[c*LD + r])
 #pragma unroll
         for (int j = 0; j < NC; ++j)
@@ -429,6 +354,24 @@ __global__ __launch_bounds__(Team<D>::THREADS) void reduce_solve_kernel(
     float *a = lds, *aux = lds + D * LD, *bvec = aux + 3 * D;
     const LongRow lr = long_rows[blockIdx.x];
     const float *p0 = partials + (int64_t)lr.seg_first * (D * D + D);
+    if constexpr (D >= 64) {
+        if (solver == ALS_SOLVER_DIRECT) {
+            float *tri = lds, *rhs = lds + Packed<D>::OFF_RHS;
+            for (int e = threadIdx.x; e < D * D + D; e += T) {
+                const float s = p0[e];
+                if (e < D * D) {
+                    const int r = e / D, c = e % D;
+                    if (c <= r) tri[tri_row(r) + c] = s + alpha * G[e] + (r == c ? lambda : 0.f);
+                } else {
+                    rhs[e - D * D] = s;
+                }
+            }
+            __syncthreads();
+            if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) != 0) return;
+            packed_solve_store<D, BF16>(lds, X, lr.row * ldx, err_flag);
+            return;
+        }
+    }
     for (int e = threadIdx.x; e < D * D + D; e += T) {
         const float s = p0[e];
         if (e < D * D) {
@@ -448,6 +391,13 @@ __global__ __launch_bounds__(Team<D>::THREADS) void reduce_solve_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------- launchers
+template <int D> static size_t solve_lds_bytes(int solver) {
+    if constexpr (D >= 64) {
+        if (solver == ALS_SOLVER_DIRECT) return Packed<D>::LDS_BYTES;
+    }
+    return Team<D>::LDS_BYTES;
+}
+
 template <int D, bool BF16>
 static als_status primal_typed(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
                                const als_params *prm, als_table *X, int64_t r0, const int32_t *row_list,
@@ -459,8 +409,9 @@ static als_status primal_typed(als_ctx *ctx, const als_csr *Y, const als_table *
     auto kern = primal_kernel<D, BF16, MODE_FUSED>;
     ALS_HIP(ctx, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)Team<D>::LDS_BYTES));
+    const size_t lds_bytes = solve_lds_bytes<D>(prm->solver);
     timer_begin(ctx, T_PRIMAL, s);
-    hipLaunchKernelGGL(kern, dim3((unsigned)nitems), dim3(Team<D>::THREADS), Team<D>::LDS_BYTES, s, Y->indptr,
+    hipLaunchKernelGGL(kern, dim3((unsigned)nitems), dim3(Team<D>::THREADS), lds_bytes, s, Y->indptr,
                        Y->indices, Y->values, V->data, V->ld, G, prm->alpha, prm->lambda, X->data, X->ld, r0,
                        row_list, (const Segment *)nullptr, (float *)nullptr, err, prm->solver, cg_iters, cg_tol);
     timer_end(ctx, s);
@@ -490,7 +441,7 @@ static als_status long_typed(als_ctx *ctx, const als_csr *Y, const als_table *V,
     timer_begin(ctx, T_REDUCE, s);
     hipLaunchKernelGGL(reduce_partials_kernel<D>, dim3((unsigned)n_long, (D * D + D + 255) / 256), dim3(256), 0, s,
                        long_rows, (float *)ctx->seg_partials.p);
-    hipLaunchKernelGGL(kred, dim3((unsigned)n_long), dim3(Team<D>::THREADS), Team<D>::LDS_BYTES, s, long_rows,
+    hipLaunchKernelGGL(kred, dim3((unsigned)n_long), dim3(Team<D>::THREADS), solve_lds_bytes<D>(prm->solver), s, long_rows,
                        (const float *)ctx->seg_partials.p, G, prm->alpha, prm->lambda, X->data, X->ld, err, prm->solver,
                        cg_iters, cg_tol);
     timer_end(ctx, s);

@@ -18,14 +18,14 @@ namespace als {
 template <int D, int KT> struct WideCfg {
     static constexpr int K = 16 * KT;
     static constexpr int TRI = tri_row(K);           // lower triangle, rows padded (tri_solve.h)
-    static constexpr int OFF_COL = TRI;              // solver's auxiliary buffer (>= 128 floats)
-    static constexpr int OFF_T = OFF_COL + 2 * K;    // tbuf[K]
+    static constexpr int OFF_COL = TRI;              // solver's auxiliary buffer
+    static constexpr int OFF_T = OFF_COL + TRI_AUX_FLOATS;  // tbuf[K]
     static constexpr int OFF_ID = OFF_T + K;         // ids[K]
     static constexpr int LDS_FLOATS = OFF_ID + K;
 };
 
 template <int D, int KT>
-__global__ __launch_bounds__(64) void dual_wide_kernel(const int64_t *__restrict__ indptr,
+__global__ __launch_bounds__(64, 2) void dual_wide_kernel(const int64_t *__restrict__ indptr,
                                                        const int32_t *__restrict__ indices,
                                                        const float *__restrict__ values,
                                                        const float *__restrict__ Z, float *__restrict__ R,
@@ -34,7 +34,7 @@ __global__ __launch_bounds__(64) void dual_wide_kernel(const int64_t *__restrict
     using C = WideCfg<D, KT>;
     constexpr int K = C::K, NJ = D / 16;
     extern __shared__ float lds[];
-    float *tri = lds, *colbuf = lds + C::OFF_COL, *tbuf = lds + C::OFF_T;
+    float *tri = lds, *aux = lds + C::OFF_COL, *tbuf = lds + C::OFF_T;
     int32_t *ids = (int32_t *)(lds + C::OFF_ID);
     const int lane = threadIdx.x, a = lane & 15, q = lane >> 4;
     const int64_t u = r0 + list[blockIdx.x];
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(64) void dual_wide_kernel(const int64_t *__restrict
         float y0 = 0.f, y1 = 0.f;
         if (lane < k) y0 = values ? values[b + lane] : 1.f;
         if (64 + lane < k) y1 = values ? values[b + 64 + lane] : 1.f;
-        tri_solve<K>(tri, colbuf, tbuf, y0, y1, k, err_flag);
+        tri_solve<K>(tri, aux, tbuf, y0, y1, k, err_flag);
     }
 
     // ---- 4. r = Z_I^T t, one lane per pair of output columns (second gather of the row's entries)

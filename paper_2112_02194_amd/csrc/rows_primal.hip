@@ -132,8 +132,8 @@ __device__ __forceinline__ void cholesky_solve_lds(float *a, float *aux, int32_t
 // buffers (tri_solve.h), the right-hand side.
 template <int D> struct Packed {
     static constexpr int TRI = tri_row(D);
-    static constexpr int OFF_COL = TRI;            // aux[2*D] (the solver needs 128 floats)
-    static constexpr int OFF_T = OFF_COL + 2 * D;  // tbuf[D]
+    static constexpr int OFF_COL = TRI;                        // the solver's auxiliary buffer
+    static constexpr int OFF_T = OFF_COL + TRI_AUX_FLOATS;     // tbuf[D]
     static constexpr int OFF_RHS = OFF_T + D;      // rhs[D]
     static constexpr size_t LDS_BYTES = (size_t)(OFF_RHS + D) * sizeof(float);
 };

@@ -24,12 +24,12 @@ UNITS = [
     ("solve_rows.hip", "solve_rows", []),
     ("loss.hip", "loss", []),
     ("dual_prepare.hip", "dual_prepare", []),
-    ("dual_rows.hip", "dual_rows_k16", ["-DROWS_K=16"]),
-    ("dual_rows.hip", "dual_rows_k64", ["-DROWS_K=64"]),
+    ("dual_rows.hip", "dual_rows", []),
     ("dual_small.hip", "dual_small_g8", ["-DSMALL_G=8"]),
     ("dual_small.hip", "dual_small_g4", ["-DSMALL_G=4"]),
-    ("dual_multi.hip", "dual_multi_m2", ["-DMULTI_M=2"]),
-    ("dual_multi.hip", "dual_multi_m3", ["-DMULTI_M=3"]),
+    ("dual_multi.hip", "dual_multi", []),
+    ("dual_wide.hip", "dual_wide_3", ["-DWIDE_KT=3"]),
+    ("dual_wide.hip", "dual_wide_4", ["-DWIDE_KT=4"]),
     ("dual_wide.hip", "dual_wide_5", ["-DWIDE_KT=5"]),
     ("dual_wide.hip", "dual_wide_6", ["-DWIDE_KT=6"]),
     ("dual_wide.hip", "dual_wide_7", ["-DWIDE_KT=7"]),

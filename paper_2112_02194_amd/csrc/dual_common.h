@@ -36,7 +36,5 @@ template <int GW, int C> __device__ __forceinline__ float group_bcast(float x) {
 // per-class launchers, one translation unit each (they compile in parallel)
 void launch_dual_k16(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
                      int count, int32_t *err, hipStream_t s);
-void launch_dual_k64(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                     int count, int32_t *err, hipStream_t s);
 
 }  // namespace als

@@ -1,10 +1,9 @@
-// Dual row update for 16 < k <= 48, compiled once per class with -DMULTI_M=2 (k <= 32) and -DMULTI_M=3
-// (k <= 48).  The algebra is in the header comment of dual_prepare.hip.
+// Dual row update for rows with 16 < k <= 32 stored entries.  The algebra is in the header comment of
+// dual_prepare.hip.  The kernel is written for M rows of S per lane (k <= 16*M); M = 2 is the one in
+// use (for 32 < k <= 48, M = 3 was measured slower than the one-row-per-wavefront kernel).
 #include "dual_common.h"
 
-#ifndef MULTI_M
-#error "compile with -DMULTI_M=2 or -DMULTI_M=3"
-#endif
+#define MULTI_M 2
 
 namespace als {
 
@@ -223,7 +222,6 @@ static void launch_multi_typed(const als_csr *Y, const float *Z, float *R, int64
                        C::LDS_FLOATS * sizeof(float), s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count, err);
 }
 
-#if MULTI_M == 2
 void launch_dual_multi2(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
                         int count, int32_t *err, hipStream_t s) {
     switch (d) {  // the dual form stops at k = d
@@ -232,14 +230,5 @@ void launch_dual_multi2(int d, const als_csr *Y, const float *Z, float *R, int64
         case 128: launch_multi_typed<128>(Y, Z, R, ldr, r0, list, count, err, s); break;
     }
 }
-#else
-void launch_dual_multi3(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                        int count, int32_t *err, hipStream_t s) {
-    switch (d) {
-        case 64: launch_multi_typed<64>(Y, Z, R, ldr, r0, list, count, err, s); break;
-        case 128: launch_multi_typed<128>(Y, Z, R, ldr, r0, list, count, err, s); break;
-    }
-}
-#endif
 
 }  // namespace als

@@ -14,11 +14,10 @@
 //                     operand registers, form S = I + Z_I Z_I^T on the matrix cores, solve the k x k
 //                     system on the vector ALU, then r = Z_I^T t
 //       dual_small_kernel  k <= 4 and 5 <= k <= 8: several rows share one 16-entry MFMA tile
-//       dual_rows_kernel   8 < k <= 16: four rows per wavefront, one lane per row of S, DPP broadcasts;
-//                          48 < k <= 64: one row per wavefront, column broadcast through LDS
-//       dual_multi_kernel  16 < k <= 48: four rows per wavefront, 2-3 rows of S per lane, DPP only
-//       dual_wide_kernel   64 < k <= 128 (d = 128): one row per wavefront, S as a packed triangle in
-//                          LDS, two rows of S per lane
+//       dual_rows_kernel   8 < k <= 16: four rows per wavefront, one lane per row of S, DPP broadcasts
+//       dual_multi_kernel  16 < k <= 32: four rows per wavefront, two rows of S per lane, DPP only
+//       dual_wide_kernel   32 < k <= 128 (d >= 64; k <= 64 at d = 64): one row per wavefront, S as a
+//                          lower triangle in LDS, blocked elimination with MFMA trailing updates
 //   transform_kernel  X = R L^{-1}   (rows r -> L^{-T} r), rounding to the table's element type
 #include "dual_common.h"
 
@@ -30,12 +29,10 @@ void launch_dual_small8(int d, const als_csr *Y, const float *Z, float *R, int64
                         int count, int32_t *err, hipStream_t s);
 void launch_dual_multi2(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
                         int count, int32_t *err, hipStream_t s);
-void launch_dual_multi3(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                        int count, int32_t *err, hipStream_t s);
 #define ALS_DECL_WIDE(kt)                                                                                         \
-    als_status launch_dual_wide##kt(als_ctx *ctx, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, \
-                                    const int32_t *list, int count, int32_t *err, hipStream_t s);
-ALS_DECL_WIDE(5) ALS_DECL_WIDE(6) ALS_DECL_WIDE(7) ALS_DECL_WIDE(8)
+    als_status launch_dual_wide##kt(als_ctx *ctx, int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, \
+                                    int64_t r0, const int32_t *list, int count, int32_t *err, hipStream_t s);
+ALS_DECL_WIDE(3) ALS_DECL_WIDE(4) ALS_DECL_WIDE(5) ALS_DECL_WIDE(6) ALS_DECL_WIDE(7) ALS_DECL_WIDE(8)
 #undef ALS_DECL_WIDE
 
 // ---------------------------------------------------------------------------------------------- factor
@@ -220,7 +217,7 @@ static als_status dual_rows_typed(als_ctx *ctx, const als_csr *Y, als_table *X, 
     int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
     const float *Z = (const float *)ctx->ztable.p;
     // Independent classes run concurrently: the two largest on the caller's stream, 32 < k <= 64 on
-    // side stream 0, the workgroup kernels (k > 64) on side stream 1.  The caller has forked the side
+    // side stream 0, k > 64 on side stream 1.  The caller has forked the side
     // streams; they are joined before the closing transform, which reads every class's result.
     als_status stb = ALS_OK;
     const bool side = ctx->use_side_streams;
@@ -244,12 +241,12 @@ static als_status dual_rows_typed(als_ctx *ctx, const als_csr *Y, als_table *X, 
         launch_dual_small4(D, Y, Z, R, ldr, r0, lists[8], counts[8], err, s);
         timer_end(ctx, s);
     }
-    ALS_TIMED_CLASS(2, s_mid, (launch_dual_multi3(D, Y, Z, R, ldr, r0, lists[2], counts[2], err, cs)))
-    ALS_TIMED_CLASS(3, s_mid, (launch_dual_k64(D, Y, Z, R, ldr, r0, lists[3], counts[3], err, cs)))
-    ALS_TIMED_CLASS(4, s_big, (stb = launch_dual_wide5(ctx, Y, Z, R, ldr, r0, lists[4], counts[4], err, cs)))
-    ALS_TIMED_CLASS(5, s_big, (stb = launch_dual_wide6(ctx, Y, Z, R, ldr, r0, lists[5], counts[5], err, cs)))
-    ALS_TIMED_CLASS(6, s_big, (stb = launch_dual_wide7(ctx, Y, Z, R, ldr, r0, lists[6], counts[6], err, cs)))
-    ALS_TIMED_CLASS(7, s_big, (stb = launch_dual_wide8(ctx, Y, Z, R, ldr, r0, lists[7], counts[7], err, cs)))
+    ALS_TIMED_CLASS(2, s_mid, (stb = launch_dual_wide3(ctx, D, Y, Z, R, ldr, r0, lists[2], counts[2], err, cs)))
+    ALS_TIMED_CLASS(3, s_mid, (stb = launch_dual_wide4(ctx, D, Y, Z, R, ldr, r0, lists[3], counts[3], err, cs)))
+    ALS_TIMED_CLASS(4, s_big, (stb = launch_dual_wide5(ctx, D, Y, Z, R, ldr, r0, lists[4], counts[4], err, cs)))
+    ALS_TIMED_CLASS(5, s_big, (stb = launch_dual_wide6(ctx, D, Y, Z, R, ldr, r0, lists[5], counts[5], err, cs)))
+    ALS_TIMED_CLASS(6, s_big, (stb = launch_dual_wide7(ctx, D, Y, Z, R, ldr, r0, lists[6], counts[6], err, cs)))
+    ALS_TIMED_CLASS(7, s_big, (stb = launch_dual_wide8(ctx, D, Y, Z, R, ldr, r0, lists[7], counts[7], err, cs)))
 #undef ALS_TIMED_CLASS
     if (side && stb == ALS_OK) stb = side_join(ctx, 0, s);
     if (side && stb == ALS_OK) stb = side_join(ctx, 1, s);

@@ -1,56 +1,46 @@
-// Dual row update, one lane per row of the k x k system: the kernel of the classes 8 < k <= 16 (four rows
-// per wavefront, gathered entries kept in registers and copied to LDS for r = Z_I^T t) and
-// 48 < k <= 64 (one row per wavefront, second gather instead of the copy).  Compiled once per class
-// with -DROWS_K=16 / -DROWS_K=64.  The algebra is in the header comment of dual_prepare.hip.
+// Dual row update for rows with 8 < k <= 16 stored entries: four rows per wavefront, one lane per row of
+// the k x k system, gathered entries kept in registers and copied to LDS for r = Z_I^T t.  The algebra
+// is in the header comment of dual_prepare.hip.
 #include "dual_common.h"
-
-#ifndef ROWS_K
-#error "compile with -DROWS_K=16 or -DROWS_K=64"
-#endif
-static_assert(ROWS_K == 16 || ROWS_K == 64, "only these two classes are built from this kernel");
 
 namespace als {
 
-template <int D, int K, bool RG> struct DualCfg {
-    static constexpr int KT = K / 16;                       // 16-entry tiles per row
-    static constexpr int GW = K <= 16 ? 16 : (K <= 32 ? 32 : 64);  // lanes that share one row's k x k system
+template <int D> struct DualCfg {
+    static constexpr int K = 16;                            // one 16-entry tile per row
+    static constexpr int GW = 16;                           // lanes that share one row's k x k system
     static constexpr int RPW = 64 / GW;                     // rows per wavefront
     static constexpr int KP = K + 4;                        // LDS row stride of S (keeps rows 16-byte aligned)
     static constexpr int NJ = D / 16;                       // float4 loads per lane and entry
-    static constexpr bool ZBUF = !RG && K <= 32;            // r = Z_I^T t through an LDS copy of Z_I
-    static constexpr int ZLD = D + 4;
+    static constexpr int ZLD = D + 4;                       // row stride of the LDS copy of Z_I
     static constexpr int SB_FLOATS = RPW * K * KP;
-    static constexpr int ZB_FLOATS = ZBUF ? K * ZLD : 0;
-    static constexpr int TAIL = 64 + 128 + 4 + (RG ? 64 * (K / 16 > 1 ? K / 16 : 1) : 0);  // tbuf[64], colbuf[2][64],
-                                                                                          // ybuf[2][2], ids (RG)
+    static constexpr int ZB_FLOATS = K * ZLD;
+    static constexpr int TAIL = 64;                         // tbuf[64]
     static constexpr int LDS_FLOATS = (SB_FLOATS > ZB_FLOATS ? SB_FLOATS : ZB_FLOATS) + TAIL;
 };
 
-// One wavefront (= one workgroup) solves RPW rows taken from `list` (row ids relative to r0), all
-// with at most K stored entries:
-//   1. per row, lane (a = lane%16, q = lane/16) loads for entry e = 16t + a and j < D/16 the four
-//      columns (4j+q)*4.. of z_e; the same register is the A and the B operand of
-//      v_mfma_f32_16x16x4, so tile (t1,t2) accumulates S[16 t1 + .][16 t2 + .] over all d columns;
-//      S = I + Z_I Z_I^T goes to LDS;
-//   2. lane i of a row's group of GW lanes owns row i of S: right-looking Cholesky with the column
-//      broadcast inside the group, then L w = y, then L^T t = w with L read back transposed;
-//   3. r = Z_I^T t with one lane per pair of output columns, either from an LDS copy of Z_I (RG = false,
-//      K <= 32) or by gathering the row's entries a second time (RG = true).
-template <int D, int K, bool RG>
+// One wavefront (= one workgroup) solves four rows taken from `list` (row ids relative to r0), all
+// with at most 16 stored entries:
+//   1. per row, lane (a = lane%16, q = lane/16) loads for entry a and j < D/16 the four columns
+//      (4j+q)*4.. of z_a; the same register is the A and the B operand of v_mfma_f32_16x16x4, so the
+//      tile accumulates S over all d columns; S = I + Z_I Z_I^T goes to LDS;
+//   2. lane i of a row's group of 16 lanes owns row i of S: right-looking Cholesky with the column
+//      broadcast by DPP inside the group, then L w = y, then L^T t = w with L read back transposed;
+//   3. r = Z_I^T t with one lane per pair of output columns, from an LDS copy of Z_I.
+template <int D>
 __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict__ indptr,
                                                        const int32_t *__restrict__ indices,
                                                        const float *__restrict__ values,
                                                        const float *__restrict__ Z, float *__restrict__ R,
                                                        int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
                                                        int count, int32_t *__restrict__ err_flag) {
-    using C = DualCfg<D, K, RG>;
-    constexpr int KT = C::KT, GW = C::GW, RPW = C::RPW, KP = C::KP, NJ = C::NJ, ZLD = C::ZLD;
+    using C = DualCfg<D>;
+    constexpr int K = C::K, KT = 1, GW = C::GW, RPW = C::RPW, KP = C::KP, NJ = C::NJ, ZLD = C::ZLD;
     extern __shared__ float lds[];
     float *sb = lds, *zb = lds, *tb = lds + (C::LDS_FLOATS - C::TAIL);
     const int lane = threadIdx.x;
     const int a = lane & 15, q = lane >> 4;
     const int grp = lane / GW, gi = lane % GW;
-    const int myrow = gi < K ? gi : K - 1;  // K = 48: lanes 48..63 shadow row 47
+    const int myrow = gi;
 
     int64_t u[RPW], b[RPW];
     int k[RPW], kmax = 0;
@@ -74,9 +64,6 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
         for (int t = 0; t < KT; ++t) {
             const int e = 16 * t + a;
             const int64_t idx = e < k[p] ? (int64_t)indices[b[p] + e] : -1;
-            if constexpr (RG) {
-                if (q == 0) ((int32_t *)(tb + 196))[p * K + e] = (int32_t)idx;  // kept for the second gather
-            }
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
                 if (idx >= 0) z[p][t][j] = *(const float4 *)(Z + idx * D + (4 * j + q) * 4);
@@ -136,7 +123,7 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
     }
     wave_sync();
     bool bad = false;
-    if constexpr (GW == 16) {
+    {
         // k <= 16: Cholesky S = L L^T, column broadcast by DPP inside the 16-lane group
         float myrinv = 1.f;
         static_for<0, K>([&](auto cc) {
@@ -177,95 +164,13 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
                 yv = myrow < c ? yv - lt * tc : (myrow == c ? tc : yv);
             }
         });
-    } else {
-        // 16 < k <= 64: S = M D M^T (M unit lower, D the pivots), one column per step.  Every lane
-        // publishes its entry of the column in LDS (double-buffered by step parity), then reads the
-        // pivot and the whole column back with broadcast reads; u = M^{-1} y rides along.
-        float *colbuf = tb + 64, *yb = tb + 64 + 128;
-        float rp_mine = 1.f;
-        static_for<0, K>([&](auto cc) {
-            constexpr int c = decltype(cc)::value;
-            if (c < kmax) {
-                float *cb = colbuf + (c & 1) * 64;
-                cb[lane] = s[c];  // S'[row][c] as it stands (column c is final)
-                if (gi == c) yb[(c & 1) * 2 + grp] = yv;
-                wave_sync();
-                const float pivot = cb[grp * GW + c];
-                const float uc = yb[(c & 1) * 2 + grp];
-                bad |= !(pivot > 0.f);
-                float rp = __builtin_amdgcn_rcpf(pivot);
-                rp = rp * (2.f - pivot * rp);  // one Newton step on the hardware reciprocal
-                rp_mine = myrow == c ? rp : rp_mine;
-                const float f = myrow > c ? s[c] * rp : 0.f;  // M[row][c]; rows above stay as they are
-                yv -= f * uc;
-                static_for<(c + 1) / 4, K / 4>([&](auto jj) {
-                    constexpr int j4 = decltype(jj)::value;
-                    const float4 col = *(const float4 *)(cb + grp * GW + 4 * j4);
-                    if constexpr (4 * j4 + 0 > c) s[4 * j4 + 0] -= f * col.x;
-                    if constexpr (4 * j4 + 1 > c) s[4 * j4 + 1] -= f * col.y;
-                    if constexpr (4 * j4 + 2 > c) s[4 * j4 + 2] -= f * col.z;
-                    if constexpr (4 * j4 + 3 > c) s[4 * j4 + 3] -= f * col.w;
-                });
-            }
-        });
-        // t_c = (u_c - sum_{R>c} S'[R][c] t_R) / pivot_c with lane c owning unknown c: the factor is
-        // read back transposed through LDS, t_c is broadcast inside the group
-        {
-            float4 *row = (float4 *)(sb + (grp * K + myrow) * KP);
-#pragma unroll
-            for (int c4 = 0; c4 < K / 4; ++c4)
-                row[c4] = make_float4(s[4 * c4], s[4 * c4 + 1], s[4 * c4 + 2], s[4 * c4 + 3]);
-        }
-        wave_sync();
-#pragma unroll
-        for (int c = 0; c < K; ++c) s[c] = sb[(grp * K + c) * KP + myrow];  // S'[c][myrow], used for myrow < c
-        static_for<0, K>([&](auto cc) {
-            constexpr int c = K - 1 - decltype(cc)::value;
-            if (c < kmax) {
-                const float tc = group_bcast<GW, c>(yv * rp_mine);
-                yv = myrow < c ? yv - s[c] * tc : (myrow == c ? tc : yv);
-            }
-        });
     }
     if (bad && myk > 0) atomicOr(err_flag, 1);
 
     // ---- 3. r = Z_I^T t
-    if constexpr (RG) {
-        // gather the row's entries a second time (they are still in the caches), one lane per pair of
-        // output columns, so that no copy of Z_I has to stay in registers or LDS during the solve
-        constexpr int CPL = D >= 128 ? 2 : 1;
-        tb[lane] = yv;  // lane grp*GW + i holds t_i
-        wave_sync();
-#pragma unroll
-        for (int p = 0; p < RPW; ++p) {
-            if (u[p] >= 0 && lane * CPL < D) {
-                float r0v = 0.f, r1v = 0.f;
-                const int32_t *ix = (const int32_t *)(tb + 196) + p * K;
-                const int kp8 = (k[p] + 7) & ~7;  // padded entries have t = 0 and id -1 (row 0 is read instead)
-                for (int e0 = 0; e0 < kp8; e0 += 8) {
-                    float2 zz[8];
-                    float te[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const int id = ix[e0 + i];
-                        te[i] = tb[p * GW + e0 + i];
-                        const float *zr = Z + (int64_t)(id < 0 ? 0 : id) * D + CPL * lane;
-                        if constexpr (CPL == 2) zz[i] = *(const float2 *)zr;
-                        else zz[i] = make_float2(zr[0], 0.f);
-                    }
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        r0v += te[i] * zz[i].x;
-                        r1v += te[i] * zz[i].y;
-                    }
-                }
-                if constexpr (CPL == 2) *(float2 *)(R + u[p] * ldr + 2 * lane) = make_float2(r0v, r1v);
-                else R[u[p] * ldr + lane] = r0v;
-            }
-        }
-    } else if constexpr (C::ZBUF) {
+    {
         constexpr int CPL = D >= 128 ? 2 : 1;  // output columns per lane
-        tb[lane] = yv;                         // K <= 32: lane == grp*K + row
+        tb[lane] = yv;                         // lane == 16*grp + row
 #pragma unroll
         for (int p = 0; p < RPW; ++p) {
             wave_sync();  // zb aliases sb and the previous row's copy: all reads of those are done
@@ -290,23 +195,18 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
                 else R[u[p] * ldr + lane] = r0v;
             }
         }
-    } else {
-        static_assert(RG || C::ZBUF, "r = Z_I^T t needs either the LDS copy (K <= 32) or the second gather");
     }
 }
 
 template <int D>
 static void launch_rows_typed(const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
                               int count, int32_t *err, hipStream_t s) {
-    constexpr int K = ROWS_K;
-    constexpr bool RG = K == 64;  // measured: the second gather only pays when registers are the limit
-    using C = DualCfg<D, K, RG>;
+    using C = DualCfg<D>;
     const unsigned blocks = (unsigned)((count + C::RPW - 1) / C::RPW);
-    hipLaunchKernelGGL((dual_rows_kernel<D, K, RG>), dim3(blocks), dim3(64), C::LDS_FLOATS * sizeof(float), s,
-                       Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count, err);
+    hipLaunchKernelGGL((dual_rows_kernel<D>), dim3(blocks), dim3(64), C::LDS_FLOATS * sizeof(float), s, Y->indptr,
+                       Y->indices, Y->values, Z, R, ldr, r0, list, count, err);
 }
 
-#if ROWS_K == 16
 void launch_dual_k16(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
                      int count, int32_t *err, hipStream_t s) {
     if (count <= 0) return;
@@ -317,15 +217,5 @@ void launch_dual_k16(int d, const als_csr *Y, const float *Z, float *R, int64_t 
         case 128: launch_rows_typed<128>(Y, Z, R, ldr, r0, list, count, err, s); break;
     }
 }
-#else
-void launch_dual_k64(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                     int count, int32_t *err, hipStream_t s) {
-    if (count <= 0) return;
-    switch (d) {  // the dual form stops at k = d
-        case 64: launch_rows_typed<64>(Y, Z, R, ldr, r0, list, count, err, s); break;
-        case 128: launch_rows_typed<128>(Y, Z, R, ldr, r0, list, count, err, s); break;
-    }
-}
-#endif
 
 }  // namespace als

@@ -1,20 +1,20 @@
-// Dual row update for 64 < k <= 128 (d = 128 only), compiled once per class with -DWIDE_KT=5..8
-// (k <= 16*WIDE_KT).  The algebra is in the header comment of dual_prepare.hip.
+// Dual row update for 32 < k <= 128 (d = 128; k <= 64 also at d = 64), compiled once per class with
+// -DWIDE_KT=3..8 (k <= 16*WIDE_KT).  The algebra is in the header comment of dual_prepare.hip.
 #include "dual_common.h"
 #include "tri_solve.h"
 
 #ifndef WIDE_KT
-#error "compile with -DWIDE_KT=5, 6, 7 or 8"
+#error "compile with -DWIDE_KT=3 .. 8"
 #endif
 
 namespace als {
 
-// One wavefront per row with k <= K = 16*KT entries (KT = 5..8).
+// One wavefront per row with k <= K = 16*KT entries (KT = 3..8).
 //   1. S = I + Z_I Z_I^T tile by tile: the wavefront keeps the 16 entries of tile t1 in registers (B
 //      operand) and streams the tiles t2 <= t1 past them (A operand, fetched again from the caches);
 //      each finished 16x16 tile goes to LDS, where S is kept as a lower triangle.
 //   2./3. Block elimination S = M P M^T and back-substitution by the wavefront (tri_solve.h).
-//   4. r = Z_I^T t with one lane per pair of output columns, gathering the entries a second time.
+//   4. r = Z_I^T t with D/64 adjacent output columns per lane, gathering the entries a second time.
 template <int D, int KT> struct WideCfg {
     static constexpr int K = 16 * KT;
     static constexpr int TRI = tri_row(K);           // lower triangle, rows padded (tri_solve.h)
@@ -102,42 +102,61 @@ __global__ __launch_bounds__(64, 2) void dual_wide_kernel(const int64_t *__restr
         tri_solve<K>(tri, aux, tbuf, y0, y1, k, err_flag);
     }
 
-    // ---- 4. r = Z_I^T t, one lane per pair of output columns (second gather of the row's entries)
+    // ---- 4. r = Z_I^T t, D/64 adjacent output columns per lane (second gather of the row's entries)
     {
-        float r0v = 0.f, r1v = 0.f;
+        constexpr int CPL = D / 64;
+        float rv[CPL];
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) rv[c] = 0.f;
         const int kp8 = (k + 7) & ~7;  // padded entries have t = 0 and id -1 (row 0 is read instead)
         for (int e0 = 0; e0 < kp8; e0 += 8) {
-            float2 zz[8];
+            float zz[8][CPL];
             float te[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int id = ids[e0 + i];
                 te[i] = tbuf[e0 + i];
-                zz[i] = *(const float2 *)(Z + (int64_t)(id < 0 ? 0 : id) * D + 2 * lane);
+                const float *zp = Z + (int64_t)(id < 0 ? 0 : id) * D + CPL * lane;
+                if constexpr (CPL == 2) {
+                    const float2 t2 = *(const float2 *)zp;
+                    zz[i][0] = t2.x;
+                    zz[i][1] = t2.y;
+                } else {
+                    zz[i][0] = *zp;
+                }
             }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                r0v += te[i] * zz[i].x;
-                r1v += te[i] * zz[i].y;
-            }
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) rv[c] += te[i] * zz[i][c];
         }
-        *(float2 *)(R + u * ldr + 2 * lane) = make_float2(r0v, r1v);
+        if constexpr (CPL == 2) *(float2 *)(R + u * ldr + 2 * lane) = make_float2(rv[0], rv[1]);
+        else R[u * ldr + lane] = rv[0];
     }
 }
-
 
 #define ALS_WIDE_NAME2(kt) launch_dual_wide##kt
 #define ALS_WIDE_NAME(kt) ALS_WIDE_NAME2(kt)
 
-als_status ALS_WIDE_NAME(WIDE_KT)(als_ctx *ctx, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0,
-                                  const int32_t *list, int count, int32_t *err, hipStream_t s) {
-    using C = WideCfg<128, WIDE_KT>;
-    auto kern = dual_wide_kernel<128, WIDE_KT>;
+template <int D>
+static als_status wide_typed(als_ctx *ctx, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0,
+                             const int32_t *list, int count, int32_t *err, hipStream_t s) {
+    using C = WideCfg<D, WIDE_KT>;
+    auto kern = dual_wide_kernel<D, WIDE_KT>;
     ALS_HIP(ctx, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)(C::LDS_FLOATS * sizeof(float))));
     hipLaunchKernelGGL(kern, dim3((unsigned)count), dim3(64), C::LDS_FLOATS * sizeof(float), s, Y->indptr, Y->indices,
                        Y->values, Z, R, ldr, r0, list, err);
     return ALS_OK;
+}
+
+als_status ALS_WIDE_NAME(WIDE_KT)(als_ctx *ctx, int d, const als_csr *Y, const float *Z, float *R, int64_t ldr,
+                                  int64_t r0, const int32_t *list, int count, int32_t *err, hipStream_t s) {
+    if (d == 128) return wide_typed<128>(ctx, Y, Z, R, ldr, r0, list, count, err, s);
+    if constexpr (WIDE_KT <= 4) {  // the dual form reaches k <= 64 at d = 64
+        if (d == 64) return wide_typed<64>(ctx, Y, Z, R, ldr, r0, list, count, err, s);
+    }
+    return fail(ctx, ALS_EDTYPE, "wide dual kernel: unsupported d");
 }
 
 }  // namespace als

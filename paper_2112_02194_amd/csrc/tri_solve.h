@@ -152,42 +152,41 @@ __device__ __forceinline__ void tri_solve(float *tri, float *aux /* [192] */, fl
     });
     if (bad && lane == 0) atomicOr(err_flag, 1);
 
-    const int ktop = (k + 7) & ~7;
+    // ---- back-substitution, eight rows of the factor fetched ahead of the dependent chain.  Row R is
+    // read by all lanes at column min(lane, R): lanes at or beyond R have their unknown already and
+    // may go on computing on whatever they read.  Groups of rows at or beyond k hold t = 0.
     float t0 = 0.f, t1v = 0.f;
-    if constexpr (TWO) {
-#pragma unroll 1
-        for (int Rt = ktop - 1; Rt >= 64; Rt -= 8) {
+    static_for<0, K / 8>([&](auto gg) {
+        constexpr int Rt = K - 1 - 8 * decltype(gg)::value;  // the group's last row; rows Rt-7 .. Rt
+        if (Rt - 7 < k) {
             float fa[8], fb[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const int base = tri_row(Rt - i);
-                fa[i] = tri[base + ra];
-                fb[i] = tri[base + (rb < Rt - i ? rb : 0)];
+                const int Rr = Rt - i;
+                const float *row = tri + tri_row(Rr);
+                if (Rr >= 64) {
+                    fa[i] = row[ra];
+                    fb[i] = row[rb < Rr ? rb : Rr];
+                } else {
+                    fa[i] = row[ra < Rr ? ra : Rr];
+                }
             }
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int Rr = Rt - i;
-                const float tR = lane_value(y1 * rp1, Rr - 64);
-                t1v = rb == Rr ? tR : t1v;
-                y1 -= (rb < Rr ? fb[i] : 0.f) * tR;
-                y0 -= fa[i] * tR;
+                if (Rr >= 64) {
+                    const float tR = lane_value(y1 * rp1, Rr - 64);
+                    t1v = rb == Rr ? tR : t1v;
+                    y1 -= fb[i] * tR;
+                    y0 -= fa[i] * tR;
+                } else {
+                    const float tR = lane_value(y0 * rp0, Rr);
+                    t0 = ra == Rr ? tR : t0;
+                    y0 -= fa[i] * tR;
+                }
             }
         }
-    }
-    constexpr int N0 = K < 64 ? K : 64;
-#pragma unroll 1
-    for (int Rt = (ktop < N0 ? ktop : N0) - 1; Rt >= 0; Rt -= 8) {
-        float fa[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) fa[i] = tri[tri_row(Rt - i) + (ra < Rt - i ? ra : 0)];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int Rr = Rt - i;
-            const float tR = lane_value(y0 * rp0, Rr);
-            t0 = ra == Rr ? tR : t0;
-            y0 -= (ra < Rr ? fa[i] : 0.f) * tR;
-        }
-    }
+    });
     if (hasa) tbuf[ra] = t0;
     if (hasb) tbuf[rb] = t1v;
     wave_sync();

@@ -23,8 +23,8 @@ if ROOT not in sys.path:
 # HBM bytes per launch measured with rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by the copy-probe factors);
 # source: profiles/c3_epoch_hbm_traffic.md.  Keyed by (workload, kernel as named in the roofline object).
 MEASURED_TRAFFIC_BYTES = {
-    ("c3", "dual_multi_kernel<128, 2>"): 2.0 * 24728475 * 1024 + 1516525 * 1024,   # 52.2 GB (second gather included)
-    ("c3", "dual_rows_kernel<128, 16>"): 2.0 * 10647019 * 1024 + 3047319 * 1024,   # 24.9 GB
+    ("c3", "dual_multi_kernel<128, 2>"): 2.0 * 24728919 * 1024 + 1516525 * 1024,   # 52.2 GB (second gather included)
+    ("c3", "dual_rows_kernel<128>"): 2.0 * 8966269 * 1024 + 2064917 * 1024,        # 20.5 GB
 }
 HBM_PEAK_GBS = 8000.0
 MFMA_F32_PEAK_TFLOPS = 157.3
@@ -180,8 +180,7 @@ def main():
     for c in range(8):
         ms, launches = stage_ms.get(f"dual_k{16 * (c + 1)}", 0.0), stage_ms.get(f"launches_k{16 * (c + 1)}", 0.0)
         if launches > 0:
-            kname = {0: f"dual_rows_kernel<{d}, 16>", 1: f"dual_multi_kernel<{d}, 2>", 2: f"dual_multi_kernel<{d}, 3>",
-                     3: f"dual_rows_kernel<{d}, 64>"}.get(c, f"dual_wide_kernel<{d}, {c + 1}>")
+            kname = {0: f"dual_rows_kernel<{d}>", 1: f"dual_multi_kernel<{d}, 2>"}.get(c, f"dual_wide_kernel<{d}, {c + 1}>")
             per_launch = nsteps * (cls_nnz[c] * (4 * d + 4) + cls_rows[c] * (4 * d + 12)) / launches
             cand[kname] = (ms, launches, "hbm", per_launch)
     if stage_ms.get("primal", 0) > 0:

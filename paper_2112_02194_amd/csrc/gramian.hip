@@ -15,7 +15,7 @@ constexpr int GRAM_THREADS = 256;
 constexpr int GRAM_MAX_BLOCKS = 1024;
 
 template <int D, bool BF16>
-__global__ __launch_bounds__(GRAM_THREADS) void gramian_partial_kernel(const void *__restrict__ V, int64_t rows,
+__global__ __launch_bounds__(GRAM_THREADS, 2) void gramian_partial_kernel(const void *__restrict__ V, int64_t rows,
                                                                        int64_t ld, float *__restrict__ partials) {
     using G = Geo<D>;
     constexpr int NC = G::NC, TM = G::TM, KS = G::KS, ACC = G::ACC;
@@ -35,29 +35,40 @@ __global__ __launch_bounds__(GRAM_THREADS) void gramian_partial_kernel(const voi
 #pragma unroll
             for (int v = 0; v < ACC; ++v) acc[i][j][v] = 0.f;
 
-    // rows r0 + kk, r0 advancing by KS per MFMA step; two steps in flight per iteration
-    for (int64_t r0 = wave_id * KS; r0 < rows; r0 += nwaves * KS * 2) {
-        float x0[NC], x1[NC];
-        const int64_t ra = r0 + kk, rb = r0 + nwaves * KS + kk;
-        if (ra < rows) {
-            load_vec<NC, BF16>(V, ra * ld + NC * m, x0);
-        } else {
+    // Rows r0 + kk, r0 advancing by nwaves*KS per MFMA step, in batches of U steps.  The loads of the next
+    // batch are issued before the MFMAs of the current one (two register sets used alternately), so that
+    // a wavefront always has a batch of rows in flight while the matrix core works.
+    constexpr int U = 4;
+    const int64_t step = nwaves * KS, batch = step * U;
+    auto issue = [&](int64_t r0, float (&x)[U][NC]) {
 #pragma unroll
-            for (int c = 0; c < NC; ++c) x0[c] = 0.f;
-        }
-        if (rb < rows) {
-            load_vec<NC, BF16>(V, rb * ld + NC * m, x1);
-        } else {
+        for (int u = 0; u < U; ++u) {
+            const int64_t r = r0 + u * step + kk;
+            if (r < rows) {
+                load_vec<NC, BF16>(V, r * ld + NC * m, x[u]);
+            } else {
 #pragma unroll
-            for (int c = 0; c < NC; ++c) x1[c] = 0.f;
-        }
-#pragma unroll
-        for (int i = 0; i < NC; ++i)
-#pragma unroll
-            for (int j = i; j < NC; ++j) {  // upper tiles only; the result is symmetric
-                acc[i][j] = mfma<D>(x0[i], x0[j], acc[i][j]);
-                acc[i][j] = mfma<D>(x1[i], x1[j], acc[i][j]);
+                for (int c = 0; c < NC; ++c) x[u][c] = 0.f;
             }
+        }
+    };
+    auto consume = [&](float (&x)[U][NC]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int i = 0; i < NC; ++i)
+#pragma unroll
+                for (int j = i; j < NC; ++j)  // upper tiles only; the result is symmetric
+                    acc[i][j] = mfma<D>(x[u][i], x[u][j], acc[i][j]);
+    };
+    float xa[U][NC], xb[U][NC];
+    int64_t r0 = wave_id * KS;
+    issue(r0, xa);
+    for (; r0 < rows; r0 += 2 * batch) {
+        issue(r0 + batch, xb);  // past the end: zeros, no loads
+        consume(xa);
+        issue(r0 + 2 * batch, xa);
+        if (r0 + batch < rows) consume(xb);
     }
 
     // fixed-order sum of the four wavefronts through LDS
@@ -99,7 +110,7 @@ __global__ __launch_bounds__(256) void gramian_reduce_kernel(const float *__rest
 template <int D, bool BF16>
 static als_status gramian_typed(als_ctx *ctx, const als_table *V, float *G, hipStream_t s) {
     constexpr int KS = Geo<D>::KS;
-    int64_t per_block = (int64_t)(GRAM_THREADS / 64) * KS * 2 * 8;  // at least 8 iterations per wave
+    int64_t per_block = (int64_t)(GRAM_THREADS / 64) * KS * 4 * 8;  // at least 8 batches of 4 steps per wave
     int nblocks = (int)std::min<int64_t>(GRAM_MAX_BLOCKS, std::max<int64_t>(1, (V->rows + per_block - 1) / per_block));
     als_status st = ensure(ctx, ctx->gram_partials, (size_t)GRAM_MAX_BLOCKS * D * D * sizeof(float));
     if (st != ALS_OK) return st;

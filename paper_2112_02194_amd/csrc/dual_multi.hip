@@ -68,6 +68,7 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
                 z[t][j] = id >= 0 ? *(const float4 *)(Z + (int64_t)id * D + (4 * j + q) * 4)
                                   : make_float4(0.f, 0.f, 0.f, 0.f);
         }
+        __builtin_amdgcn_s_setprio(1);  // matrix-core work first: other wavefronts fill in with vector work
 #pragma unroll
         for (int t1 = 0; t1 < M; ++t1)
 #pragma unroll
@@ -88,6 +89,7 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
                     if (c <= Rr) tri[p * TRI + Rr * (Rr + 1) / 2 + c] = acc[v] + (c == Rr ? 1.f : 0.f);
                 }
             }
+        __builtin_amdgcn_s_setprio(0);
     }
     wave_sync();
 

@@ -113,6 +113,7 @@ def main():
     p = make_problem(args.workload, device=dev, **kw)
     torch.cuda.synchronize()
     stats = p.stats()
+    torch.cuda.empty_cache()  # the generator's temporaries go back to the driver: the library allocates with hipMalloc
     log(f"generated {args.workload} in {time.perf_counter() - t0:.1f} s: {stats}")
     nnz, d, m, n = p.nnz, p.d, p.rows, p.cols
     es = 4 if p.table_dtype == torch.float32 else 2

@@ -144,6 +144,9 @@ def _geometric(u: torch.Tensor, mean: float, kmax: int) -> torch.Tensor:
 def csr_from_edges(rows: int, cols: int, r: torch.Tensor, c: torch.Tensor,
                    v: Optional[torch.Tensor] = None):
     """Sort edges by (row, col), drop duplicate pairs, return (indptr, indices, values)."""
+    if r.numel() >= 2 ** 31:
+        raise ValueError(f"{r.numel()} drawn entries: the generator sorts a matrix in one piece and is limited to "
+                         "2^31-1 entries; build fewer rows (configuration c5 fits up to about 80M rows)")
     key = r.to(torch.int64) * cols + c.to(torch.int64)
     if v is None:
         key = torch.unique(key)  # sorted, duplicates removed

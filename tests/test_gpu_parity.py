@@ -110,6 +110,23 @@ def test_dual_threshold_sweep(ctx, gpu_device, dual_max_k):
                 row_range=(3, 590))
 
 
+@pytest.mark.parametrize("d,dtype", [(128, "f32"), (64, "f32"), (128, "bf16"), (32, "f32")])
+def test_every_row_length_0_to_140(ctx, gpu_device, d, dtype):
+    """Rows with exactly k = 0, 1, ..., 140 stored entries, four of each, in shuffled order: every boundary
+    between the row classes (4|5, 8|9, 16|17, 32|33, 48|49, ..., 128|129 and the switch to the d x d
+    system) is crossed, with general labels."""
+    say(f"solve_rows auto, every row length 0..140, d={d} {dtype}")
+    p = make_problem("c1", rows=4 * 141, cols=3000, d=d, values="uniform", dtype=dtype)
+    gen = torch.Generator().manual_seed(20211206 + d)
+    lengths = (torch.arange(4 * 141) % 141)[torch.randperm(4 * 141, generator=gen)]
+    cols = [torch.randperm(p.cols, generator=gen)[:int(k)].sort().values for k in lengths]
+    p.indptr = torch.zeros(4 * 141 + 1, dtype=torch.int64)
+    p.indptr[1:] = torch.cumsum(lengths, 0)
+    p.indices = torch.cat(cols).to(torch.int32)
+    p.values = 0.5 + torch.rand(int(p.indptr[-1]), generator=gen)
+    _solve_case(ctx, gpu_device, p, als.PATH_AUTO, scale_v=8.0)
+
+
 def test_dual_ill_conditioned_gramian(ctx, gpu_device):
     """A table whose Gramian has a wide spectrum and a small lambda: cond(alpha*G + lambda*I) ~ 7e4."""
     say("solve_rows auto ill-conditioned table")

@@ -127,11 +127,12 @@ def test_every_row_length_0_to_140(ctx, gpu_device, d, dtype):
     _solve_case(ctx, gpu_device, p, als.PATH_AUTO, scale_v=8.0)
 
 
-def test_dual_ill_conditioned_gramian(ctx, gpu_device):
+@pytest.mark.parametrize("d", [64, 128])
+def test_dual_ill_conditioned_gramian(ctx, gpu_device, d):
     """A table whose Gramian has a wide spectrum and a small lambda: cond(alpha*G + lambda*I) ~ 7e4."""
-    say("solve_rows auto ill-conditioned table")
-    p = make_problem("c1", rows=500, cols=800, d=64)
-    scale = torch.logspace(0, -2.5, 64)[None, :]
+    say(f"solve_rows auto ill-conditioned table d={d}")
+    p = make_problem("c1", rows=500, cols=800, d=d)
+    scale = torch.logspace(0, -2.5, d)[None, :]
     p.H0 = p.H0 * 40.0 * scale
     p.lam = 1e-4
     for path in (als.PATH_AUTO, als.PATH_PRIMAL):

@@ -22,7 +22,8 @@ template <int C> __device__ __forceinline__ float bcast16(float x) {
 
 template <int D, int M> struct MultiCfg {
     static constexpr int K = 16 * M, TRI = K * (K + 1) / 2;
-    static constexpr int OFF_T = 4 * TRI, OFF_ID = OFF_T + 4 * K, LDS_FLOATS = OFF_ID + 4 * K;
+    static constexpr int OFF_T = 4 * TRI, OFF_ID = OFF_T + 4 * K, OFF_DUMP = OFF_ID + 4 * K;
+    static constexpr int LDS_FLOATS = OFF_DUMP + 64;  // one dump slot per lane for stores that must not land
 };
 
 template <int D, int M>
@@ -37,6 +38,10 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
     extern __shared__ float lds[];
     float *tri = lds, *tbuf = lds + C::OFF_T;
     int32_t *ids = (int32_t *)(lds + C::OFF_ID);
+    // Accesses to the packed triangle are never put under a lane-dependent branch (a branch per element costs
+    // more than the access): reads go to an in-range address and are selected afterwards, stores of entries
+    // that do not exist go to the lane's dump slot.
+    float *dump = lds + C::OFF_DUMP + threadIdx.x;
     const int lane = threadIdx.x, a = lane & 15, q = lane >> 4;  // MFMA view: entry a of a tile, column group q
     const int g = lane >> 4, i = lane & 15;                       // solver view: system g, lane i of its group
 
@@ -86,7 +91,9 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int c = 16 * t2 + 4 * q + v;
-                    if (c <= Rr) tri[p * TRI + Rr * (Rr + 1) / 2 + c] = acc[v] + (c == Rr ? 1.f : 0.f);
+                    float *dst = tri + p * TRI + Rr * (Rr + 1) / 2 + c;
+                    if (t2 == t1) dst = c <= Rr ? dst : dump;  // compile-time test: only diagonal tiles have c > Rr
+                    *dst = acc[v] + (c == Rr ? 1.f : 0.f);
                 }
             }
         __builtin_amdgcn_s_setprio(0);
@@ -106,7 +113,10 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
     for (int bk = 0; bk < M; ++bk) {
         const int Rr = 16 * bk + i;
 #pragma unroll
-        for (int c = 0; c < 16 * (bk + 1); ++c) s[bk][c] = c <= Rr ? tri[g * TRI + Rr * (Rr + 1) / 2 + c] : 0.f;
+        for (int c = 0; c < 16 * (bk + 1); ++c) {
+            const float v = tri[g * TRI + Rr * (Rr + 1) / 2 + c];  // c > Rr reads the next row: in range, unused
+            s[bk][c] = (c < 16 * bk || c <= Rr) ? v : 0.f;
+        }
         y[bk] = 0.f;
         if (Rr < myk) y[bk] = values ? values[myb + Rr] : 1.f;
         rpm[bk] = 1.f;
@@ -147,15 +157,21 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
     for (int bk = 0; bk < M; ++bk) {
         const int Rr = 16 * bk + i;
 #pragma unroll
-        for (int c = 0; c < 16 * (bk + 1); ++c)
-            if (c <= Rr) tri[g * TRI + Rr * (Rr + 1) / 2 + c] = s[bk][c];
+        for (int c = 0; c < 16 * (bk + 1); ++c) {
+            float *dst = tri + g * TRI + Rr * (Rr + 1) / 2 + c;
+            if (c >= 16 * bk) dst = c <= Rr ? dst : dump;
+            *dst = s[bk][c];
+        }
     }
     wave_sync();
 #pragma unroll
     for (int bk = 0; bk < M; ++bk) {
         const int col = 16 * bk + i;
 #pragma unroll
-        for (int Rr = 16 * bk; Rr < K; ++Rr) s[bk][Rr] = Rr > col ? tri[g * TRI + Rr * (Rr + 1) / 2 + col] : 0.f;
+        for (int Rr = 16 * bk; Rr < K; ++Rr) {
+            const float v = tri[g * TRI + Rr * (Rr + 1) / 2 + col];  // col > Rr reads a later row: in range, unused
+            s[bk][Rr] = (Rr >= 16 * (bk + 1) || Rr > col) ? v : 0.f;
+        }
     }
     float t[M];
 #pragma unroll

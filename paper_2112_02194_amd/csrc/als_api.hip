@@ -76,6 +76,7 @@ static als_status check_table(als_ctx *ctx, const als_table *t, const char *name
     if (t->dtype != ALS_F32 && t->dtype != ALS_BF16) return fail(ctx, ALS_EDTYPE, std::string(name) + ": unknown dtype");
     if (t->rows < 0) return fail(ctx, ALS_EINVAL, std::string(name) + ": negative row count");
     if (t->ld < t->d) return fail(ctx, ALS_ESHAPE, std::string(name) + ": ld < d");
+    if (t->ld > INT32_MAX) return fail(ctx, ALS_ESHAPE, std::string(name) + ": ld does not fit 31 bits");
     size_t es = t->dtype == ALS_F32 ? 4 : 2;
     if ((t->ld * es) % 16 != 0 || ((uintptr_t)t->data % 16) != 0)
         return fail(ctx, ALS_ESHAPE, std::string(name) + ": rows must be 16-byte aligned");

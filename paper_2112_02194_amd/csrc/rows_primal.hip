@@ -41,6 +41,7 @@ __device__ __forceinline__ void accumulate_entries(const void *__restrict__ V, i
     constexpr int NC = G::NC, TM = G::TM, KS = G::KS, U = 8;
     const int lane = threadIdx.x & 63;
     const int m = lane % TM, kk = lane / TM;
+    const uint32_t ld32 = (uint32_t)ld;  // the leading dimension fits 32 bits (checked on the host)
     for (int64_t base = begin; base < end; base += 64) {
         const int64_t p = base + lane;
         const int myidx = p < end ? indices[p] : -1;
@@ -48,17 +49,30 @@ __device__ __forceinline__ void accumulate_entries(const void *__restrict__ V, i
         const int cnt = (int)((end - base) < 64 ? (end - base) : 64);
         const int nsteps = (cnt + KS - 1) / KS;
         for (int s0 = 0; s0 < nsteps; s0 += U) {
+            // all lane exchanges of the batch first, then all loads: one wait instead of one per load
+            int idx[U];
             float x[U][NC], y[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int e = (s0 + u) * KS + kk;
-                const int idx = e < 64 ? __shfl(myidx, e & 63) : -1;
-                y[u] = e < 64 ? __shfl(myy, e & 63) : 0.f;
-                if (idx >= 0) {
-                    load_vec<NC, BF16>(V, (int64_t)idx * ld + NC * m, x[u]);
-                } else {
+                idx[u] = __shfl(myidx, e & 63);
+                y[u] = __shfl(myy, e & 63);
+            }
+            if ((s0 + U) * KS <= cnt) {  // uniform: every slot of the batch holds an entry
 #pragma unroll
-                    for (int c = 0; c < NC; ++c) x[u][c] = 0.f;
+                for (int u = 0; u < U; ++u)
+                    load_vec<NC, BF16>(V, (int64_t)((uint64_t)(uint32_t)idx[u] * ld32) + NC * m, x[u]);
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const bool have = (s0 + u) * KS + kk < cnt;
+                    y[u] = have ? y[u] : 0.f;
+                    if (have) {
+                        load_vec<NC, BF16>(V, (int64_t)((uint64_t)(uint32_t)idx[u] * ld32) + NC * m, x[u]);
+                    } else {
+#pragma unroll
+                        for (int c = 0; c < NC; ++c) x[u][c] = 0.f;
+                    }
                 }
             }
 #pragma unroll

@@ -30,7 +30,8 @@ template <int D> struct Team {
 
 // ---------------------------------------------------------------------------------------------- accumulate
 // Accumulates, for entries [begin, end) of the CSR arrays, tile-row `I` of sum v (x) v into acc[]
-// and this lane's share of sum y*v into bsum[] (lane (m,kk) holds columns NC*m.. of entries kk mod KS).
+// and, in the wavefront of tile-row 0 only, this lane's share of sum y*v into bsum[] (lane (m,kk) holds
+// columns NC*m.. of entries kk mod KS).
 template <int D, bool BF16>
 __device__ __forceinline__ void accumulate_entries(const void *__restrict__ V, int64_t ld,
                                                    const int32_t *__restrict__ indices,
@@ -42,6 +43,7 @@ __device__ __forceinline__ void accumulate_entries(const void *__restrict__ V, i
     const int lane = threadIdx.x & 63;
     const int m = lane % TM, kk = lane / TM;
     const uint32_t ld32 = (uint32_t)ld;  // the leading dimension fits 32 bits (checked on the host)
+    const bool first_row = __builtin_amdgcn_readfirstlane(I) == 0;
     for (int64_t base = begin; base < end; base += 64) {
         const int64_t p = base + lane;
         const int myidx = p < end ? indices[p] : -1;
@@ -81,10 +83,13 @@ __device__ __forceinline__ void accumulate_entries(const void *__restrict__ V, i
 #pragma unroll
                 for (int c = 1; c < NC; ++c) a = (I == c) ? x[u][c] : a;
 #pragma unroll
-                for (int j = 0; j < NC; ++j) {
-                    acc[j] = mfma<D>(a, x[u][j], acc[j]);
-                    bsum[j] += y[u] * x[u][j];
-                }
+                for (int j = 0; j < NC; ++j) acc[j] = mfma<D>(a, x[u][j], acc[j]);
+            }
+            if (first_row) {  // scalar branch: only the wavefront of tile-row 0 carries the right-hand side
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int j = 0; j < NC; ++j) bsum[j] += y[u] * x[u][j];
             }
         }
     }

@@ -192,35 +192,57 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
     for (int bk = 0; bk < M; ++bk) tbuf[g * K + 16 * bk + i] = t[bk];
     wave_sync();
 
-    // ---- 4. r = Z_I^T t (second gather of the row's entries); the four rows advance together, eight
-    // entries each per round, so that 32 loads per lane are in flight
+    // ---- 4. r = Z_I^T t (second gather of the row's entries); the four rows advance together, EPR
+    // entries each per round.  Per round: first the ids and t of all rows from LDS with 16-byte reads,
+    // then the loads, then the products - no wait and no lane-dependent branch between two loads.
     {
         float r0v[4] = {0.f, 0.f, 0.f, 0.f}, r1v[4] = {0.f, 0.f, 0.f, 0.f};
         const bool col_ok = lane * CPL < D;
-        const int kmax8 = (kmax + 7) & ~7;  // padded entries have t = 0 and id -1 (row 0 is read instead)
-        for (int e0 = 0; e0 < kmax8; e0 += 8) {
-            float2 zz[4][8];
-            float te[4][8];
+        const float *zcol = Z + (col_ok ? CPL * lane : 0);  // lanes without a column (d = 32) read column 0
+        // entries per row and round (measured: 16 eight-byte loads in flight are best at d = 128, 32 four-byte
+        // loads at d <= 64)
+        constexpr int EPR = CPL == 2 ? 4 : 8, NQ = EPR / 4;
+        const int kmaxr = (kmax + EPR - 1) / EPR * EPR;  // padded entries have t = 0 and id -1 (row 0 is read instead)
+        for (int e0 = 0; e0 < kmaxr; e0 += EPR) {
+            int4 idq[4][NQ];
+            float4 teq[4][NQ];
 #pragma unroll
             for (int p = 0; p < 4; ++p)
 #pragma unroll
-                for (int x = 0; x < 8; ++x) {
-                    const int id = ids[p * K + e0 + x];
-                    te[p][x] = tbuf[p * K + e0 + x];
-                    const float *zr = Z + (int64_t)(id < 0 ? 0 : id) * D + CPL * lane;
-                    zz[p][x] = make_float2(0.f, 0.f);
-                    if (col_ok && e0 < k[p]) {
-                        if constexpr (CPL == 2) zz[p][x] = *(const float2 *)zr;
-                        else zz[p][x].x = zr[0];
+                for (int h = 0; h < NQ; ++h) {
+                    idq[p][h] = *(const int4 *)(ids + p * K + e0 + 4 * h);
+                    teq[p][h] = *(const float4 *)(tbuf + p * K + e0 + 4 * h);
+                }
+            float2 zz[4][EPR];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                if (e0 < k[p]) {  // uniform
+#pragma unroll
+                    for (int h = 0; h < NQ; ++h) {
+                        const int id[4] = {idq[p][h].x, idq[p][h].y, idq[p][h].z, idq[p][h].w};
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) {
+                            const float *zr = zcol + (int64_t)(id[x] < 0 ? 0 : id[x]) * D;
+                            if constexpr (CPL == 2) zz[p][4 * h + x] = *(const float2 *)zr;
+                            else zz[p][4 * h + x] = make_float2(zr[0], 0.f);
+                        }
                     }
                 }
+            }
 #pragma unroll
-            for (int p = 0; p < 4; ++p)
+            for (int p = 0; p < 4; ++p) {
+                if (e0 < k[p]) {
 #pragma unroll
-                for (int x = 0; x < 8; ++x) {
-                    r0v[p] += te[p][x] * zz[p][x].x;
-                    r1v[p] += te[p][x] * zz[p][x].y;
+                    for (int h = 0; h < NQ; ++h) {
+                        const float te[4] = {teq[p][h].x, teq[p][h].y, teq[p][h].z, teq[p][h].w};
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) {
+                            r0v[p] += te[x] * zz[p][4 * h + x].x;
+                            r1v[p] += te[x] * zz[p][4 * h + x].y;
+                        }
+                    }
                 }
+            }
         }
 #pragma unroll
         for (int p = 0; p < 4; ++p) {

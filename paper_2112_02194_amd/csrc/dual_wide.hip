@@ -111,11 +111,14 @@ __global__ __launch_bounds__(64, 2) void dual_wide_kernel(const int64_t *__restr
         const int kp8 = (k + 7) & ~7;  // padded entries have t = 0 and id -1 (row 0 is read instead)
         for (int e0 = 0; e0 < kp8; e0 += 8) {
             float zz[8][CPL];
-            float te[8];
+            // ids and t of the round with 16-byte LDS reads, before the first load is issued
+            const int4 ia = *(const int4 *)(ids + e0), ib = *(const int4 *)(ids + e0 + 4);
+            const float4 ta = *(const float4 *)(tbuf + e0), tb = *(const float4 *)(tbuf + e0 + 4);
+            const int idr[8] = {ia.x, ia.y, ia.z, ia.w, ib.x, ib.y, ib.z, ib.w};
+            const float te[8] = {ta.x, ta.y, ta.z, ta.w, tb.x, tb.y, tb.z, tb.w};
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const int id = ids[e0 + i];
-                te[i] = tbuf[e0 + i];
+                const int id = idr[i];
                 const float *zp = Z + (int64_t)(id < 0 ? 0 : id) * D + CPL * lane;
                 if constexpr (CPL == 2) {
                     const float2 t2 = *(const float2 *)zp;

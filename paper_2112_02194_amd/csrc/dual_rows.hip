@@ -180,15 +180,25 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
                 for (int j = 0; j < NJ; ++j) *(float4 *)(zb + (16 * t + a) * ZLD + (4 * j + q) * 4) = z[p][t][j];
             wave_sync();
             if (u[p] >= 0 && lane * CPL < D) {
+                // four slots at a time (slots past the row's k hold t = 0 and zero entries): the LDS reads of a
+                // group are issued together, one round trip per group instead of one per entry
                 float r0v = 0.f, r1v = 0.f;
-                for (int e = 0; e < k[p]; ++e) {
-                    const float te = tb[p * K + e];
-                    if constexpr (CPL == 2) {
-                        const float2 zz = *(const float2 *)(zb + e * ZLD + 2 * lane);
-                        r0v += te * zz.x;
-                        r1v += te * zz.y;
-                    } else {
-                        r0v += te * zb[e * ZLD + lane];
+#pragma unroll
+                for (int h = 0; h < K / 4; ++h) {
+                    if (4 * h < k[p]) {  // uniform
+                        const float4 tq = *(const float4 *)(tb + p * K + 4 * h);
+                        const float te[4] = {tq.x, tq.y, tq.z, tq.w};
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) {
+                            const int e = 4 * h + x;
+                            if constexpr (CPL == 2) {
+                                const float2 zz = *(const float2 *)(zb + e * ZLD + 2 * lane);
+                                r0v += te[x] * zz.x;
+                                r1v += te[x] * zz.y;
+                            } else {
+                                r0v += te[x] * zb[e * ZLD + lane];
+                            }
+                        }
                     }
                 }
                 if constexpr (CPL == 2) *(float2 *)(R + u[p] * ldr + 2 * lane) = make_float2(r0v, r1v);

@@ -153,15 +153,25 @@ __global__ __launch_bounds__(64) void dual_small_kernel(const int64_t *__restric
             const int k = meta[3 * rr + 2];
             const int64_t u = ((int64_t)meta[3 * rr + 1] << 32) | (uint32_t)meta[3 * rr + 0];
             if (u >= 0 && lane * CPL < D) {
+                // four slots at a time (slots past the row's k hold t = 0 and zero entries): the LDS reads of a
+                // group are issued together, one round trip per group instead of one per entry
                 float r0v = 0.f, r1v = 0.f;
-                for (int x = 0; x < k; ++x) {
-                    const float te = tb[p * 16 + sidx * G + x];
-                    if constexpr (CPL == 2) {
-                        const float2 zz = *(const float2 *)(zb + (sidx * G + x) * ZLD + 2 * lane);
-                        r0v += te * zz.x;
-                        r1v += te * zz.y;
-                    } else {
-                        r0v += te * zb[(sidx * G + x) * ZLD + lane];
+#pragma unroll
+                for (int h = 0; h < G / 4; ++h) {
+                    if (4 * h < k) {  // uniform
+                        const float4 tq = *(const float4 *)(tb + p * 16 + sidx * G + 4 * h);
+                        const float te[4] = {tq.x, tq.y, tq.z, tq.w};
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) {
+                            const int e = sidx * G + 4 * h + x;
+                            if constexpr (CPL == 2) {
+                                const float2 zz = *(const float2 *)(zb + e * ZLD + 2 * lane);
+                                r0v += te[x] * zz.x;
+                                r1v += te[x] * zz.y;
+                            } else {
+                                r0v += te[x] * zb[e * ZLD + lane];
+                            }
+                        }
                     }
                 }
                 if constexpr (CPL == 2) *(float2 *)(R + u * ldr + 2 * lane) = make_float2(r0v, r1v);

@@ -69,9 +69,11 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
             const int32_t id = e < k[p] ? indices[b[p] + e] : -1;
             if (q == 0) ids[p * K + e] = id;
 #pragma unroll
-            for (int j = 0; j < NJ; ++j)
-                z[t][j] = id >= 0 ? *(const float4 *)(Z + (int64_t)id * D + (4 * j + q) * 4)
-                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int j = 0; j < NJ; ++j) z[t][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (id >= 0) {  // one masked region per tile, not one per load
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) z[t][j] = *(const float4 *)(Z + (int64_t)id * D + (4 * j + q) * 4);
+            }
         }
         __builtin_amdgcn_s_setprio(1);  // matrix-core work first: other wavefronts fill in with vector work
 #pragma unroll

@@ -65,9 +65,10 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
             const int e = 16 * t + a;
             const int64_t idx = e < k[p] ? (int64_t)indices[b[p] + e] : -1;
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-                if (idx >= 0) z[p][t][j] = *(const float4 *)(Z + idx * D + (4 * j + q) * 4);
-                else z[p][t][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int j = 0; j < NJ; ++j) z[p][t][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (idx >= 0) {  // one masked region per tile, not one per load
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) z[p][t][j] = *(const float4 *)(Z + idx * D + (4 * j + q) * 4);
             }
         }
     int myk = 0;

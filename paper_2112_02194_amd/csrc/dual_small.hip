@@ -74,8 +74,11 @@ __global__ __launch_bounds__(64) void dual_small_kernel(const int64_t *__restric
         const int64_t idx = e < k ? (int64_t)indices[b + e] : -1;
         yl[p] = e < k ? (values ? values[b + e] : 1.f) : 0.f;
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
-            z[p][j] = idx >= 0 ? *(const float4 *)(Z + idx * D + (4 * j + q) * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int j = 0; j < NJ; ++j) z[p][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (idx >= 0) {  // one masked region per tile, not one per load
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) z[p][j] = *(const float4 *)(Z + idx * D + (4 * j + q) * 4);
+        }
     }
     // ---- 2. the tiles' products; tile p's 16 x 16 result to LDS (only its diagonal blocks are used)
 #pragma unroll

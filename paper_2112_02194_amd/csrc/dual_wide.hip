@@ -54,11 +54,14 @@ __global__ __launch_bounds__(64, 2) void dual_wide_kernel(const int64_t *__restr
     constexpr int RT = KT < 5 ? KT : 5;
     float4 zres[RT][NJ];
 #pragma unroll
-    for (int t = 0; t < RT; ++t)
+    for (int t = 0; t < RT; ++t) {
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
-            zres[t][j] = myid[t] >= 0 ? *(const float4 *)(Z + (int64_t)myid[t] * D + (4 * j + q) * 4)
-                                      : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int j = 0; j < NJ; ++j) zres[t][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (myid[t] >= 0) {  // one masked region per tile, not one per load
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) zres[t][j] = *(const float4 *)(Z + (int64_t)myid[t] * D + (4 * j + q) * 4);
+        }
+    }
 #pragma unroll
     for (int t1 = 0; t1 < KT; ++t1) {
         float4 zb[NJ];

@@ -8,7 +8,7 @@ namespace als {
 template <int D> struct DualCfg {
     static constexpr int K = 16;                            // one 16-entry tile per row
     static constexpr int GW = 16;                           // lanes that share one row's k x k system
-    static constexpr int RPW = 64 / GW;                     // rows per wavefront
+    static constexpr int RPW = 64 / GW;                     // rows per wavefront (4: read as one int4)
     static constexpr int KP = K + 4;                        // LDS row stride of S (keeps rows 16-byte aligned)
     static constexpr int NJ = D / 16;                       // float4 loads per lane and entry
     static constexpr int ZLD = D + 4;                       // row stride of the LDS copy of Z_I
@@ -42,35 +42,52 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
     const int grp = lane / GW, gi = lane % GW;
     const int myrow = gi;
 
+    // Row descriptors, then column ids, then table rows: each stage is issued for all four rows before the
+    // next one starts, so that a wavefront waits for three memory round trips, not for three per row.
+    // (Loads are unconditional on clamped addresses; what does not exist is masked afterwards.)
     int64_t u[RPW], b[RPW];
-    int k[RPW], kmax = 0;
+    int k[RPW], kmax = 0, rel[RPW];
+    {
+        // one 16-byte read of the wavefront's four list entries; past the end of the list (its workspace is
+        // padded for this) the first entry stands in
+        const int4 r4 = *(const int4 *)(list + (int64_t)blockIdx.x * RPW);
+        const int first = blockIdx.x * RPW;
+        rel[0] = r4.x;
+        rel[1] = first + 1 < count ? r4.y : r4.x;
+        rel[2] = first + 2 < count ? r4.z : r4.x;
+        rel[3] = first + 3 < count ? r4.w : r4.x;
+    }
+    int64_t b1[RPW];
 #pragma unroll
     for (int p = 0; p < RPW; ++p) {
-        const int item = blockIdx.x * RPW + p;
-        u[p] = -1; b[p] = 0; k[p] = 0;
-        if (item < count) {
-            u[p] = r0 + list[item];
-            b[p] = indptr[u[p]];
-            k[p] = (int)(indptr[u[p] + 1] - b[p]);
-        }
+        b[p] = indptr[r0 + rel[p]];
+        b1[p] = indptr[r0 + rel[p] + 1];
+    }
+#pragma unroll
+    for (int p = 0; p < RPW; ++p) {
+        const bool have = blockIdx.x * RPW + p < count;
+        u[p] = have ? r0 + rel[p] : -1;
+        k[p] = have ? (int)(b1[p] - b[p]) : 0;
         kmax = k[p] > kmax ? k[p] : kmax;
     }
 
     // ---- 1. gather + S tiles
+    int64_t idx[RPW];
+#pragma unroll
+    for (int p = 0; p < RPW; ++p) {
+        const int32_t id = indices[b[p] + (a < k[p] ? a : 0)];  // rows of this class have k >= 1: always in range
+        idx[p] = a < k[p] ? (int64_t)id : -1;
+    }
     float4 z[RPW][KT][NJ];
 #pragma unroll
-    for (int p = 0; p < RPW; ++p)
+    for (int p = 0; p < RPW; ++p) {
 #pragma unroll
-        for (int t = 0; t < KT; ++t) {
-            const int e = 16 * t + a;
-            const int64_t idx = e < k[p] ? (int64_t)indices[b[p] + e] : -1;
+        for (int j = 0; j < NJ; ++j) z[p][0][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (idx[p] >= 0) {  // one masked region per tile, not one per load
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) z[p][t][j] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (idx >= 0) {  // one masked region per tile, not one per load
-#pragma unroll
-                for (int j = 0; j < NJ; ++j) z[p][t][j] = *(const float4 *)(Z + idx * D + (4 * j + q) * 4);
-            }
+            for (int j = 0; j < NJ; ++j) z[p][0][j] = *(const float4 *)(Z + idx[p] * D + (4 * j + q) * 4);
         }
+    }
     int myk = 0;
     int64_t myb = 0;
 #pragma unroll

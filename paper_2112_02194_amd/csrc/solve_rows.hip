@@ -121,7 +121,8 @@ als_status launch_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V,
     const int64_t cap_mid = std::min<int64_t>(nrows, Y->nnz / (dual_max + 1) + 1);
     const size_t off_seg = (size_t)cap_long * sizeof(LongRow);
     const size_t off_lists = off_seg + (size_t)cap_seg * sizeof(Segment);
-    als_status st = ensure(ctx, ctx->lists, off_lists + (size_t)(cap_mid + off[10]) * sizeof(int32_t));
+    // + 16 bytes: the row kernels read a wavefront's four list entries with one 16-byte load
+    als_status st = ensure(ctx, ctx->lists, off_lists + (size_t)(cap_mid + off[10]) * sizeof(int32_t) + 16);
     if (st != ALS_OK) return st;
     LongRow *long_rows = (LongRow *)ctx->lists.p;
     Segment *segs = (Segment *)((char *)ctx->lists.p + off_seg);

@@ -45,17 +45,29 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
     const int lane = threadIdx.x, a = lane & 15, q = lane >> 4;  // MFMA view: entry a of a tile, column group q
     const int g = lane >> 4, i = lane & 15;                       // solver view: system g, lane i of its group
 
-    int64_t u[4], b[4];
-    int k[4], kmax = 0;
+    // Row descriptors of all four rows first (one 16-byte read of the list entries - the list's workspace is
+    // padded for it; past the end of the list the first entry stands in - then the four indptr pairs
+    // together): one wait per stage instead of one per row.
+    int64_t u[4], b[4], b1[4];
+    int k[4], kmax = 0, rel[4];
+    {
+        const int4 r4 = *(const int4 *)(list + (int64_t)blockIdx.x * 4);
+        const int first = blockIdx.x * 4;
+        rel[0] = r4.x;
+        rel[1] = first + 1 < count ? r4.y : r4.x;
+        rel[2] = first + 2 < count ? r4.z : r4.x;
+        rel[3] = first + 3 < count ? r4.w : r4.x;
+    }
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-        const int item = blockIdx.x * 4 + p;
-        u[p] = -1; b[p] = 0; k[p] = 0;
-        if (item < count) {
-            u[p] = r0 + list[item];
-            b[p] = indptr[u[p]];
-            k[p] = (int)(indptr[u[p] + 1] - b[p]);
-        }
+        b[p] = indptr[r0 + rel[p]];
+        b1[p] = indptr[r0 + rel[p] + 1];
+    }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const bool have = blockIdx.x * 4 + p < count;
+        u[p] = have ? r0 + rel[p] : -1;
+        k[p] = have ? (int)(b1[p] - b[p]) : 0;
         kmax = k[p] > kmax ? k[p] : kmax;
     }
 

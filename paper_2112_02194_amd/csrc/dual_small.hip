@@ -52,32 +52,51 @@ __global__ __launch_bounds__(64) void dual_small_kernel(const int64_t *__restric
     const int sub = a / G, e = a % G;  // MFMA view: sub-system of the tile and entry slot
     const bool upper = (a & 8) != 0;
 
-    // ---- 1. gather: tile p holds rows p*SPT .. p*SPT + SPT-1 of this wavefront
+    // ---- 1. gather: tile p holds rows p*SPT .. p*SPT + SPT-1 of this wavefront.  List entry, row
+    // descriptor, column id and table row are four dependent loads; each stage is issued for all four
+    // tiles before the next one starts (unconditional loads on clamped addresses, masked afterwards), so
+    // that a wavefront waits for four memory round trips instead of sixteen.
     float4 z[4][NJ];
     float yl[4];  // label of this lane's entry in tile p
+    int rel[4], kk[4];
+    int64_t bb[4], b1[4], idx[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int item = blockIdx.x * NR + p * SPT + sub;
+        rel[p] = list[item < count ? item : count - 1];
+    }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        bb[p] = indptr[r0 + rel[p]];
+        b1[p] = indptr[r0 + rel[p] + 1];
+    }
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         const int rr = p * SPT + sub;
-        const int item = blockIdx.x * NR + rr;
-        int64_t u = -1, b = 0;
-        int k = 0;
-        if (item < count) {
-            u = r0 + list[item];
-            b = indptr[u];
-            k = (int)(indptr[u + 1] - b);
-        }
+        const bool have = blockIdx.x * NR + rr < count;
+        const int64_t u = have ? r0 + rel[p] : -1;
+        kk[p] = have ? (int)(b1[p] - bb[p]) : 0;
         if (q == 0 && e == 0) {
             meta[3 * rr + 0] = (int32_t)(u & 0xffffffff);
             meta[3 * rr + 1] = (int32_t)(u >> 32);
-            meta[3 * rr + 2] = k;
+            meta[3 * rr + 2] = kk[p];
         }
-        const int64_t idx = e < k ? (int64_t)indices[b + e] : -1;
-        yl[p] = e < k ? (values ? values[b + e] : 1.f) : 0.f;
+    }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int64_t at = bb[p] + (e < kk[p] ? e : 0);  // a row of the list has k >= 1: always in range
+        const int32_t id = indices[at];
+        const float yv = values ? values[at] : 1.f;
+        idx[p] = e < kk[p] ? (int64_t)id : -1;
+        yl[p] = e < kk[p] ? yv : 0.f;
+    }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
 #pragma unroll
         for (int j = 0; j < NJ; ++j) z[p][j] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (idx >= 0) {  // one masked region per tile, not one per load
+        if (idx[p] >= 0) {  // one masked region per tile, not one per load
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) z[p][j] = *(const float4 *)(Z + idx * D + (4 * j + q) * 4);
+            for (int j = 0; j < NJ; ++j) z[p][j] = *(const float4 *)(Z + idx[p] * D + (4 * j + q) * 4);
         }
     }
     // ---- 2. the tiles' products; tile p's 16 x 16 result to LDS (only its diagonal blocks are used)

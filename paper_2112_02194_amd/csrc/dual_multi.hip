@@ -72,13 +72,22 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
     }
 
     // ---- 1. S of every row, packed lower triangle in LDS
+    int32_t idv[4][M];  // the column ids of all four rows first: one wait, not one per row
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+        for (int t = 0; t < M; ++t) {
+            const int e = 16 * t + a;
+            const int32_t id = indices[b[p] + (e < k[p] ? e : 0)];  // clamped: unconditional load, masked below
+            idv[p][t] = e < k[p] ? id : -1;
+        }
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         float4 z[M][NJ];
 #pragma unroll
         for (int t = 0; t < M; ++t) {
             const int e = 16 * t + a;
-            const int32_t id = e < k[p] ? indices[b[p] + e] : -1;
+            const int32_t id = idv[p][t];
             if (q == 0) ids[p * K + e] = id;
 #pragma unroll
             for (int j = 0; j < NJ; ++j) z[t][j] = make_float4(0.f, 0.f, 0.f, 0.f);

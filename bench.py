@@ -23,8 +23,8 @@ if ROOT not in sys.path:
 # HBM bytes per launch measured with rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by the copy-probe factors);
 # source: profiles/c3_epoch_hbm_traffic.md.  Keyed by (workload, kernel as named in the roofline object).
 MEASURED_TRAFFIC_BYTES = {
-    ("c3", "dual_multi_kernel<128, 2>"): 2.0 * 25099957 * 1024 + 1516525 * 1024,   # 53.0 GB (second gather included)
-    ("c3", "dual_rows_kernel<128>"): 2.0 * 8966406 * 1024 + 2064917 * 1024,        # 20.5 GB
+    ("c3", "dual_multi_kernel<128, 2>"): 2.0 * 24195312 * 1024 + 1516525 * 1024,   # 51.1 GB (second gather included)
+    ("c3", "dual_rows_kernel<128>"): 2.0 * 8965572 * 1024 + 2064917 * 1024,        # 20.5 GB
 }
 HBM_PEAK_GBS = 8000.0
 MFMA_F32_PEAK_TFLOPS = 157.3

@@ -14,6 +14,10 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Four consecutive entries of a row list, read with one load.  The lists start at arbitrary 4-byte offsets of
+// the workspace (which is padded so that reading up to three entries past a list's end stays inside it).
+struct __attribute__((packed, aligned(4))) ListQuad { int32_t x, y, z, w; };
+
 template <int B, int E, class F> __device__ __forceinline__ void static_for(F &&f) {
     if constexpr (B < E) {
         f(std::integral_constant<int, B>{});

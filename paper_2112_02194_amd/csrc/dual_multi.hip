@@ -51,7 +51,7 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
     int64_t u[4], b[4], b1[4];
     int k[4], kmax = 0, rel[4];
     {
-        const int4 r4 = *(const int4 *)(list + (int64_t)blockIdx.x * 4);
+        const ListQuad r4 = *(const ListQuad *)(list + (int64_t)blockIdx.x * 4);
         const int first = blockIdx.x * 4;
         rel[0] = r4.x;
         rel[1] = first + 1 < count ? r4.y : r4.x;

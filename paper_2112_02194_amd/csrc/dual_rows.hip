@@ -50,7 +50,7 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
     {
         // one 16-byte read of the wavefront's four list entries; past the end of the list (its workspace is
         // padded for this) the first entry stands in
-        const int4 r4 = *(const int4 *)(list + (int64_t)blockIdx.x * RPW);
+        const ListQuad r4 = *(const ListQuad *)(list + (int64_t)blockIdx.x * RPW);
         const int first = blockIdx.x * RPW;
         rel[0] = r4.x;
         rel[1] = first + 1 < count ? r4.y : r4.x;

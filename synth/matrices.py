@@ -23,9 +23,17 @@ Recipes (degrees -> column ids), one per configuration key:
         columns uniform.
 
 Zipf(s) over ranks 1..N is drawn as floor of the continuous density x^-s on
-[1, N+1), which has the same tail and needs no table.  Duplicate (row, col)
-pairs are dropped after generation, so realised degrees can be slightly below
-the drawn ones; callers print the realised statistics.
+[1, N+1), which has the same tail and needs no table.
+
+Column ids inside a row are distinct.  ``c2`` .. ``c5`` redraw a colliding slot
+(attempt t of slot (row, j) is again a pure hash of (seed, t, row, j)) until the
+row holds as many distinct ids as its drawn degree, so the realised degrees are
+the drawn ones; ``c1`` drops duplicate pairs instead, which is what brings its
+clipped-Zipf mean of 27.8 down to the "about 20" its statement names.
+
+Matrices are built in blocks of rows (no single sort sees more than ``BLOCK``
+keys) and transposed by column ranges, so 100M x 100M with 2.5e9 entries fits
+the 2^31-element limits of the sorting primitives.
 """
 from __future__ import annotations
 
@@ -141,12 +149,15 @@ def _geometric(u: torch.Tensor, mean: float, kmax: int) -> torch.Tensor:
 
 # --------------------------------------------------------------------------- CSR helpers
 
+BLOCK = 1 << 27  # most keys handed to one sort
+
+
 def csr_from_edges(rows: int, cols: int, r: torch.Tensor, c: torch.Tensor,
                    v: Optional[torch.Tensor] = None):
-    """Sort edges by (row, col), drop duplicate pairs, return (indptr, indices, values)."""
+    """Sort edges by (row, col), drop duplicate pairs, return (indptr, indices, values).
+    One sort over all edges: for edge lists below 2^31 entries."""
     if r.numel() >= 2 ** 31:
-        raise ValueError(f"{r.numel()} drawn entries: the generator sorts a matrix in one piece and is limited to "
-                         "2^31-1 entries; build fewer rows (configuration c5 fits up to about 80M rows)")
+        raise ValueError("csr_from_edges sorts the edge list in one piece: at most 2^31-1 entries")
     key = r.to(torch.int64) * cols + c.to(torch.int64)
     if v is None:
         key = torch.unique(key)  # sorted, duplicates removed
@@ -171,10 +182,58 @@ def _expand_rows(indptr: torch.Tensor) -> torch.Tensor:
     return torch.repeat_interleave(torch.arange(rows, device=indptr.device, dtype=torch.int64), deg)
 
 
-def transpose_csr(rows: int, cols: int, indptr, indices, values=None):
-    """CSR of the transposed matrix (true transpose, columns sorted inside each row)."""
-    r = _expand_rows(indptr)
-    return csr_from_edges(cols, rows, indices.to(torch.int64), r, values)
+def _ranges(ptr: torch.Tensor, block: int):
+    """Cut [0, n) into consecutive ranges [a, b) with ptr[b] - ptr[a] <= block (at least one item each)."""
+    n = ptr.numel() - 1
+    out, a = [], 0
+    while a < n:
+        b = int(torch.searchsorted(ptr, ptr[a] + block, right=True)) - 1
+        b = min(max(b, a + 1), n)
+        out.append((a, b))
+        a = b
+    return out
+
+
+def transpose_csr(rows: int, cols: int, indptr, indices, values=None, block: int = BLOCK):
+    """CSR of the transposed matrix (true transpose, columns sorted inside each row).
+
+    Counting pass over the column ids, then one sort per range of columns that holds at most
+    ``block`` entries; the entries of a range are picked out of the matrix chunk by chunk."""
+    dev = indices.device
+    nnz = indices.numel()
+    counts = torch.zeros(cols, dtype=torch.int64, device=dev)
+    for p0 in range(0, nnz, block):
+        counts += torch.bincount(indices[p0:p0 + block], minlength=cols)
+    t_indptr = torch.zeros(cols + 1, dtype=torch.int64, device=dev)
+    torch.cumsum(counts, 0, out=t_indptr[1:])
+    del counts
+    t_indices = torch.empty(nnz, dtype=torch.int32, device=dev)
+    t_values = None if values is None else torch.empty(nnz, dtype=values.dtype, device=dev)
+    for c0, c1 in _ranges(t_indptr, block):
+        keys, vals = [], []
+        for p0 in range(0, nnz, block):
+            idx = indices[p0:p0 + block]
+            sel = torch.nonzero((idx >= c0) & (idx < c1)).flatten()
+            if sel.numel() == 0:
+                continue
+            cc = idx[sel].to(torch.int64) - c0
+            sel += p0
+            rr = torch.searchsorted(indptr, sel, right=True) - 1  # the row that holds entry `sel`
+            keys.append(cc * rows + rr)
+            if values is not None:
+                vals.append(values[sel])
+        o0, o1 = int(t_indptr[c0]), int(t_indptr[c1])
+        if o1 == o0:
+            continue
+        key = torch.cat(keys)
+        del keys
+        if values is None:
+            key = torch.sort(key).values
+        else:
+            key, order = torch.sort(key)
+            t_values[o0:o1] = torch.cat(vals)[order]
+        t_indices[o0:o1] = (key - torch.div(key, rows, rounding_mode="floor") * rows).to(torch.int32)
+    return t_indptr, t_indices, t_values
 
 
 # --------------------------------------------------------------------------- problems
@@ -245,64 +304,147 @@ def _permutation(n: int, seed: int, stream: int, device) -> torch.Tensor:
     return torch.argsort(h, stable=True)
 
 
-def _columns(kind: str, rows: int, cols: int, seed: int, r: torch.Tensor, j: torch.Tensor) -> torch.Tensor:
-    device = r.device
-    u = uniform01(hash_u64(seed, 2, r, j))
-    if kind == "c1":
-        perm = _permutation(cols, seed, 7, device)
-        return perm[_zipf_rank(u, 1.1, cols) - 1]
-    if kind in ("c2", "c4", "c5"):
-        return torch.clamp((u * cols).to(torch.int64), 0, cols - 1)
-    if kind == "c3":
-        nhosts = max(1, cols // 100)
-        hid = torch.arange(nhosts, device=device, dtype=torch.int64)
-        w = torch.exp(_normal(seed, 3, hid, 0))  # lognormal(0, 1)
-        size = torch.clamp(torch.floor(w / w.sum() * cols).to(torch.int64), min=1)
-        # give the rounding remainder to the largest host so sizes sum to cols
-        size[torch.argmax(size)] += cols - int(size.sum())
-        assert int(size.min()) >= 1
-        start = torch.zeros(nhosts + 1, dtype=torch.int64, device=device)
-        torch.cumsum(size, 0, out=start[1:])
-        host = torch.searchsorted(start, r, right=True) - 1
-        hs, h0 = size[host], start[host]
-        u2 = uniform01(hash_u64(seed, 5, r, j))
-        local = h0 + torch.clamp((u2 * (hs - 1).double()).to(torch.int64), max=torch.clamp(hs - 2, min=0))
-        local = local + (local >= r).to(torch.int64)  # skip self
-        perm = _permutation(cols, seed, 7, device)
-        popular = perm[_zipf_rank(u2, 1.0, cols) - 1]
-        inside = (u < 0.8) & (hs > 1)
-        return torch.where(inside, local, popular)
-    raise ValueError(kind)
+class _ColumnSampler:
+    """Column id of slot (row, j), attempt t: a pure function of (seed, t, row, j).  The tables a recipe
+    needs (host boundaries, the rank -> id permutation) are built once."""
+
+    STRIDE = 16  # hash streams of attempt t: 2 + 16 t and 5 + 16 t (attempt 0: the recipe's own streams 2 and 5)
+
+    def __init__(self, kind: str, rows: int, cols: int, seed: int, device):
+        self.kind, self.rows, self.cols, self.seed = kind, rows, cols, seed
+        if kind in ("c1", "c3"):
+            self.perm = _permutation(cols, seed, 7, device)
+        if kind == "c3":
+            nhosts = max(1, cols // 100)
+            hid = torch.arange(nhosts, device=device, dtype=torch.int64)
+            w = torch.exp(_normal(seed, 3, hid, 0))  # lognormal(0, 1)
+            size = torch.clamp(torch.floor(w / w.sum() * cols).to(torch.int64), min=1)
+            # give the rounding remainder to the largest host so sizes sum to cols
+            size[torch.argmax(size)] += cols - int(size.sum())
+            assert int(size.min()) >= 1
+            self.size = size
+            self.start = torch.zeros(nhosts + 1, dtype=torch.int64, device=device)
+            torch.cumsum(size, 0, out=self.start[1:])
+
+    def draw(self, r: torch.Tensor, j: torch.Tensor, attempt: int = 0) -> torch.Tensor:
+        kind, cols, seed = self.kind, self.cols, self.seed
+        u = uniform01(hash_u64(seed, 2 + self.STRIDE * attempt, r, j))
+        if attempt >= 16 or kind in ("c2", "c4", "c5"):  # late attempts of every recipe: uniform over all columns
+            return torch.clamp((u * cols).to(torch.int64), 0, cols - 1)
+        if kind == "c1":
+            return self.perm[_zipf_rank(u, 1.1, cols) - 1]
+        if kind == "c3":
+            host = torch.searchsorted(self.start, r, right=True) - 1
+            hs, h0 = self.size[host], self.start[host]
+            u2 = uniform01(hash_u64(seed, 5 + self.STRIDE * attempt, r, j))
+            local = h0 + torch.clamp((u2 * (hs - 1).double()).to(torch.int64), max=torch.clamp(hs - 2, min=0))
+            local = local + (local >= r).to(torch.int64)  # skip self
+            popular = self.perm[_zipf_rank(u2, 1.0, cols) - 1]
+            inside = (u < 0.8) & (hs > 1)
+            if attempt >= 6:  # a host smaller than the row's local share can never supply distinct ids
+                return popular
+            return torch.where(inside, local, popular)
+        raise ValueError(kind)
+
+
+RESAMPLE = {"c1": False, "c2": True, "c3": True, "c4": True, "c5": True}
+MAX_ATTEMPTS = 64
+
+
+def _member(sorted_keys: torch.Tensor, q: torch.Tensor) -> torch.Tensor:
+    if sorted_keys.numel() == 0:
+        return torch.zeros_like(q, dtype=torch.bool)
+    pos = torch.clamp(torch.searchsorted(sorted_keys, q), max=sorted_keys.numel() - 1)
+    return sorted_keys[pos] == q
+
+
+def _block_keys(sampler: _ColumnSampler, r: torch.Tensor, j: torch.Tensor, resample: bool) -> torch.Tensor:
+    """Sorted distinct keys row * cols + col of one block of slots."""
+    cols = sampler.cols
+    key, order = torch.sort(r * cols + sampler.draw(r, j, 0), stable=True)  # of equal keys the lowest slot stays
+    dup = torch.zeros_like(key, dtype=torch.bool)
+    dup[1:] = key[1:] == key[:-1]
+    uniq = key[~dup]
+    if not resample or not bool(dup.any()):
+        return uniq
+    pend = order[dup]  # slots whose id is already taken in their row
+    del key, order, dup
+    accepted = torch.empty(0, dtype=torch.int64, device=r.device)
+    for attempt in range(1, MAX_ATTEMPTS):
+        if pend.numel() == 0:
+            break
+        rp = r[pend]
+        kn = rp * cols + sampler.draw(rp, j[pend], attempt)
+        ks, o2 = torch.sort(kn, stable=True)
+        again = torch.zeros_like(kn, dtype=torch.bool)
+        again[o2[1:]] = ks[1:] == ks[:-1]  # the same id drawn twice in this round: the later slot waits
+        bad = again | _member(uniq, kn) | _member(accepted, kn)
+        accepted = torch.sort(torch.cat([accepted, kn[~bad]])).values
+        pend = pend[bad]
+    return torch.sort(torch.cat([uniq, accepted])).values  # slots still pending after the last attempt are dropped
+
+
+def build_csr(kind: str, rows: int, cols: int, seed: int, deg: torch.Tensor, block: int = BLOCK):
+    """CSR of the recipe's matrix from the drawn row degrees, built in blocks of rows."""
+    dev = deg.device
+    sampler = _ColumnSampler(kind, rows, cols, seed, dev)
+    ptr0 = torch.zeros(rows + 1, dtype=torch.int64, device=dev)
+    torch.cumsum(deg, 0, out=ptr0[1:])
+    indices = torch.empty(int(ptr0[-1]), dtype=torch.int32, device=dev)
+    counts = torch.empty(rows, dtype=torch.int64, device=dev)
+    written = 0
+    for a, b in _ranges(ptr0, block):
+        n = int(ptr0[b] - ptr0[a])
+        r = a + torch.repeat_interleave(torch.arange(b - a, device=dev, dtype=torch.int64), deg[a:b])
+        j = torch.arange(n, device=dev, dtype=torch.int64) - (ptr0[r] - ptr0[a])
+        key = _block_keys(sampler, r, j, RESAMPLE[kind])
+        del r, j
+        rr = torch.div(key, cols, rounding_mode="floor")
+        indices[written:written + key.numel()] = (key - rr * cols).to(torch.int32)
+        counts[a:b] = torch.bincount(rr - a, minlength=b - a)
+        written += key.numel()
+        del key, rr
+    indptr = torch.zeros(rows + 1, dtype=torch.int64, device=dev)
+    torch.cumsum(counts, 0, out=indptr[1:])
+    return indptr, indices[:written]
+
+
+def entry_values(seed: int, indptr: torch.Tensor, indices: torch.Tensor, transposed: bool = False,
+                 block: int = BLOCK) -> torch.Tensor:
+    """Labels in [0.5, 1.5), a pure function of (seed, row, column) of the untransposed matrix."""
+    out = torch.empty(indices.numel(), dtype=torch.float32, device=indices.device)
+    for a, b in _ranges(indptr, block):
+        o0, o1 = int(indptr[a]), int(indptr[b])
+        deg = indptr[a + 1:b + 1] - indptr[a:b]
+        r = a + torch.repeat_interleave(torch.arange(b - a, device=indices.device, dtype=torch.int64), deg)
+        c = indices[o0:o1].to(torch.int64)
+        if transposed:
+            r, c = c, r
+        out[o0:o1] = (0.5 + uniform01(hash_u64(seed, 9, r, c))).to(torch.float32)
+    return out
 
 
 def make_problem(kind: str, device="cpu", rows: Optional[int] = None, cols: Optional[int] = None,
                  d: Optional[int] = None, values: str = "ones", seed: Optional[int] = None,
-                 dtype: Optional[str] = None) -> SparseProblem:
+                 dtype: Optional[str] = None, tables: bool = True) -> SparseProblem:
     """Build one synthetic problem.  ``rows``/``cols``/``d`` override the
     configuration's sizes (the recipe scales with them); ``values`` is "ones"
     (binary implicit feedback, stored as no value array) or "uniform" (labels in
-    [0.5, 1.5), to exercise general y)."""
+    [0.5, 1.5), to exercise general y); ``tables=False`` leaves W0 and H0 out."""
     cfg = dict(CONFIGS[kind])
     rows = rows or cfg["rows"]
     cols = cols or cfg["cols"]
     d = d or cfg["d"]
     seed = cfg["seed"] if seed is None else seed
     tdt = {"f32": torch.float32, "bf16": torch.bfloat16}[dtype or cfg["dtype"]]
-    deg = _degrees(kind, rows, seed, device)
-    deg = torch.clamp(deg, max=cols)
-    indptr0 = torch.zeros(rows + 1, dtype=torch.int64, device=device)
-    torch.cumsum(deg, 0, out=indptr0[1:])
-    r = _expand_rows(indptr0)
-    j = torch.arange(r.numel(), device=device, dtype=torch.int64) - indptr0[r]
-    c = _columns(kind, rows, cols, seed, r, j)
-    v = None
-    if values == "uniform":
-        v = (0.5 + uniform01(hash_u64(seed, 9, r, j))).to(torch.float32)
-    indptr, indices, vals = csr_from_edges(rows, cols, r, c, v)
-    del r, j, c
-    t_indptr, t_indices, t_vals = transpose_csr(rows, cols, indptr, indices, vals)
-    W0 = init_table(rows, d, seed, 11, device=device, dtype=tdt)
-    H0 = init_table(cols, d, seed, 13, device=device, dtype=tdt)
+    deg = torch.clamp(_degrees(kind, rows, seed, device), max=cols - 1 if kind == "c3" else cols)
+    indptr, indices = build_csr(kind, rows, cols, seed, deg)
+    del deg
+    vals = entry_values(seed, indptr, indices) if values == "uniform" else None
+    t_indptr, t_indices, _ = transpose_csr(rows, cols, indptr, indices, None)
+    t_vals = entry_values(seed, t_indptr, t_indices, transposed=True) if values == "uniform" else None
+    W0 = init_table(rows, d, seed, 11, device=device, dtype=tdt) if tables else None
+    H0 = init_table(cols, d, seed, 13, device=device, dtype=tdt) if tables else None
     return SparseProblem(kind, rows, cols, d, cfg["alpha"], cfg["lam"], cfg["epochs"], tdt,
                          indptr, indices, vals, t_indptr, t_indices, t_vals, W0, H0)
 

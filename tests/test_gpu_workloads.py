@@ -1,6 +1,6 @@
 """GPU parity on the shapes of the larger configurations.
 
-Scaled-down versions of configurations 2-5 are compared with the oracle on every row; configuration 3 is
+Scaled-down versions of configurations 2-5 are compared with the oracle on every row; each of them is
 also run at its full size, in the launch configuration bench.py times, and checked on sampled rows (rows
 are independent given the fixed table and its Gramian, so a sample is an exact check of those rows).
 """
@@ -43,7 +43,7 @@ def test_scaled_configuration_one_epoch(ctx, gpu_device, kind, rows):
     say(f"  {kind}: errW {rel_fro(f64(W), Wo):.2e} errH {rel_fro(f64(H), Ho):.2e} loss rel {abs(lg - lo) / abs(lo):.2e} "
         f"max deg rows {int((p.indptr[1:] - p.indptr[:-1]).max())} cols {int((p.t_indptr[1:] - p.t_indptr[:-1]).max())}")
     assert rel_fro(f64(W), Wo) <= tol and rel_fro(f64(H), Ho) <= tol
-    assert max_row_err(f64(W), Wo) <= 10 * tol and max_row_err(f64(H), Ho) <= 10 * tol
+    assert max_row_err(f64(W), Wo) <= tol and max_row_err(f64(H), Ho) <= tol
     assert abs(lg - lo) <= tol * abs(lo)
 
 
@@ -64,31 +64,65 @@ def _sample_rows(indptr, n_uniform, n_per_stratum, n_long, seed):
     return torch.unique(torch.cat(picks))
 
 
-def test_configuration_3_full_size_sampled(ctx, gpu_device):
-    """10M x 10M, d=128, defaults as in bench.py: Gramians in full, solved rows on a seeded sample."""
-    say("c3 full size: generate")
-    p = make_problem("c3", device=gpu_device)
+class _HostChunks:
+    """Row slices of a device table as fp64 numpy arrays, so that the oracle's chunked Gramian can walk
+    a table that is too large to copy to the host in one piece (or is stored as bf16)."""
+
+    def __init__(self, t):
+        self.t, self.shape = t, tuple(t.shape)
+
+    def __getitem__(self, sl):
+        return self.t[sl].double().cpu().numpy()
+
+
+FULL = {  # kind: (uniformly sampled rows per half, rows per stratum, long rows besides the four largest)
+    "c2": (100000, 1500, 40),
+    "c3": (100000, 1500, 40),
+    "c4": (100000, 1500, 40),
+    "c5": (100000, 1500, 40),
+}
+
+
+@pytest.mark.parametrize("kind", ["c2", "c3", "c4", "c5"])
+def test_configuration_full_size_sampled(ctx, gpu_device, kind):
+    """The named configuration at its full size (c5: 100M x 100M, 2.5e9 entries, bf16 tables), defaults as in
+    bench.py: Gramians checked in full, solved rows on a seeded sample (uniform rows, the k = 0, 1, 2 strata, the
+    strata at the row-class boundaries, the largest rows and a spread of the other long ones)."""
+    import time
+    t0 = time.time()
+    say(f"{kind} full size: generate")
+    p = make_problem(kind, device=gpu_device)
+    torch.cuda.synchronize()
+    say(f"{kind} full size: generated in {time.time() - t0:.1f} s: {p.stats()}")
     Y = als.Csr(p.rows, p.cols, p.indptr, p.indices)
     Yt = als.Csr(p.cols, p.rows, p.t_indptr, p.t_indices)
+    als.als_check_csr(ctx, Y)
+    als.als_check_csr(ctx, Yt)
     prm = als.make_params(p.alpha, p.lam)
-    W, H = p.W0.clone(), p.H0.clone()
+    W, H = p.W0, p.H0  # updated in place: the column half sees the W just solved
+    storage = "f32" if p.table_dtype == torch.float32 else "bf16"
+    tol = TOL[p.table_dtype]
+    n_uniform, n_stratum, n_long = FULL[kind]
     for tag, M, V, X in (("row half", Y, H, W), ("column half", Yt, W, H)):
-        say(f"c3 full size: {tag}")
+        t0 = time.time()
+        say(f"{kind} full size: {tag}")
         G = als.als_gramian(ctx, V)
-        Vh = V.cpu().numpy()
-        Gref = oracle.gramian_matmul(Vh)
+        Gref = oracle.gramian_matmul(_HostChunks(V))
         assert np.abs(f64(G) - Gref).max() <= 1e-5 * np.abs(Gref).max()
+        say(f"  {tag}: Gramian checked, {time.time() - t0:.1f} s")
         als.als_solve_rows(ctx, M, V, G, prm, X)
         als.als_status_sync(ctx)
-        rows = _sample_rows(M.indptr, 20000, 1500, 40, seed=5)
+        rows = _sample_rows(M.indptr, n_uniform, n_stratum, n_long, seed=5)
         sp, si, _, used = extract_rows(M.indptr, M.indices, None, rows)
         Vsub = V[used].double().cpu().numpy()
-        ref = oracle.solve_rows(sp.cpu().numpy(), si.cpu().numpy(), None, Vsub, Gref, p.alpha, p.lam, None, "f32")
+        ref = oracle.solve_rows(sp.cpu().numpy(), si.cpu().numpy(), None, Vsub, Gref, p.alpha, p.lam, None, storage)
         got = f64(X[rows])
         kk = (M.indptr[rows + 1] - M.indptr[rows]).cpu().numpy()
         say(f"  {tag}: {rows.numel()} rows sampled (k from {kk.min()} to {kk.max()}, {int(sp[-1])} entries): "
-            f"rel err {rel_fro(got, ref):.2e}, worst row {max_row_err(got, ref):.2e}")
-        assert rel_fro(got, ref) <= 1e-4
-        assert max_row_err(got, ref) <= 1e-3
+            f"rel err {rel_fro(got, ref):.2e}, worst row {max_row_err(got, ref):.2e}, {time.time() - t0:.1f} s")
+        assert rel_fro(got, ref) <= tol
+        assert max_row_err(got, ref) <= tol
         assert np.all(got[kk == 0] == 0.0)
-        del Vh
+        del Vsub, ref, got, G
+    del p, Y, Yt, W, H, M, V, X
+    torch.cuda.empty_cache()

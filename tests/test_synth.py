@@ -97,3 +97,31 @@ def test_extract_rows_is_a_faithful_submatrix():
         a, b = int(p.indptr[u]), int(p.indptr[u + 1])
         assert torch.equal(used[si[sp[r]:sp[r + 1]].long()], p.indices[a:b].long())
         assert torch.equal(sv[sp[r]:sp[r + 1]], p.values[a:b])
+
+
+def test_block_size_does_not_change_the_matrix_and_degrees_are_the_drawn_ones():
+    """Row blocks and column ranges are plumbing: any block size gives the same CSR and the same transpose;
+    with redrawn collisions every row holds exactly its drawn number of distinct column ids."""
+    from synth.matrices import CONFIGS, _degrees, build_csr, transpose_csr
+    n = 20000
+    for kind in ("c2", "c3", "c4", "c5"):
+        seed = CONFIGS[kind]["seed"]
+        deg = torch.clamp(_degrees(kind, n, seed, "cpu"), max=n - 1)
+        big = build_csr(kind, n, n, seed, deg)
+        small = build_csr(kind, n, n, seed, deg, block=30011)
+        assert torch.equal(big[0], small[0]) and torch.equal(big[1], small[1])
+        assert torch.equal(big[0][1:] - big[0][:-1], deg)
+        _check_csr(n, n, big[0], big[1])
+        ta = transpose_csr(n, n, big[0], big[1])
+        tb = transpose_csr(n, n, big[0], big[1], block=30011)
+        assert torch.equal(ta[0], tb[0]) and torch.equal(ta[1], tb[1])
+        _check_csr(n, n, ta[0], ta[1])
+
+
+def test_transpose_with_values_in_column_ranges():
+    from synth.matrices import transpose_csr
+    p = make_problem("c1", rows=300, cols=250, values="uniform")
+    a = transpose_csr(p.rows, p.cols, p.indptr, p.indices, p.values)
+    b = transpose_csr(p.rows, p.cols, p.indptr, p.indices, p.values, block=97)
+    assert all(torch.equal(x, y) for x, y in zip(a, b))
+    assert torch.equal(a[2], p.t_values) and torch.equal(a[1], p.t_indices)

@@ -103,6 +103,20 @@ als_status als_destroy(als_ctx *ctx);
  * across blocks.  Asynchronous on `stream` (a hipStream_t, NULL = default). */
 als_status als_gramian(als_ctx *ctx, const als_table *V, float *G, void *stream);
 
+/* als_gramian for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  No context; calls no hipMalloc, hipFree or any other allocating
+ * routine.  The per-workgroup partial sums live in a static device array of 10 MiB that every GPU the library
+ * runs on holds until the process ends; it fits tables of at most ALS_GRAMIAN_STATIC_MAX_ROWS rows, larger
+ * ones are refused with ALS_ESHAPE.  `device` must be the calling thread's current device.  Same kernels,
+ * same summation order and therefore the same bits as als_gramian.  The address of the array is looked up
+ * once per device, by als_create or by the first call (so make one of the two before capturing a graph).
+ * All calls on one GPU share the array: calls that overlap in time on one GPU (different streams or
+ * threads) race and give wrong sums; calls on one stream are ordered and safe.  On failure
+ * als_static_last_error() holds the reason (per thread). */
+#define ALS_GRAMIAN_STATIC_MAX_ROWS 262144
+als_status als_gramian_static(int device, const als_table *V, float *G, void *stream);
+const char *als_static_last_error(void);
+
 /* Row update of Eq. 4 (Algorithm 1 lines 3-10) for rows row_begin <= u < row_end of Y:
  *     X[u] = ( sum_{i in Y[u]} v_i (x) v_i + alpha*G + lambda*I )^{-1} sum_{i in Y[u]} y_ui v_i
  * with v_i the rows of the fixed table V (V->rows == Y->cols) and G = V^T V as

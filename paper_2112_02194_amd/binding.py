@@ -24,7 +24,7 @@ SOLVER_DIRECT, SOLVER_CG = 0, 1
 
 EXPORTS = ["als_create", "als_destroy", "als_gramian", "als_solve_rows", "als_epoch", "als_loss",
            "als_status_sync", "als_check_csr", "als_copy_probe", "als_set_timing", "als_get_timing",
-           "als_strerror", "als_last_error"]
+           "als_strerror", "als_last_error", "als_gramian_static", "als_static_last_error"]
 
 
 class c_als_csr(ctypes.Structure):
@@ -79,6 +79,10 @@ def load_library(path: str = LIB_PATH):
     lib.als_strerror.restype = ctypes.c_char_p
     lib.als_last_error.argtypes = [vp]
     lib.als_last_error.restype = ctypes.c_char_p
+    lib.als_gramian_static.argtypes = [i32, P(c_als_table), vp, vp]
+    lib.als_gramian_static.restype = i32
+    lib.als_static_last_error.argtypes = []
+    lib.als_static_last_error.restype = ctypes.c_char_p
     _lib = lib
     return lib
 
@@ -166,6 +170,17 @@ def als_gramian(ctx: Context, V: torch.Tensor, out: Optional[torch.Tensor] = Non
     tv = _table(V)
     ctx._check(ctx.lib.als_gramian(ctx.handle, ctypes.byref(tv), G.data_ptr(), _stream()))
     return G
+
+
+def als_gramian_static(V: torch.Tensor, out: torch.Tensor) -> torch.Tensor:
+    """als_gramian without a context and without any allocation: ``out`` (fp32 [d, d]) is the caller's."""
+    lib = load_library()
+    assert out.dtype == torch.float32 and out.is_contiguous() and out.shape == (V.shape[1], V.shape[1])
+    tv = _table(V)
+    st = lib.als_gramian_static(V.device.index or 0, ctypes.byref(tv), out.data_ptr(), _stream())
+    if st != ALS_OK:
+        raise AlsError(st, f"{lib.als_strerror(st).decode()}: {lib.als_static_last_error().decode()}")
+    return out
 
 
 def als_solve_rows(ctx: Context, Y: Csr, V: torch.Tensor, G: torch.Tensor, params: c_als_params, X: torch.Tensor,

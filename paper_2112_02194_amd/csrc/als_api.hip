@@ -1,5 +1,6 @@
 // C-ABI entry points of libals: argument validation, context and workspace management, and the
 // epoch / loss glue.  All arithmetic of the method lives in the kernel translation units.
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -8,8 +9,11 @@
 
 namespace als {
 
+static thread_local char static_error[256] = "";  // message of the last failed context-free call of this thread
+
 als_status fail(als_ctx *ctx, als_status st, const std::string &msg) {
     if (ctx) ctx->last_error = msg;
+    else snprintf(static_error, sizeof(static_error), "%s", msg.c_str());
     return st;
 }
 
@@ -151,6 +155,7 @@ als_status als_create(als_ctx **out, int device) {
     als_ctx *ctx = new (std::nothrow) als_ctx();
     if (!ctx) return ALS_ENOMEM;
     ctx->device = device;
+    (void)gramian_static_setup(device);  // address of this GPU's static workspace, for als_gramian_static
     als_status st = ensure(ctx, ctx->small, SM_BYTES);
     if (st == ALS_OK) st = ensure(ctx, ctx->gram_w, 128 * 128 * sizeof(float));
     if (st == ALS_OK) st = ensure(ctx, ctx->gram_h, 128 * 128 * sizeof(float));
@@ -202,6 +207,26 @@ als_status als_gramian(als_ctx *ctx, const als_table *V, float *G, void *stream)
     timers_reset(ctx);
     return launch_gramian(ctx, V, G, (hipStream_t)stream);
 }
+
+als_status als_gramian_static(int device, const als_table *V, float *G, void *stream) {
+    int ndev = 0, cur = -1;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev || hipGetDevice(&cur) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(nullptr, ALS_EHIP, "als_gramian_static: no such device");
+    }
+    if (cur != device) return fail(nullptr, ALS_EINVAL, "als_gramian_static: `device` must be the calling thread's current device");
+    als_status st = check_table(nullptr, V, "V");
+    if (st != ALS_OK) return st;
+    if (!G) return fail(nullptr, ALS_EINVAL, "G is null");
+    if (V->rows > ALS_GRAMIAN_STATIC_MAX_ROWS)
+        return fail(nullptr, ALS_ESHAPE, "als_gramian_static: V has " + std::to_string(V->rows) + " rows, the static workspace holds the partial sums of at most " +
+                                             std::to_string((long long)ALS_GRAMIAN_STATIC_MAX_ROWS) + " (use als_gramian)");
+    st = launch_gramian_static(device, V, G, (hipStream_t)stream);
+    if (st != ALS_OK) return fail(nullptr, st, "als_gramian_static: launch failed");
+    return ALS_OK;
+}
+
+const char *als_static_last_error(void) { return static_error; }
 
 als_status als_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
                           const als_params *prm, als_table *X, int64_t r0, int64_t r1, void *stream) {

@@ -185,6 +185,8 @@ als_status side_join(als_ctx *ctx, int i, hipStream_t s);
 
 // kernels' host launchers (each validates nothing: the API layer has done so)
 als_status launch_gramian(als_ctx *ctx, const als_table *V, float *G, hipStream_t s);
+hipError_t gramian_static_setup(int device);
+als_status launch_gramian_static(int device, const als_table *V, float *G, hipStream_t s);
 als_status launch_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
                              const als_params *prm, als_table *X, int64_t r0, int64_t r1, hipStream_t s);
 als_status launch_loss(als_ctx *ctx, const als_csr *Y, const als_table *W, const als_table *H,

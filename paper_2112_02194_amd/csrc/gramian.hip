@@ -9,6 +9,8 @@
 // reproducible bit for bit.  The grid grows with the table so that no fp32 summation chain inside
 // the matrix core is longer than GRAM_CHAIN steps: on a 1e8-row table chains of 12 000 steps showed a
 // relative error of 1.3e-5 on the diagonal (sums of squares), all of one sign.
+#include <mutex>
+
 #include "als_internal.h"
 
 namespace als {
@@ -164,6 +166,54 @@ als_status launch_gramian(als_ctx *ctx, const als_table *V, float *G, hipStream_
         case 128: return bf ? gramian_typed<128, true>(ctx, V, G, s) : gramian_typed<128, false>(ctx, V, G, s);
     }
     return fail(ctx, ALS_EDTYPE, "unsupported d");
+}
+
+// ---------------------------------------------------------------------------------------------- no allocation
+// als_gramian_static: the same kernels with their partial sums in a file-scope device array instead of
+// the context's workspace, for callers that cannot allocate.  Every GPU holds its own copy of the array
+// at its own address; the address is looked up once per device (with that device current) and kept.
+// Nothing in the array has to start at zero: every partial and slice that is read has been written by
+// the same call.  Calls that overlap on one GPU share the array and race.
+constexpr int STATIC_BLOCKS = 128;   // 262 144 rows at d = 128 (2048 rows per workgroup)
+constexpr int STATIC_SLICES = 16;
+constexpr size_t STATIC_BYTES = (size_t)STATIC_BLOCKS * 128 * 128 * sizeof(float) +
+                                (size_t)STATIC_SLICES * 128 * 128 * sizeof(double);
+static __device__ __align__(256) unsigned char scratch[STATIC_BYTES];
+
+constexpr int STATIC_MAX_DEVICES = 64;
+static void *scratch_ptr[STATIC_MAX_DEVICES];  // per device, null until looked up
+static std::mutex scratch_mutex;
+
+// Device address of this GPU's copy of the array; `device` must be current.
+hipError_t gramian_static_setup(int device) {
+    if (device < 0 || device >= STATIC_MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (scratch_ptr[device]) return hipSuccess;
+    void *p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    scratch_ptr[device] = p;
+    return hipSuccess;
+}
+
+template <int D, bool BF16>
+static als_status gramian_static_typed(const als_table *V, float *G, void *work, hipStream_t s) {
+    const int nblocks = gramian_blocks<D>(V->rows);  // <= STATIC_BLOCKS: the caller has checked the row count
+    gramian_enqueue<D, BF16>(V, G, work, nblocks, std::min(nblocks, STATIC_SLICES), s);
+    return hipGetLastError() == hipSuccess ? ALS_OK : ALS_EHIP;
+}
+
+als_status launch_gramian_static(int device, const als_table *V, float *G, hipStream_t s) {
+    if (gramian_static_setup(device) != hipSuccess) return ALS_EHIP;
+    void *work = scratch_ptr[device];
+    const bool bf = V->dtype == ALS_BF16;
+    switch (V->d) {
+        case 16: return bf ? gramian_static_typed<16, true>(V, G, work, s) : gramian_static_typed<16, false>(V, G, work, s);
+        case 32: return bf ? gramian_static_typed<32, true>(V, G, work, s) : gramian_static_typed<32, false>(V, G, work, s);
+        case 64: return bf ? gramian_static_typed<64, true>(V, G, work, s) : gramian_static_typed<64, false>(V, G, work, s);
+        case 128: return bf ? gramian_static_typed<128, true>(V, G, work, s) : gramian_static_typed<128, false>(V, G, work, s);
+    }
+    return ALS_EDTYPE;
 }
 
 }  // namespace als

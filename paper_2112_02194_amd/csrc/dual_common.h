@@ -37,6 +37,44 @@ template <int GW, int C> __device__ __forceinline__ float group_bcast(float x) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------- split products
+// S = I + Z_I Z_I^T on the bf16 matrix cores at fp32-like accuracy: every fp32 entry z is cut into
+// hi = its upper 16 bits (a bf16 number) and lo = the upper 16 bits of z - hi (z - hi is exact), so that
+// z = hi + lo up to 2^-16 |z|, and a product z z' is taken as hi hi' + hi lo' + lo hi' (the dropped
+// lo lo' is below 2^-16 |z z'|).  Three v_mfma_f32_16x16x32_bf16 (16 clocks each, 32 columns deep) replace
+// eight v_mfma_f32_16x16x4_f32 (32 clocks each): a fifth of the matrix-core time for three vector
+// instructions per entry.  Accumulation is fp32 as before.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+struct SplitOperand { bf16x8 hi, lo; };  // eight columns of one table row
+
+// Upper halves of x (low 16 bits of the result) and y (high 16 bits).
+__device__ __forceinline__ uint32_t pack_upper(float x, float y) {
+    return __builtin_amdgcn_perm(__float_as_uint(y), __float_as_uint(x), 0x07060302u);
+}
+__device__ __forceinline__ float lower_part(float x) { return x - __uint_as_float(__float_as_uint(x) & 0xffff0000u); }
+
+// Operand of one 32-column step from two 16-byte pieces of a row (the column order inside the step is the
+// same for both operands of a product, so it does not matter).
+__device__ __forceinline__ SplitOperand split_operand(const float4 &p, const float4 &r) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 h = {pack_upper(p.x, p.y), pack_upper(p.z, p.w), pack_upper(r.x, r.y), pack_upper(r.z, r.w)};
+    const u32x4 l = {pack_upper(lower_part(p.x), lower_part(p.y)), pack_upper(lower_part(p.z), lower_part(p.w)),
+                     pack_upper(lower_part(r.x), lower_part(r.y)), pack_upper(lower_part(r.z), lower_part(r.w))};
+    SplitOperand o;
+    o.hi = __builtin_bit_cast(bf16x8, h);
+    o.lo = __builtin_bit_cast(bf16x8, l);
+    return o;
+}
+
+// acc += A B^T over the step's 32 columns (A supplies the tile's rows 4q+v, B its column a, as with the
+// fp32 instruction).
+__device__ __forceinline__ floatx4 split_mfma(const SplitOperand &a, const SplitOperand &b, floatx4 acc) {
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.hi, b.hi, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.hi, b.lo, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.lo, b.hi, acc, 0, 0, 0);
+    return acc;
+}
+
 // per-class launchers, one translation unit each (they compile in parallel)
 void launch_dual_k16(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
                      int count, int32_t *err, hipStream_t s);

@@ -96,18 +96,30 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
                 for (int j = 0; j < NJ; ++j) z[t][j] = *(const float4 *)(Z + (int64_t)id * D + (4 * j + q) * 4);
             }
         }
+        SplitOperand zs[M][NJ / 2 > 0 ? NJ / 2 : 1];
+        if constexpr (NJ >= 2) {
+#pragma unroll
+            for (int t = 0; t < M; ++t)
+#pragma unroll
+                for (int h = 0; h < NJ / 2; ++h) zs[t][h] = split_operand(z[t][2 * h], z[t][2 * h + 1]);
+        }
         __builtin_amdgcn_s_setprio(1);  // matrix-core work first: other wavefronts fill in with vector work
 #pragma unroll
         for (int t1 = 0; t1 < M; ++t1)
 #pragma unroll
             for (int t2 = 0; t2 <= t1; ++t2) {
                 floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+                if constexpr (NJ >= 2) {
 #pragma unroll
-                for (int j = 0; j < NJ; ++j) {
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[t2][j].x, z[t1][j].x, acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[t2][j].y, z[t1][j].y, acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[t2][j].z, z[t1][j].z, acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[t2][j].w, z[t1][j].w, acc, 0, 0, 0);
+                    for (int h = 0; h < NJ / 2; ++h) acc = split_mfma(zs[t2][h], zs[t1][h], acc);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) {
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[t2][j].x, z[t1][j].x, acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[t2][j].y, z[t1][j].y, acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[t2][j].z, z[t1][j].z, acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[t2][j].w, z[t1][j].w, acc, 0, 0, 0);
+                    }
                 }
                 // acc[v] = S[Rr][c], Rr = 16*t1 + a, c = 16*t2 + 4q + v (S is symmetric); keep c <= Rr
                 const int Rr = 16 * t1 + a;

@@ -105,17 +105,21 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
         for (int t1 = 0; t1 < KT; ++t1)
 #pragma unroll
             for (int t2 = 0; t2 <= t1; ++t2) acc[t1][t2] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (NJ >= 2) {  // split products on the bf16 matrix cores (dual_common.h)
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
+            for (int h = 0; h < NJ / 2; ++h) {
+                const SplitOperand zs = split_operand(z[p][0][2 * h], z[p][0][2 * h + 1]);
+                acc[0][0] = split_mfma(zs, zs, acc[0][0]);
+            }
+        } else {
 #pragma unroll
-            for (int t1 = 0; t1 < KT; ++t1)
-#pragma unroll
-                for (int t2 = 0; t2 <= t1; ++t2) {
-                    acc[t1][t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][t1][j].x, z[p][t2][j].x, acc[t1][t2], 0, 0, 0);
-                    acc[t1][t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][t1][j].y, z[p][t2][j].y, acc[t1][t2], 0, 0, 0);
-                    acc[t1][t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][t1][j].z, z[p][t2][j].z, acc[t1][t2], 0, 0, 0);
-                    acc[t1][t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][t1][j].w, z[p][t2][j].w, acc[t1][t2], 0, 0, 0);
-                }
+            for (int j = 0; j < NJ; ++j) {
+                acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][0][j].x, z[p][0][j].x, acc[0][0], 0, 0, 0);
+                acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][0][j].y, z[p][0][j].y, acc[0][0], 0, 0, 0);
+                acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][0][j].z, z[p][0][j].z, acc[0][0], 0, 0, 0);
+                acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][0][j].w, z[p][0][j].w, acc[0][0], 0, 0, 0);
+            }
+        }
         // lower block triangle of S = I + Z_I Z_I^T (diagonal tiles in full)
 #pragma unroll
         for (int t1 = 0; t1 < KT; ++t1)

@@ -103,12 +103,20 @@ __global__ __launch_bounds__(64) void dual_small_kernel(const int64_t *__restric
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (NJ >= 2) {  // split products on the bf16 matrix cores (dual_common.h)
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][j].x, z[p][j].x, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][j].y, z[p][j].y, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][j].z, z[p][j].z, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][j].w, z[p][j].w, acc, 0, 0, 0);
+            for (int h = 0; h < NJ / 2; ++h) {
+                const SplitOperand zs = split_operand(z[p][2 * h], z[p][2 * h + 1]);
+                acc = split_mfma(zs, zs, acc);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][j].x, z[p][j].x, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][j].y, z[p][j].y, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][j].z, z[p][j].z, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(z[p][j].w, z[p][j].w, acc, 0, 0, 0);
+            }
         }
 #pragma unroll
         for (int v = 0; v < 4; ++v) {

@@ -50,41 +50,53 @@ __global__ __launch_bounds__(64, 2) void dual_wide_kernel(const int64_t *__restr
         if (q == 0) ids[e] = myid[t];
     }
     // the first RT tiles stay in registers for the whole phase (one round of loads, all in flight
-    // together); later tiles are fetched when they are needed
-    constexpr int RT = KT < 5 ? KT : 5;
-    float4 zres[RT][NJ];
+    // together), already cut into the hi/lo bf16 operands of the split products (dual_common.h); later
+    // tiles are fetched and cut when they are needed
+    constexpr int RT = KT < 5 ? KT : (KT < 7 ? 5 : 4), NH = NJ / 2;
+    auto fetch = [&](int t, float4 (&raw)[NJ]) {
 #pragma unroll
-    for (int t = 0; t < RT; ++t) {
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) zres[t][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int j = 0; j < NJ; ++j) raw[j] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (myid[t] >= 0) {  // one masked region per tile, not one per load
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) zres[t][j] = *(const float4 *)(Z + (int64_t)myid[t] * D + (4 * j + q) * 4);
+            for (int j = 0; j < NJ; ++j) raw[j] = *(const float4 *)(Z + (int64_t)myid[t] * D + (4 * j + q) * 4);
         }
+    };
+    SplitOperand zop[RT][NH];
+    {
+        float4 raw[RT][NJ];
+#pragma unroll
+        for (int t = 0; t < RT; ++t) fetch(t, raw[t]);
+#pragma unroll
+        for (int t = 0; t < RT; ++t)
+#pragma unroll
+            for (int h = 0; h < NH; ++h) zop[t][h] = split_operand(raw[t][2 * h], raw[t][2 * h + 1]);
     }
 #pragma unroll
     for (int t1 = 0; t1 < KT; ++t1) {
-        float4 zb[NJ];
+        SplitOperand zb[NH];
+        if (t1 < RT) {
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-            if (t1 < RT) zb[j] = zres[t1 < RT ? t1 : 0][j];
-            else zb[j] = myid[t1] >= 0 ? *(const float4 *)(Z + (int64_t)myid[t1] * D + (4 * j + q) * 4)
-                                       : make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int h = 0; h < NH; ++h) zb[h] = zop[t1 < RT ? t1 : 0][h];
+        } else {
+            float4 raw[NJ];
+            fetch(t1, raw);
+#pragma unroll
+            for (int h = 0; h < NH; ++h) zb[h] = split_operand(raw[2 * h], raw[2 * h + 1]);
         }
 #pragma unroll
         for (int t2 = 0; t2 <= t1; ++t2) {
             floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (t2 == t1) {
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-                float4 za;
-                if (t2 == t1) za = zb[j];
-                else if (t2 < RT) za = zres[t2 < RT ? t2 : 0][j];
-                else za = myid[t2] >= 0 ? *(const float4 *)(Z + (int64_t)myid[t2] * D + (4 * j + q) * 4)
-                                        : make_float4(0.f, 0.f, 0.f, 0.f);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(za.x, zb[j].x, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(za.y, zb[j].y, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(za.z, zb[j].z, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(za.w, zb[j].w, acc, 0, 0, 0);
+                for (int h = 0; h < NH; ++h) acc = split_mfma(zb[h], zb[h], acc);
+            } else if (t2 < RT) {
+#pragma unroll
+                for (int h = 0; h < NH; ++h) acc = split_mfma(zop[t2 < RT ? t2 : 0][h], zb[h], acc);
+            } else {
+                float4 raw[NJ];
+                fetch(t2, raw);
+#pragma unroll
+                for (int h = 0; h < NH; ++h) acc = split_mfma(split_operand(raw[2 * h], raw[2 * h + 1]), zb[h], acc);
             }
             // acc[v] = S[Rr][c], Rr = 16*t1 + a, c = 16*t2 + 4q + v (S is symmetric); keep c <= Rr
             const int Rr = 16 * t1 + a;

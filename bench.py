@@ -20,12 +20,22 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per launch measured with rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by the copy-probe factors);
-# source: profiles/c3_epoch_hbm_traffic.md.  Keyed by (workload, kernel as named in the roofline object).
-MEASURED_TRAFFIC_BYTES = {
-    ("c3", "dual_multi_kernel<128, 2>"): 2.0 * 24195312 * 1024 + 1516525 * 1024,   # 51.1 GB (second gather included)
-    ("c3", "dual_rows_kernel<128>"): 2.0 * 8965572 * 1024 + 2064917 * 1024,        # 20.5 GB
-}
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` on `workload` from the committed counter summary
+    (profiles/hbm_traffic.json, written by profile_summary.py from rocprofv3 FETCH_SIZE / WRITE_SIZE passes
+    scaled by the copy-probe factors); None when that kernel was not profiled on that workload."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        table = json.load(f)
+    key = kernel.replace(" ", "")
+    for entry in table.get(workload, []):
+        if entry["kernel"].replace(" ", "").startswith(key.split("(")[0]):
+            return entry["bytes_per_launch"]
+    return None
+
+
 HBM_PEAK_GBS = 8000.0
 MFMA_F32_PEAK_TFLOPS = 157.3
 
@@ -138,77 +148,87 @@ def main():
         torch.cuda.synchronize()
         log(f"warmup {i} done")
     als.als_set_timing(ctx, True)
-    stage_ms = {}
+    stage_ms, stage_launches = {}, {}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         als.als_epoch(ctx, Y, Yt, W, H, prm)
-        for k, v in als.als_get_timing(ctx).items():
-            stage_ms[k] = stage_ms.get(k, 0.0) + v
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    # a second, untimed pass collects the per-kernel times (reading them waits for the events of every launch)
+    for i in range(args.steps):
+        als.als_epoch(ctx, Y, Yt, W, H, prm)
+        tm = als.als_get_timing(ctx)
+        for k, v in tm.items():
+            if k != "launches":
+                stage_ms[k] = stage_ms.get(k, 0.0) + v
+                stage_launches[k] = stage_launches.get(k, 0.0) + tm["launches"][k]
+    torch.cuda.synchronize()
     als.als_set_timing(ctx, False)
     als.als_status_sync(ctx)
     ms_per_step = 1e3 * elapsed / max(args.steps, 1)
     loss = als.als_loss(ctx, Y, W, H, prm)
-    log(f"{args.steps} epochs in {elapsed:.3f} s; stage ms (sum over steps): "
-        + ", ".join(f"{k}={v:.2f}" for k, v in stage_ms.items()) + f"; loss {loss:.6g}")
+    log(f"{args.steps} epochs in {elapsed:.3f} s; kernel ms per epoch: "
+        + ", ".join(f"{k}={v / max(args.steps, 1):.2f}" for k, v in stage_ms.items() if v > 0) + f"; loss {loss:.6g}")
 
-    # ---- roofline of the dominant kernel (largest share of the timed region) ----------------------
-    # Algorithmic work, per launch, of the kernels that can dominate:
-    #   dual row kernel of class c (rows with 16c < k <= 16(c+1)):  HBM-bound,
-    #       bytes = nnz_c*(4*d + 4) [gathered fp32 rows of Z + column ids]
-    #             + rows_c*(4*d + 8 + 4) [r store, indptr, list entry]
-    #   primal fused kernel (rows beyond the dual range):  fp32-MFMA-bound,
-    #       flops = 2*nnz_p*d^2 + rows_p*(d^3/3 + 2*d^2)
-    #   table transform (Z = V L^-T and X = R L^-1):  HBM-bound, bytes = rows*d*(s_in + s_out)
-    #   Gramian: fp32-MFMA-bound, flops = 2*rows*d^2
-    # Counts are summed over the launches of the timed region and divided by the launch count.
+    # ---- roofline per kernel ------------------------------------------------------------------------
+    # Algorithmic work per epoch of each timed kernel (what the method itself must move or compute):
+    #   dual row kernel of a class:  HBM-bound,  nnz_c*(4*d + 4) [gathered fp32 rows of Z + column ids]
+    #                                           + rows_c*(4*d + 8 + 4) [r store, indptr, list entry] bytes
+    #   Z = V L^-T and X = R L^-1:   HBM-bound,  rows*d*(s_in + s_out) bytes
+    #   Gramian:                     fp32 tables: fp32-MFMA-bound, 2*rows*d^2 flop; bf16 tables: HBM-bound, rows*d*2 bytes
+    #   primal fused rows:           fp32-MFMA-bound, 2*nnz_p*d^2 + rows_p*(d^3/3 + 2*d^2) flop
+    #   long-row segments:           fp32-MFMA-bound, 2*nnz_l*d^2 flop
+    # achieved = work of the launches timed / their summed duration (HIP events on the launch stream).
     nsteps = max(args.steps, 1)
     deg = {"row": p.indptr[1:] - p.indptr[:-1], "col": p.t_indptr[1:] - p.t_indptr[:-1]}
     dual_max = 0 if args.path == "primal" else {16: 16, 32: 32, 64: 64, 128: 128}[d]
-    cls_rows, cls_nnz = [0] * 8, [0] * 8
-    prim_rows = prim_nnz = 0
+    bounds = [("dual_k4", 0, 4), ("dual_k8", 4, 8)] + [(f"dual_k{16 * (c + 1)}", max(16 * c, 8), 16 * (c + 1)) for c in range(8)]
+    kernel_names = {"dual_k4": f"dual_small_kernel<{d}, 4>", "dual_k8": f"dual_small_kernel<{d}, 8>",
+                    "dual_k16": f"dual_rows_kernel<{d}>", "dual_k32": f"dual_multi_kernel<{d}, 2>"}
+    for c in range(2, 8):
+        kernel_names[f"dual_k{16 * (c + 1)}"] = f"dual_wide_kernel<{d}, {c + 1}>"
+    kernel_names.update({"gramian": f"gramian_partial_kernel<{d}>", "transform_z": f"transform_kernel<{d}> (Z = V L^-T)",
+                         "transform_x": f"transform_kernel<{d}> (X = R L^-1)", "primal": f"primal_kernel<{d}> (fused)",
+                         "segment": f"primal_kernel<{d}> (segments)"})
+    work = {}
+    long_nnz = prim_rows = prim_nnz = 0
     for kdeg in deg.values():
-        for c in range(8):
-            msk = (kdeg > 16 * c) & (kdeg <= min(16 * (c + 1), dual_max))
-            cls_rows[c] += int(msk.sum())
-            cls_nnz[c] += int(kdeg[msk].sum())
+        for name, lo, hi in bounds:
+            msk = (kdeg > lo) & (kdeg <= min(hi, dual_max))
+            r_c, n_c = int(msk.sum()), int(kdeg[msk].sum())
+            w = work.setdefault(name, ["hbm", 0.0])
+            w[1] += n_c * (4 * d + 4) + r_c * (4 * d + 12)
         msk = (kdeg > dual_max) & (kdeg <= 512)
         prim_rows += int(msk.sum())
         prim_nnz += int(kdeg[msk].sum())
-    cand = {}
-    for c in range(8):
-        ms, launches = stage_ms.get(f"dual_k{16 * (c + 1)}", 0.0), stage_ms.get(f"launches_k{16 * (c + 1)}", 0.0)
-        if launches > 0:
-            kname = {0: f"dual_rows_kernel<{d}>", 1: f"dual_multi_kernel<{d}, 2>"}.get(c, f"dual_wide_kernel<{d}, {c + 1}>")
-            per_launch = nsteps * (cls_nnz[c] * (4 * d + 4) + cls_rows[c] * (4 * d + 12)) / launches
-            cand[kname] = (ms, launches, "hbm", per_launch)
-    if stage_ms.get("primal", 0) > 0:
-        fl = nsteps * (2.0 * prim_nnz * d * d + prim_rows * (d ** 3 / 3.0 + 2.0 * d * d)) / (2 * nsteps)
-        cand[f"primal_kernel<{d}>"] = (stage_ms["primal"], 2 * nsteps, "mfma", fl)
-    if stage_ms.get("transform", 0) > 0:
-        # per half: factor (negligible) + Z transform (rows*d*(es+4)) + X transform (rows*d*(4+es)), timed together
-        by = 0.5 * (m + n) * d * (es + 4) * 2
-        cand[f"transform_kernel<{d}> (both passes of a half-epoch)"] = (stage_ms["transform"], 2 * nsteps, "hbm", by)
-    if stage_ms.get("gramian", 0) > 0:
-        cand[f"gramian_partial_kernel<{d}>"] = (stage_ms["gramian"], 2 * nsteps, "mfma", 2.0 * 0.5 * (m + n) * d * d)
-    dom = max(cand, key=lambda kk: cand[kk][0])
-    dom_ms_total, dom_launches, bound, work = cand[dom]
-    dom_ms = dom_ms_total / dom_launches
-    if bound == "hbm":
-        ach = work / (dom_ms * 1e-3) / 1e9
-        roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": ach / HBM_PEAK_GBS, "traffic": None}
-    else:
-        ach = work / (dom_ms * 1e-3) / 1e12
-        roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / MFMA_F32_PEAK_TFLOPS, "traffic": None}
-    if not args.rows:
-        roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((args.workload, dom))
-    roof["avg_launch_ms"] = dom_ms
-    roof["launches"] = dom_launches
-    roof["share_of_epoch"] = dom_ms_total / nsteps / ms_per_step
+        long_nnz += int(kdeg[kdeg > 512].sum())
+    work["primal"] = ["mfma", 2.0 * prim_nnz * d * d + prim_rows * (d ** 3 / 3.0 + 2.0 * d * d)]
+    work["segment"] = ["mfma", 2.0 * long_nnz * d * d]
+    work["transform_z"] = ["hbm", float(m + n) * d * (es + 4)]
+    work["transform_x"] = ["hbm", float(m + n) * d * (4 + es)]
+    work["gramian"] = ["mfma", 2.0 * (m + n) * d * d] if es == 4 else ["hbm", float(m + n) * d * es]
+    stages = {}
+    for name, (bound, per_epoch) in work.items():
+        ms = stage_ms.get(name, 0.0) / nsteps
+        if ms <= 0 or per_epoch <= 0:
+            continue
+        if bound == "hbm":
+            ach, peak, unit = per_epoch / (ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
+        else:
+            ach, peak, unit = per_epoch / (ms * 1e-3) / 1e12, MFMA_F32_PEAK_TFLOPS, "TFLOP/s"
+        launches = stage_launches.get(name, 0.0) / nsteps
+        stages[name] = {"kernel": kernel_names.get(name, name), "ms_per_epoch": round(ms, 4), "launches_per_epoch": launches,
+                        "bound": bound, "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
+                        "algorithmic_per_epoch": per_epoch}
+    dom = max(stages, key=lambda kk: stages[kk]["ms_per_epoch"])
+    sd = stages[dom]
+    per_launch = sd["algorithmic_per_epoch"] / max(sd["launches_per_epoch"], 1.0)
+    roof = {"kernel": sd["kernel"], "bound": sd["bound"], "achieved": sd["achieved"], "peak": sd["peak"], "unit": sd["unit"],
+            "frac": sd["frac"], "traffic": None if args.rows else measured_traffic(args.workload, sd["kernel"]),
+            "avg_launch_ms": sd["ms_per_epoch"] / max(sd["launches_per_epoch"], 1.0), "launches": sd["launches_per_epoch"] * nsteps,
+            "algorithmic_per_launch": per_launch,
+            "share_of_epoch": sd["ms_per_epoch"] / ms_per_step}
     # whole-epoch figure against the HBM floor of the method itself (gather + ids + both tables once)
     epoch_bytes = 2 * nnz * (d * es + 4) + 2 * (m + n) * d * es + 8 * (m + n + 2)
     roof["epoch_algorithmic_GBps"] = epoch_bytes / (ms_per_step * 1e-3) / 1e9
@@ -222,9 +242,9 @@ def main():
                                f"alpha={p.alpha}, lambda={p.lam}, 1 epoch = 2 half-epochs + 2 Gramians",
                    "path": args.path, "row_deg_mean": stats["row_deg_mean"], "col_deg_max": stats["col_deg_max"]},
         "epoch_ms": ms_per_step, "rows_per_sec": (m + n) / (ms_per_step * 1e-3),
-        "stage_ms_per_epoch": {k: round(v / max(args.steps, 1), 4) for k, v in stage_ms.items() if v > 0},
         "loss_after": loss,
         "roofline": roof,
+        "kernels": stages,
     }
     if args.rows:
         out["config"]["note"] = "node count overridden: not the named workload"

@@ -125,9 +125,11 @@ const char *als_static_last_error(void);
  * have Y->rows rows, the same d and dtype as V, and must not overlap V.  All
  * arithmetic is fp32 (fp64 for the one shared d x d factorisation); the result
  * is rounded once (to nearest even) to X's dtype.  Rows outside the range are
- * left untouched.  Enqueues on `stream`; synchronises that stream once, after
- * classifying the rows, to size the long-row workspace.  A non-positive pivot
- * sets a device flag reported as ALS_ENOTSPD by the next als_loss/als_status_sync. */
+ * left untouched.  Asynchronous on `stream`: nothing waits for the GPU and nothing
+ * is copied back (the first call with a larger problem than any before grows the
+ * workspace, which allocates).  A non-positive pivot sets a device flag reported as
+ * ALS_ENOTSPD by the next als_loss/als_status_sync; an indptr that does not fit nnz
+ * is reported there as ALS_EINVAL. */
 als_status als_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
                           const als_params *params, als_table *X, int64_t row_begin,
                           int64_t row_end, void *stream);
@@ -159,17 +161,16 @@ als_status als_check_csr(als_ctx *ctx, const als_csr *Y, void *stream);
  * this kernel give the scale factor applied to the counters of the other kernels. */
 als_status als_copy_probe(als_ctx *ctx, const void *src, void *dst, int64_t bytes, void *stream);
 
-/* Accumulated GPU time in milliseconds (HIP events on the call's stream) of the kernels launched by
- * the most recent als_gramian / als_solve_rows / als_epoch / als_loss, by stage:
- *   [0] Gramian   [1] row classification   [2] shared factorisation + table transforms of the dual form
- *   [3] all dual row kernels   [4] primal fused row kernel   [5] long-row segment accumulation
- *   [6] long-row reduce + solve   [7] number of dual row-kernel launches
- *   [8..15] dual row kernel of class c = 0..7 (rows with 16c < k <= 16(c+1) stored entries)
- *   [16..23] launches of that class's kernel
- * Timing is recorded only while enabled with als_set_timing(ctx, 1); reading waits for the recorded
- * events. */
+/* Diagnostics, not part of the method.  GPU time in milliseconds (HIP events on the call's stream) of the
+ * kernels launched by the most recent als_gramian / als_solve_rows / als_epoch / als_loss, per kernel:
+ *   [0] Gramian (3 kernels)   [1] row classification (5 kernels)   [2] shared factorisation + Z = V L^-T
+ *   [3] X = R L^-1   [4] primal fused row kernel   [5] long-row segment accumulation   [6] long-row reduce + solve
+ *   [7] dual rows k <= 4   [8] dual rows 5 <= k <= 8   [9 + c] dual rows 16c < k <= 16(c+1), c = 0..7 (c = 0: 8 < k)
+ * followed by the number of timed launches of each slot in [ALS_TIMING_SLOTS + slot].  Timing is recorded only
+ * while enabled with als_set_timing(ctx, 1); reading waits for the recorded events. */
+#define ALS_TIMING_SLOTS 17
 als_status als_set_timing(als_ctx *ctx, int enabled);
-als_status als_get_timing(als_ctx *ctx, double *ms_host /* [24] */);
+als_status als_get_timing(als_ctx *ctx, double *ms_host /* [2 * ALS_TIMING_SLOTS] */);
 
 const char *als_strerror(als_status status);
 const char *als_last_error(const als_ctx *ctx);

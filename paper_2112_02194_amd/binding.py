@@ -226,11 +226,15 @@ def als_set_timing(ctx: Context, enabled: bool) -> None:
     ctx._check(ctx.lib.als_set_timing(ctx.handle, int(enabled)))
 
 
-TIMING_SLOTS = (["gramian", "classify", "transform", "dual", "primal", "segment", "reduce", "dual_launches"]
-                + [f"dual_k{16 * (c + 1)}" for c in range(8)] + [f"launches_k{16 * (c + 1)}" for c in range(8)])
+TIMING_SLOTS = (["gramian", "classify", "transform_z", "transform_x", "primal", "segment", "reduce", "dual_k4", "dual_k8"]
+                + [f"dual_k{16 * (c + 1)}" for c in range(8)])
 
 
 def als_get_timing(ctx: Context) -> dict:
-    buf = (ctypes.c_double * 24)()
+    """ms per kernel slot, and under "launches" the number of timed launches of each slot."""
+    n = len(TIMING_SLOTS)
+    buf = (ctypes.c_double * (2 * n))()
     ctx._check(ctx.lib.als_get_timing(ctx.handle, buf))
-    return dict(zip(TIMING_SLOTS, list(buf)))
+    out = dict(zip(TIMING_SLOTS, list(buf)[:n]))
+    out["launches"] = dict(zip(TIMING_SLOTS, list(buf)[n:]))
+    return out

@@ -54,18 +54,6 @@ void timer_end(als_ctx *ctx, hipStream_t s) {
     (void)hipEventRecord(ctx->timers.back().e1, s);
 }
 
-als_status side_fork(als_ctx *ctx, hipStream_t s) {
-    ALS_HIP(ctx, hipEventRecord(ctx->fork_ev, s));
-    for (int i = 0; i < 3; ++i) ALS_HIP(ctx, hipStreamWaitEvent(ctx->side[i], ctx->fork_ev, 0));
-    return ALS_OK;
-}
-
-als_status side_join(als_ctx *ctx, int i, hipStream_t s) {
-    ALS_HIP(ctx, hipEventRecord(ctx->join_ev[i], ctx->side[i]));
-    ALS_HIP(ctx, hipStreamWaitEvent(s, ctx->join_ev[i], 0));
-    return ALS_OK;
-}
-
 static void timers_reset(als_ctx *ctx) {
     for (auto &t : ctx->timers) ctx->free_timers.push_back(t);
     ctx->timers.clear();
@@ -162,14 +150,15 @@ als_status als_create(als_ctx **out, int device) {
     if (st == ALS_OK && hipHostMalloc((void **)&ctx->host_counters, 16 * sizeof(int32_t)) != hipSuccess) st = ALS_ENOMEM;
     if (st == ALS_OK && hipHostMalloc((void **)&ctx->host_scalar, 2 * sizeof(double)) != hipSuccess) st = ALS_ENOMEM;
     if (st == ALS_OK && hipMemset(ctx->small.p, 0, ctx->small.bytes) != hipSuccess) st = ALS_EHIP;
-    for (int i = 0; i < 3 && st == ALS_OK; ++i) {
-        if (hipStreamCreateWithFlags(&ctx->side[i], hipStreamNonBlocking) != hipSuccess ||
-            hipEventCreateWithFlags(&ctx->join_ev[i], hipEventDisableTiming) != hipSuccess)
-            st = ALS_EHIP;
-    }
-    if (st == ALS_OK && hipEventCreateWithFlags(&ctx->fork_ev, hipEventDisableTiming) != hipSuccess) st = ALS_EHIP;
-    // opt-in: measured no gain on MI355X (the row kernels are instruction-issue bound, not latency bound)
-    if (const char *e = getenv("ALS_SIDE_STREAMS")) ctx->use_side_streams = atoi(e) != 0;
+    if (st == ALS_OK && hipHostMalloc((void **)&ctx->hint_counts, N_HINTS * HINT_INTS * sizeof(int32_t),
+                                      hipHostMallocMapped) != hipSuccess)
+        st = ALS_ENOMEM;
+    if (st == ALS_OK) memset(ctx->hint_counts, 0, N_HINTS * HINT_INTS * sizeof(int32_t));
+    if (st == ALS_OK && hipHostGetDevicePointer((void **)&ctx->hint_counts_dev, ctx->hint_counts, 0) != hipSuccess)
+        st = ALS_EHIP;
+    hipDeviceProp_t prop;
+    if (st == ALS_OK && hipGetDeviceProperties(&prop, device) == hipSuccess && prop.multiProcessorCount > 0)
+        ctx->num_cu = prop.multiProcessorCount;
     if (st != ALS_OK) {
         als_destroy(ctx);
         return st;
@@ -186,11 +175,7 @@ als_status als_destroy(als_ctx *ctx) {
                       &ctx->loss_partials, &ctx->gram_w, &ctx->gram_h};
     for (DevBuf *b : bufs)
         if (b->p) (void)hipFree(b->p);
-    for (int i = 0; i < 3; ++i) {
-        if (ctx->side[i]) (void)hipStreamDestroy(ctx->side[i]);
-        if (ctx->join_ev[i]) (void)hipEventDestroy(ctx->join_ev[i]);
-    }
-    if (ctx->fork_ev) (void)hipEventDestroy(ctx->fork_ev);
+    if (ctx->hint_counts) (void)hipHostFree(ctx->hint_counts);
     if (ctx->host_counters) (void)hipHostFree(ctx->host_counters);
     if (ctx->host_scalar) (void)hipHostFree(ctx->host_scalar);
     for (auto &t : ctx->timers) { (void)hipEventDestroy(t.e0); (void)hipEventDestroy(t.e1); }
@@ -266,6 +251,8 @@ als_status als_status_sync(als_ctx *ctx, void *stream) {
     ALS_HIP(ctx, hipStreamSynchronize(s));
     if (ctx->host_counters[2] != 0) {
         ALS_HIP(ctx, hipMemsetAsync(flag, 0, sizeof(int32_t), s));
+        if (ctx->host_counters[2] & 2)
+            return fail(ctx, ALS_EINVAL, "CSR structure inconsistent with its nnz: rows were dropped (run als_check_csr)");
         return fail(ctx, ALS_ENOTSPD, "a non-positive pivot was met while factorising a row system");
     }
     return ALS_OK;
@@ -331,13 +318,9 @@ als_status als_get_timing(als_ctx *ctx, double *ms_host) {
         float ms = 0.f;
         ALS_HIP(ctx, hipEventElapsedTime(&ms, t.e0, t.e1));
         ctx->timing_ms[t.slot] += ms;
-        if (t.slot >= T_DUAL_CLASS0 && t.slot < T_DUAL_CLASS0 + 8) {
-            ctx->timing_ms[T_DUAL] += ms;
-            ctx->timing_ms[T_LAUNCHES] += 1.0;
-            ctx->timing_ms[t.slot + 8] += 1.0;
-        }
+        ctx->timing_ms[T_COUNT + t.slot] += 1.0;
     }
-    for (int i = 0; i < T_COUNT; ++i) ms_host[i] = ctx->timing_ms[i];
+    for (int i = 0; i < 2 * T_COUNT; ++i) ms_host[i] = ctx->timing_ms[i];
     return ALS_OK;
 }
 

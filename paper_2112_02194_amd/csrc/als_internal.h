@@ -119,12 +119,23 @@ struct DevBuf {
     size_t bytes = 0;
 };
 
-enum TimingSlot { T_GRAMIAN = 0, T_CLASSIFY, T_TRANSFORM, T_DUAL, T_PRIMAL, T_SEGMENT, T_REDUCE, T_LAUNCHES,
-                  T_DUAL_CLASS0 = 8, T_COUNT = 24 };  // [8..15] ms per dual class, [16..23] launches per class
+// One slot per kernel (or pair of kernels timed together); T_DUAL_CLASS0 + c: dual row kernel of the class
+// 16c < k <= 16(c+1) (c = 0: 8 < k <= 16).
+enum TimingSlot { T_GRAMIAN = 0, T_CLASSIFY, T_TRANSFORM, T_TRANSFORM_X, T_PRIMAL, T_SEGMENT, T_REDUCE, T_SMALL4,
+                  T_SMALL8, T_DUAL_CLASS0 = 9, T_COUNT = ALS_TIMING_SLOTS };
 
 struct Timer {
     hipEvent_t e0 = nullptr, e1 = nullptr;
     int slot = 0;
+};
+
+constexpr int N_HINTS = 8, HINT_INTS = 32;  // per slot: [0..15] the counters, [16] the sequence number (written last)
+struct HintSlot {
+    const void *indptr = nullptr;  // key: the matrix (by address and size), the row range and what shapes the classes
+    int64_t rows = 0, nnz = 0, r0 = 0, r1 = 0;
+    int32_t split = 0, dual_max = 0, d = 0;
+    uint32_t seq = 0;              // sequence number of the call that last enqueued a write of this slot; 0 = unused
+    uint32_t first_seq = 0;        // sequence number of the first call with this key: counts stamped >= it belong to the key
 };
 
 }  // namespace als
@@ -142,20 +153,26 @@ struct als_ctx {
     als::DevBuf gram_w, gram_h; // fp32 [d*d] Gramians used by als_epoch / als_loss
     int32_t *host_counters = nullptr;  // pinned, 16 ints
     double *host_scalar = nullptr;     // pinned, 2 doubles
-    // side streams (default priority) on which kernels of independent row classes run concurrently
-    hipStream_t side[3] = {nullptr, nullptr, nullptr};
-    hipEvent_t fork_ev = nullptr, join_ev[3] = {nullptr, nullptr, nullptr};
-    bool use_side_streams = false;
+    int num_cu = 256;                  // compute units of the device (sizes the default grids)
+    // Launch-size hints.  als_solve_rows never waits for the row-class counts: its kernels read them
+    // from device memory and walk their lists with grid-stride loops, so any grid is correct.  The counts
+    // of a call are also stored (by the GPU, into host-visible memory) in one of these slots, and the next
+    // call on the same matrix and range sizes its grids from them, so that every workgroup gets one item.
+    als::HintSlot hints[als::N_HINTS];
+    int32_t *hint_counts = nullptr;    // pinned, device-visible: [N_HINTS][HINT_INTS], written by the GPU
+    int32_t *hint_counts_dev = nullptr;  // the same memory as the device addresses it
+    uint32_t hint_seq = 0;
     bool timing = false;
     std::vector<als::Timer> timers;
     std::vector<als::Timer> free_timers;
-    double timing_ms[als::T_COUNT] = {0};
+    double timing_ms[2 * als::T_COUNT] = {0};  // ms per slot, then launches per slot
 };
 
 namespace als {
 
 // Layout of ctx->small (byte offsets).
-constexpr size_t SM_COUNTERS = 0;       // int32[16]: [0] n_long [1] n_seg [2] error flag [3] n_mid [4] csr check [5] k<=4 [6] 5<=k<=8 [8..15] dual classes
+constexpr size_t SM_COUNTERS = 0;       // int32[16]: [0] n_long [1] n_seg [2] error flag [3] n_mid [4] csr check [5] k<=4 [6] 5<=k<=8 [7] split in use [8..15] dual classes
+constexpr size_t SM_LONGSTAT = 128;     // int64[2]: entries and rows beyond the requested split (sizes the segments)
 constexpr size_t SM_LOSS = 64;          // double[2]
 constexpr size_t SM_FACTOR = 256;       // fp32 [2][128*128]: L^{-1} and scratch for the dual form
 constexpr size_t SM_BYTES = SM_FACTOR + 2 * 128 * 128 * sizeof(float) + 128 * 128 * sizeof(double);
@@ -172,9 +189,15 @@ als_status fail(als_ctx *ctx, als_status st, const std::string &msg);
 als_status ensure(als_ctx *ctx, DevBuf &b, size_t bytes);
 void timer_begin(als_ctx *ctx, int slot, hipStream_t s);
 void timer_end(als_ctx *ctx, hipStream_t s);
-// Make side stream i wait for everything enqueued on `s` so far / make `s` wait for side stream i.
-als_status side_fork(als_ctx *ctx, hipStream_t s);
-als_status side_join(als_ctx *ctx, int i, hipStream_t s);
+// How a list of `capacity` steps at most is launched when its length is only known on the device.  The
+// row kernels come in two forms: one step per workgroup (launched with `known` workgroups, the length the
+// previous call on the same matrix saw; steps beyond the true length return at once), and a grid-stride walk
+// over everything from step `known` on (launched with `rest` workgroups; finds nothing to do when the hint
+// was right).  Together they cover the list whatever the hint was.
+struct StepGrid {
+    unsigned known, rest;
+};
+StepGrid step_grid(const als_ctx *ctx, int64_t capacity, int64_t hint, int per_cu);
 
 #define ALS_HIP(ctx, expr)                                                                      \
     do {                                                                                        \

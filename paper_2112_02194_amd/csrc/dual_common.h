@@ -14,6 +14,20 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Makes a wavefront-uniform value opaque to the optimiser.  The grid-stride forms of the row kernels pass their
+// arguments through this at the top of every iteration: with nothing loop-invariant left in sight, the
+// compiler cannot hoist the step's address arithmetic out of the loop, which otherwise costs the step about
+// twice its registers (and scratch memory for the larger steps).
+template <class T> __device__ __forceinline__ T opaque(T v) {
+    asm volatile("" : "+s"(v));
+    return v;
+}
+__device__ __forceinline__ int opaque_tid() {
+    int lane = threadIdx.x;
+    asm volatile("" : "+v"(lane));
+    return lane;
+}
+
 // Four consecutive entries of a row list, read with one load.  The lists start at arbitrary 4-byte offsets of
 // the workspace (which is padded so that reading up to three entries past a list's end stays inside it).
 struct __attribute__((packed, aligned(4))) ListQuad { int32_t x, y, z, w; };
@@ -36,6 +50,22 @@ template <int GW, int C> __device__ __forceinline__ float group_bcast(float x) {
         return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), C));
     }
 }
+
+// ---------------------------------------------------------------------------------------------- fused broadcasts
+// acc += (src as held by lane C of this lane's row of 16 lanes) * mul in ONE vector instruction: the row
+// broadcast is a DPP modifier of the multiply-add (the compiler emits a separate broadcast move and a
+// three-operand multiply-add instead).  The hardware needs two idle issue slots between a vector
+// instruction that writes a register and a DPP read of it, and does not interlock: dpp_settle() must be
+// applied to every register that one of these instructions (or a plain vector instruction right before)
+// has written and that is read through DPP next; the dependence it creates also keeps the compiler from
+// moving such a read in front of it.
+template <int C> __device__ __forceinline__ void fmac_bcast16(float &acc, float src, float mul) {
+    asm volatile("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+                 : "+v"(acc)
+                 : "v"(src), "v"(mul), "n"(C));
+}
+__device__ __forceinline__ void dpp_settle(float &a) { asm volatile("s_nop 1" : "+v"(a)); }
+__device__ __forceinline__ void dpp_settle(float &a, float &b) { asm volatile("s_nop 1" : "+v"(a), "+v"(b)); }
 
 // ---------------------------------------------------------------------------------------------- split products
 // S = I + Z_I Z_I^T on the bf16 matrix cores at fp32-like accuracy: every fp32 entry z is cut into
@@ -76,7 +106,8 @@ __device__ __forceinline__ floatx4 split_mfma(const SplitOperand &a, const Split
 }
 
 // per-class launchers, one translation unit each (they compile in parallel)
+// (`count_dev`: device address of the list's length; `g`: see StepGrid)
 void launch_dual_k16(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                     int count, int32_t *err, hipStream_t s);
+                     const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s);
 
 }  // namespace als

@@ -26,24 +26,24 @@ template <int D, int M> struct MultiCfg {
     static constexpr int LDS_FLOATS = OFF_DUMP + 64;  // one dump slot per lane for stores that must not land
 };
 
+// One step: the four rows list[4 blk .. 4 blk + 3] (blk * 4 < count).
 template <int D, int M>
-__global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restrict__ indptr,
-                                                        const int32_t *__restrict__ indices,
-                                                        const float *__restrict__ values,
-                                                        const float *__restrict__ Z, float *__restrict__ R,
-                                                        int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
-                                                        int count, int32_t *__restrict__ err_flag) {
+__device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indptr,
+                                                const int32_t *__restrict__ indices,
+                                                const float *__restrict__ values, const float *__restrict__ Z,
+                                                float *__restrict__ R, int64_t ldr, int64_t r0,
+                                                const int32_t *__restrict__ list, int count,
+                                                int32_t *__restrict__ err_flag, int blk, float *lds) {
     using C = MultiCfg<D, M>;
     constexpr int K = C::K, TRI = C::TRI, NJ = D / 16, CPL = D >= 128 ? 2 : 1;
-    extern __shared__ float lds[];
     float *tri = lds, *tbuf = lds + C::OFF_T;
     int32_t *ids = (int32_t *)(lds + C::OFF_ID);
     // Accesses to the packed triangle are never put under a lane-dependent branch (a branch per element costs
     // more than the access): reads go to an in-range address and are selected afterwards, stores of entries
     // that do not exist go to the lane's dump slot.
-    float *dump = lds + C::OFF_DUMP + threadIdx.x;
-    const int lane = threadIdx.x, a = lane & 15, q = lane >> 4;  // MFMA view: entry a of a tile, column group q
-    const int g = lane >> 4, i = lane & 15;                       // solver view: system g, lane i of its group
+    const int lane = opaque_tid(), a = lane & 15, q = lane >> 4;  // MFMA view: entry a of a tile, column group q
+    float *dump = lds + C::OFF_DUMP + lane;
+    const int g = lane >> 4, i = lane & 15;                         // solver view: system g, lane i of its group
 
     // Row descriptors of all four rows first (one 16-byte read of the list entries - the list's workspace is
     // padded for it; past the end of the list the first entry stands in - then the four indptr pairs
@@ -51,8 +51,8 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
     int64_t u[4], b[4], b1[4];
     int k[4], kmax = 0, rel[4];
     {
-        const ListQuad r4 = *(const ListQuad *)(list + (int64_t)blockIdx.x * 4);
-        const int first = blockIdx.x * 4;
+        const ListQuad r4 = *(const ListQuad *)(list + (int64_t)blk * 4);
+        const int first = blk * 4;
         rel[0] = r4.x;
         rel[1] = first + 1 < count ? r4.y : r4.x;
         rel[2] = first + 2 < count ? r4.z : r4.x;
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
     }
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-        const bool have = blockIdx.x * 4 + p < count;
+        const bool have = blk * 4 + p < count;
         u[p] = have ? r0 + rel[p] : -1;
         k[p] = have ? (int)(b1[p] - b[p]) : 0;
         kmax = k[p] > kmax ? k[p] : kmax;
@@ -157,6 +157,7 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
         rpm[bk] = 1.f;
     }
     bool bad = false;
+    dpp_settle(s[0][0], s[1][0]);
     static_for<0, K>([&](auto cc) {
         constexpr int c = decltype(cc)::value;
         constexpr int cb = c / 16, ci = c % 16;
@@ -166,23 +167,28 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
             bad |= !(pivot > 0.f);
             float rp = __builtin_amdgcn_rcpf(pivot);
             rp = rp * (2.f - pivot * rp);  // one Newton step on the hardware reciprocal
-            float f[M];
+            float nf[M];  // -M[Rr][c]
             static_for<cb, M>([&](auto bb) {
                 constexpr int bk = decltype(bb)::value;
                 const int Rr = 16 * bk + i;
                 rpm[bk] = Rr == c ? rp : rpm[bk];
-                f[bk] = Rr > c ? s[bk][c] * rp : 0.f;  // M[Rr][c]; rows above stay as they are
-                y[bk] -= f[bk] * uc;
+                nf[bk] = Rr > c ? -(s[bk][c] * rp) : 0.f;  // rows above stay as they are
+                y[bk] += nf[bk] * uc;
             });
+            // S'[Rr][j] -= M[Rr][c] S'[j][c]: the broadcast of S'[j][c] from the lane that owns row j rides on
+            // the multiply-add (column c is final since the previous step and has settled)
             static_for<c + 1, K>([&](auto jj) {
                 constexpr int j = decltype(jj)::value;
                 constexpr int jb = j / 16, ji = j % 16;
-                const float cj = bcast16<ji>(s[jb][c]);  // S'[j][c]
                 static_for<jb, M>([&](auto bb) {
                     constexpr int bk = decltype(bb)::value;
-                    s[bk][j] -= f[bk] * cj;
+                    fmac_bcast16<ji>(s[bk][j], s[jb][c], nf[bk]);
                 });
             });
+            if constexpr (c + 1 < K) {  // the next step reads column c + 1 through DPP
+                if constexpr ((c + 1) / 16 == 0) dpp_settle(s[0][c + 1], s[1][c + 1]);
+                else dpp_settle(s[M - 1][c + 1]);
+            }
         }
     });
     if (bad && myk > 0) atomicOr(err_flag, 1);
@@ -289,20 +295,51 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
     }
 }
 
+// LOOP = false: workgroup b takes step first_blk + b, if the list is that long (the launch for a list whose
+// length the host knows from the previous call).  LOOP = true: grid-stride walk from first_blk to the end of
+// the list, correct for any grid size (the length is only known on the device); the step inlined into a
+// loop needs about twice the registers, so this form only serves what the first form did not cover.
+template <int D, int M, bool LOOP>
+__global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restrict__ indptr,
+                                                        const int32_t *__restrict__ indices,
+                                                        const float *__restrict__ values,
+                                                        const float *__restrict__ Z, float *__restrict__ R,
+                                                        int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
+                                                        const int32_t *__restrict__ count_ptr, int first_blk,
+                                                        int32_t *__restrict__ err_flag) {
+    extern __shared__ float lds[];
+    const int count = *count_ptr;
+    int blk = first_blk + blockIdx.x;
+    if constexpr (!LOOP) {
+        if (blk * 4 < count) dual_multi_step<D, M>(indptr, indices, values, Z, R, ldr, r0, list, count, err_flag, blk, lds);
+    } else {
+        for (; blk * 4 < count; blk += gridDim.x) {
+            dual_multi_step<D, M>(opaque(indptr), opaque(indices), opaque(values), opaque(Z), opaque(R), opaque(ldr),
+                                  opaque(r0), opaque(list), opaque(count), opaque(err_flag), blk, opaque(lds));
+            wave_sync();  // the next step reuses the LDS buffers
+        }
+    }
+}
+
 template <int D>
 static void launch_multi_typed(const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0,
-                               const int32_t *list, int count, int32_t *err, hipStream_t s) {
+                               const int32_t *list, const int32_t *count_dev, StepGrid g, int32_t *err,
+                               hipStream_t s) {
     using C = MultiCfg<D, MULTI_M>;
-    hipLaunchKernelGGL((dual_multi_kernel<D, MULTI_M>), dim3((unsigned)((count + 3) / 4)), dim3(64),
-                       C::LDS_FLOATS * sizeof(float), s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count, err);
+    if (g.known > 0)
+        hipLaunchKernelGGL((dual_multi_kernel<D, MULTI_M, false>), dim3(g.known), dim3(64), C::LDS_FLOATS * sizeof(float),
+                           s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count_dev, 0, err);
+    if (g.rest > 0)
+        hipLaunchKernelGGL((dual_multi_kernel<D, MULTI_M, true>), dim3(g.rest), dim3(64), C::LDS_FLOATS * sizeof(float),
+                           s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count_dev, (int)g.known, err);
 }
 
 void launch_dual_multi2(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                        int count, int32_t *err, hipStream_t s) {
+                        const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
     switch (d) {  // the dual form stops at k = d
-        case 32: launch_multi_typed<32>(Y, Z, R, ldr, r0, list, count, err, s); break;
-        case 64: launch_multi_typed<64>(Y, Z, R, ldr, r0, list, count, err, s); break;
-        case 128: launch_multi_typed<128>(Y, Z, R, ldr, r0, list, count, err, s); break;
+        case 32: launch_multi_typed<32>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
+        case 64: launch_multi_typed<64>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
+        case 128: launch_multi_typed<128>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
     }
 }
 

@@ -24,14 +24,15 @@
 namespace als {
 
 void launch_dual_small4(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                        int count, int32_t *err, hipStream_t s);
+                        const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s);
 void launch_dual_small8(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                        int count, int32_t *err, hipStream_t s);
+                        const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s);
 void launch_dual_multi2(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                        int count, int32_t *err, hipStream_t s);
+                        const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s);
 #define ALS_DECL_WIDE(kt)                                                                                         \
     als_status launch_dual_wide##kt(als_ctx *ctx, int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, \
-                                    int64_t r0, const int32_t *list, int count, int32_t *err, hipStream_t s);
+                                    int64_t r0, const int32_t *list, const int32_t *count_dev, StepGrid g,        \
+                                    int32_t *err, hipStream_t s);
 ALS_DECL_WIDE(3) ALS_DECL_WIDE(4) ALS_DECL_WIDE(5) ALS_DECL_WIDE(6) ALS_DECL_WIDE(7) ALS_DECL_WIDE(8)
 #undef ALS_DECL_WIDE
 
@@ -105,8 +106,7 @@ template <int D> struct XfCfg {
 };
 
 template <int D, bool IN_BF16, bool OUT_BF16, bool UPPER>
-__global__ __launch_bounds__(256) void transform_kernel(const void *__restrict__ In, int64_t ldi,
-                                                        void *__restrict__ Out, int64_t ldo,
+__global__ __launch_bounds__(256) void transform_kernel(const void *In, int64_t ldi, void *Out, int64_t ldo,
                                                         const float *__restrict__ M, int64_t r0, int64_t r1,
                                                         const int64_t *__restrict__ indptr, int64_t k_max) {
     using C = XfCfg<D>;
@@ -185,14 +185,17 @@ static als_status dual_prepare_typed(als_ctx *ctx, const als_table *V, const flo
     float *Linv = (float *)((char *)ctx->small.p + SM_FACTOR), *LinvT = Linv + 128 * 128;
     int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
     constexpr size_t factor_lds = (size_t)(D * (D + 1) + D) * sizeof(double);
-    ALS_HIP(ctx, hipFuncSetAttribute((const void *)factor_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)factor_lds));
+    static const hipError_t attr_f = hipFuncSetAttribute((const void *)factor_kernel<D>,
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)factor_lds);
+    static const hipError_t attr_t = hipFuncSetAttribute((const void *)transform_kernel<D, BF16, false, true>,
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                         (int)XfCfg<D>::LDS_BYTES);  // both once per process
+    ALS_HIP(ctx, attr_f);
+    ALS_HIP(ctx, attr_t);
     timer_begin(ctx, T_TRANSFORM, s);
     hipLaunchKernelGGL(factor_kernel<D>, dim3(1), dim3(256), factor_lds, s, G, prm->alpha, prm->lambda, Linv, LinvT,
                        err);
     const unsigned tblocks = (unsigned)std::min<int64_t>(1024, std::max<int64_t>(1, (V->rows + 127) / 128));
-    ALS_HIP(ctx, hipFuncSetAttribute((const void *)transform_kernel<D, BF16, false, true>,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)XfCfg<D>::LDS_BYTES));
     hipLaunchKernelGGL((transform_kernel<D, BF16, false, true>), dim3(tblocks), dim3(256), XfCfg<D>::LDS_BYTES, s, V->data, V->ld,
                        ctx->ztable.p, (int64_t)D, (const float *)LinvT, (int64_t)0, V->rows,
                        (const int64_t *)nullptr, (int64_t)0);
@@ -201,10 +204,13 @@ static als_status dual_prepare_typed(als_ctx *ctx, const als_table *V, const flo
     return ALS_OK;
 }
 
-// Part 2: the row kernels of the four k-classes, then X = R L^{-1} on the rows they solved.
+// Part 2: the row kernels of the k-classes, then X = R L^{-1} on the rows they solved.  Every class is
+// launched (its kernel finds the length of its list in device memory); `caps` bounds the lists, `hints` holds
+// the lengths seen by the previous call on the same matrix, or -1.
 template <int D, bool BF16>
 static als_status dual_rows_typed(als_ctx *ctx, const als_csr *Y, als_table *X, int64_t r0, int64_t r1,
-                                  int dual_max, const int32_t *const lists[10], const int counts[10], hipStream_t s) {
+                                  int dual_max, const int32_t *const lists[10], const int32_t *const counts_dev[10],
+                                  const int64_t caps[10], const int hints[10], hipStream_t s) {
     float *R = (float *)X->data;
     int64_t ldr = X->ld;
     if (BF16) {
@@ -216,45 +222,39 @@ static als_status dual_rows_typed(als_ctx *ctx, const als_csr *Y, als_table *X, 
     const float *Linv = (const float *)((char *)ctx->small.p + SM_FACTOR);
     int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
     const float *Z = (const float *)ctx->ztable.p;
-    // Independent classes run concurrently: the two largest on the caller's stream, 32 < k <= 64 on
-    // side stream 0, k > 64 on side stream 1.  The caller has forked the side
-    // streams; they are joined before the closing transform, which reads every class's result.
     als_status stb = ALS_OK;
-    const bool side = ctx->use_side_streams;
-    hipStream_t s_mid = side ? ctx->side[0] : s, s_big = side ? ctx->side[1] : s;
-#define ALS_TIMED_CLASS(cls, strm, call)            \
-    if (counts[cls] > 0 && stb == ALS_OK) {         \
-        hipStream_t cs = strm;                      \
-        timer_begin(ctx, T_DUAL_CLASS0 + cls, cs);  \
-        call;                                       \
-        timer_end(ctx, cs);                         \
+    // workgroups of class `cls` whose kernel takes `rpw` rows per step
+    auto grid = [&](int cls, int rpw) {
+        const int64_t cap = (caps[cls] + rpw - 1) / rpw;
+        const int64_t hint = hints[cls] < 0 ? -1 : ((int64_t)hints[cls] + rpw - 1) / rpw;
+        return step_grid(ctx, cap, hint, 32);
+    };
+#define ALS_TIMED_CLASS(slot, cls, rpw, call)           \
+    if (caps[cls] > 0 && stb == ALS_OK) {               \
+        const StepGrid g = grid(cls, rpw);              \
+        timer_begin(ctx, slot, s);                      \
+        call;                                           \
+        timer_end(ctx, s);                              \
     }
-    ALS_TIMED_CLASS(1, s, (launch_dual_multi2(D, Y, Z, R, ldr, r0, lists[1], counts[1], err, cs)))
-    ALS_TIMED_CLASS(0, s, (launch_dual_k16(D, Y, Z, R, ldr, r0, lists[0], counts[0], err, cs)))
-    if (counts[9] > 0) {  // 5 <= k <= 8 and k <= 4: several rows per MFMA tile; timed with class 0
-        timer_begin(ctx, T_DUAL_CLASS0, s);
-        launch_dual_small8(D, Y, Z, R, ldr, r0, lists[9], counts[9], err, s);
-        timer_end(ctx, s);
-    }
-    if (counts[8] > 0) {
-        timer_begin(ctx, T_DUAL_CLASS0, s);
-        launch_dual_small4(D, Y, Z, R, ldr, r0, lists[8], counts[8], err, s);
-        timer_end(ctx, s);
-    }
-    ALS_TIMED_CLASS(2, s_mid, (stb = launch_dual_wide3(ctx, D, Y, Z, R, ldr, r0, lists[2], counts[2], err, cs)))
-    ALS_TIMED_CLASS(3, s_mid, (stb = launch_dual_wide4(ctx, D, Y, Z, R, ldr, r0, lists[3], counts[3], err, cs)))
-    ALS_TIMED_CLASS(4, s_big, (stb = launch_dual_wide5(ctx, D, Y, Z, R, ldr, r0, lists[4], counts[4], err, cs)))
-    ALS_TIMED_CLASS(5, s_big, (stb = launch_dual_wide6(ctx, D, Y, Z, R, ldr, r0, lists[5], counts[5], err, cs)))
-    ALS_TIMED_CLASS(6, s_big, (stb = launch_dual_wide7(ctx, D, Y, Z, R, ldr, r0, lists[6], counts[6], err, cs)))
-    ALS_TIMED_CLASS(7, s_big, (stb = launch_dual_wide8(ctx, D, Y, Z, R, ldr, r0, lists[7], counts[7], err, cs)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 1, 1, 4, (launch_dual_multi2(D, Y, Z, R, ldr, r0, lists[1], counts_dev[1], g, err, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0, 0, 4, (launch_dual_k16(D, Y, Z, R, ldr, r0, lists[0], counts_dev[0], g, err, s)))
+    // 5 <= k <= 8 and k <= 4: several rows per MFMA tile
+    ALS_TIMED_CLASS(T_SMALL8, 9, 8, (launch_dual_small8(D, Y, Z, R, ldr, r0, lists[9], counts_dev[9], g, err, s)))
+    ALS_TIMED_CLASS(T_SMALL4, 8, 16, (launch_dual_small4(D, Y, Z, R, ldr, r0, lists[8], counts_dev[8], g, err, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 2, 2, 1, (stb = launch_dual_wide3(ctx, D, Y, Z, R, ldr, r0, lists[2], counts_dev[2], g, err, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 3, 3, 1, (stb = launch_dual_wide4(ctx, D, Y, Z, R, ldr, r0, lists[3], counts_dev[3], g, err, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 4, 4, 1, (stb = launch_dual_wide5(ctx, D, Y, Z, R, ldr, r0, lists[4], counts_dev[4], g, err, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 5, 5, 1, (stb = launch_dual_wide6(ctx, D, Y, Z, R, ldr, r0, lists[5], counts_dev[5], g, err, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 6, 6, 1, (stb = launch_dual_wide7(ctx, D, Y, Z, R, ldr, r0, lists[6], counts_dev[6], g, err, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 7, 7, 1, (stb = launch_dual_wide8(ctx, D, Y, Z, R, ldr, r0, lists[7], counts_dev[7], g, err, s)))
 #undef ALS_TIMED_CLASS
-    if (side && stb == ALS_OK) stb = side_join(ctx, 0, s);
-    if (side && stb == ALS_OK) stb = side_join(ctx, 1, s);
     if (stb != ALS_OK) return stb;
-    timer_begin(ctx, T_TRANSFORM, s);
+    static const hipError_t attr_x = hipFuncSetAttribute((const void *)transform_kernel<D, false, BF16, false>,
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                         (int)XfCfg<D>::LDS_BYTES);  // once per process
+    ALS_HIP(ctx, attr_x);
+    timer_begin(ctx, T_TRANSFORM_X, s);
     const unsigned xblocks = (unsigned)std::min<int64_t>(1024, std::max<int64_t>(1, (r1 - r0 + 127) / 128));
-    ALS_HIP(ctx, hipFuncSetAttribute((const void *)transform_kernel<D, false, BF16, false>,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)XfCfg<D>::LDS_BYTES));
     hipLaunchKernelGGL((transform_kernel<D, false, BF16, false>), dim3(xblocks), dim3(256), XfCfg<D>::LDS_BYTES, s, (const void *)R, ldr,
                        X->data, X->ld, Linv, r0, r1, Y->indptr, (int64_t)dual_max);
     timer_end(ctx, s);
@@ -275,13 +275,14 @@ als_status launch_dual_prepare(als_ctx *ctx, const als_table *V, const float *G,
 }
 
 als_status launch_dual_rows(als_ctx *ctx, const als_csr *Y, als_table *X, int64_t r0, int64_t r1, int dual_max,
-                            const int32_t *const lists[10], const int counts[10], hipStream_t s) {
+                            const int32_t *const lists[10], const int32_t *const counts[10], const int64_t caps[10],
+                            const int hints[10], hipStream_t s) {
     const bool bf = X->dtype == ALS_BF16;
     switch (X->d) {
-        case 16: return bf ? dual_rows_typed<16, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, s) : dual_rows_typed<16, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, s);
-        case 32: return bf ? dual_rows_typed<32, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, s) : dual_rows_typed<32, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, s);
-        case 64: return bf ? dual_rows_typed<64, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, s) : dual_rows_typed<64, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, s);
-        case 128: return bf ? dual_rows_typed<128, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, s) : dual_rows_typed<128, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, s);
+        case 16: return bf ? dual_rows_typed<16, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, caps, hints, s) : dual_rows_typed<16, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, caps, hints, s);
+        case 32: return bf ? dual_rows_typed<32, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, caps, hints, s) : dual_rows_typed<32, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, caps, hints, s);
+        case 64: return bf ? dual_rows_typed<64, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, caps, hints, s) : dual_rows_typed<64, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, caps, hints, s);
+        case 128: return bf ? dual_rows_typed<128, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, caps, hints, s) : dual_rows_typed<128, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, caps, hints, s);
     }
     return fail(ctx, ALS_EDTYPE, "unsupported d");
 }

@@ -27,17 +27,15 @@ template <int D> struct DualCfg {
 //      broadcast by DPP inside the group, then L w = y, then L^T t = w with L read back transposed;
 //   3. r = Z_I^T t with one lane per pair of output columns, from an LDS copy of Z_I.
 template <int D>
-__global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict__ indptr,
-                                                       const int32_t *__restrict__ indices,
-                                                       const float *__restrict__ values,
-                                                       const float *__restrict__ Z, float *__restrict__ R,
-                                                       int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
-                                                       int count, int32_t *__restrict__ err_flag) {
+__device__ __forceinline__ void dual_rows_step(const int64_t *__restrict__ indptr, const int32_t *__restrict__ indices,
+                                               const float *__restrict__ values, const float *__restrict__ Z,
+                                               float *__restrict__ R, int64_t ldr, int64_t r0,
+                                               const int32_t *__restrict__ list, int count,
+                                               int32_t *__restrict__ err_flag, int blk, float *lds) {
     using C = DualCfg<D>;
     constexpr int K = C::K, KT = 1, GW = C::GW, RPW = C::RPW, KP = C::KP, NJ = C::NJ, ZLD = C::ZLD;
-    extern __shared__ float lds[];
     float *sb = lds, *zb = lds, *tb = lds + (C::LDS_FLOATS - C::TAIL);
-    const int lane = threadIdx.x;
+    const int lane = opaque_tid();
     const int a = lane & 15, q = lane >> 4;
     const int grp = lane / GW, gi = lane % GW;
     const int myrow = gi;
@@ -50,8 +48,8 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
     {
         // one 16-byte read of the wavefront's four list entries; past the end of the list (its workspace is
         // padded for this) the first entry stands in
-        const ListQuad r4 = *(const ListQuad *)(list + (int64_t)blockIdx.x * RPW);
-        const int first = blockIdx.x * RPW;
+        const ListQuad r4 = *(const ListQuad *)(list + (int64_t)blk * RPW);
+        const int first = blk * RPW;
         rel[0] = r4.x;
         rel[1] = first + 1 < count ? r4.y : r4.x;
         rel[2] = first + 2 < count ? r4.z : r4.x;
@@ -65,7 +63,7 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
     }
 #pragma unroll
     for (int p = 0; p < RPW; ++p) {
-        const bool have = blockIdx.x * RPW + p < count;
+        const bool have = blk * RPW + p < count;
         u[p] = have ? r0 + rel[p] : -1;
         k[p] = have ? (int)(b1[p] - b[p]) : 0;
         kmax = k[p] > kmax ? k[p] : kmax;
@@ -155,13 +153,16 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
                 bad |= !(pivot > 0.f);
                 float rinv = __builtin_amdgcn_rsqf(pivot);
                 rinv = rinv * (1.5f - 0.5f * pivot * rinv * rinv);  // one Newton step on the hardware estimate
-                const float lc = s[c] * rinv;
+                float lc = s[c] * rinv;
+                float nlc = -lc;
+                dpp_settle(lc);  // just written, read through DPP below
                 s[c] = lc;
                 myrinv = myrow == c ? rinv : myrinv;
-                static_for<c + 1, K>([&](auto ii) {
+                static_for<c + 1, K>([&](auto ii) {  // s[i] -= L[row][c] L[i][c], broadcast fused into the multiply-add
                     constexpr int i = decltype(ii)::value;
-                    s[i] -= lc * group_bcast<GW, i>(lc);
+                    fmac_bcast16<i>(s[i], lc, nlc);
                 });
+                if constexpr (c + 1 < K) dpp_settle(s[c + 1]);  // the next step's pivot is read through DPP
             }
         });
         static_for<0, K>([&](auto cc) {  // L w = y
@@ -230,23 +231,49 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
     }
 }
 
+// The two launch forms of a step kernel (see StepGrid): one step per workgroup, or a grid-stride walk from
+// step first_blk to the end of the list.
+template <int D, bool LOOP>
+__global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict__ indptr,
+                                                       const int32_t *__restrict__ indices,
+                                                       const float *__restrict__ values,
+                                                       const float *__restrict__ Z, float *__restrict__ R,
+                                                       int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
+                                                       const int32_t *__restrict__ count_ptr, int first_blk,
+                                                       int32_t *__restrict__ err_flag) {
+    extern __shared__ float lds[];
+    const int count = *count_ptr;
+    int blk = first_blk + blockIdx.x;
+    if constexpr (!LOOP) {
+        if (blk * DualCfg<D>::RPW < count) dual_rows_step<D>(indptr, indices, values, Z, R, ldr, r0, list, count, err_flag, blk, lds);
+    } else {
+        for (; blk * DualCfg<D>::RPW < count; blk += gridDim.x) {
+            dual_rows_step<D>(opaque(indptr), opaque(indices), opaque(values), opaque(Z), opaque(R), opaque(ldr), opaque(r0),
+                              opaque(list), opaque(count), opaque(err_flag), blk, opaque(lds));
+            wave_sync();  // the next step reuses the LDS buffers
+        }
+    }
+}
+
 template <int D>
 static void launch_rows_typed(const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                              int count, int32_t *err, hipStream_t s) {
+                              const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
     using C = DualCfg<D>;
-    const unsigned blocks = (unsigned)((count + C::RPW - 1) / C::RPW);
-    hipLaunchKernelGGL((dual_rows_kernel<D>), dim3(blocks), dim3(64), C::LDS_FLOATS * sizeof(float), s, Y->indptr,
-                       Y->indices, Y->values, Z, R, ldr, r0, list, count, err);
+    if (g.known > 0)
+        hipLaunchKernelGGL((dual_rows_kernel<D, false>), dim3(g.known), dim3(64), C::LDS_FLOATS * sizeof(float), s,
+                           Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count_dev, 0, err);
+    if (g.rest > 0)
+        hipLaunchKernelGGL((dual_rows_kernel<D, true>), dim3(g.rest), dim3(64), C::LDS_FLOATS * sizeof(float), s,
+                           Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count_dev, (int)g.known, err);
 }
 
 void launch_dual_k16(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                     int count, int32_t *err, hipStream_t s) {
-    if (count <= 0) return;
+                     const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
     switch (d) {
-        case 16: launch_rows_typed<16>(Y, Z, R, ldr, r0, list, count, err, s); break;
-        case 32: launch_rows_typed<32>(Y, Z, R, ldr, r0, list, count, err, s); break;
-        case 64: launch_rows_typed<64>(Y, Z, R, ldr, r0, list, count, err, s); break;
-        case 128: launch_rows_typed<128>(Y, Z, R, ldr, r0, list, count, err, s); break;
+        case 16: launch_rows_typed<16>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
+        case 32: launch_rows_typed<32>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
+        case 64: launch_rows_typed<64>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
+        case 128: launch_rows_typed<128>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
     }
 }
 

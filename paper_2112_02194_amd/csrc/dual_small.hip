@@ -37,18 +37,16 @@ template <int D, int G> struct SmallCfg {
 };
 
 template <int D, int G>
-__global__ __launch_bounds__(64) void dual_small_kernel(const int64_t *__restrict__ indptr,
-                                                        const int32_t *__restrict__ indices,
-                                                        const float *__restrict__ values,
-                                                        const float *__restrict__ Z, float *__restrict__ R,
-                                                        int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
-                                                        int count, int32_t *__restrict__ err_flag) {
+__device__ __forceinline__ void dual_small_step(const int64_t *__restrict__ indptr, const int32_t *__restrict__ indices,
+                                                const float *__restrict__ values, const float *__restrict__ Z,
+                                                float *__restrict__ R, int64_t ldr, int64_t r0,
+                                                const int32_t *__restrict__ list, int count,
+                                                int32_t *__restrict__ err_flag, int blk, float *lds) {
     using C = SmallCfg<D, G>;
     constexpr int SPT = C::SPT, NR = C::NR, KP = C::KP, ZLD = C::ZLD, NJ = D / 16, CPL = D >= 128 ? 2 : 1;
-    extern __shared__ float lds[];
     float *sb = lds, *zb = lds, *tb = lds + C::OFF_T;
     int32_t *meta = (int32_t *)(lds + C::OFF_META);  // [NR][3]: u lo, u hi, k
-    const int lane = threadIdx.x, a = lane & 15, q = lane >> 4;
+    const int lane = opaque_tid(), a = lane & 15, q = lane >> 4;
     const int sub = a / G, e = a % G;  // MFMA view: sub-system of the tile and entry slot
     const bool upper = (a & 8) != 0;
 
@@ -62,7 +60,7 @@ __global__ __launch_bounds__(64) void dual_small_kernel(const int64_t *__restric
     int64_t bb[4], b1[4], idx[4];
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-        const int item = blockIdx.x * NR + p * SPT + sub;
+        const int item = blk * NR + p * SPT + sub;
         rel[p] = list[item < count ? item : count - 1];
     }
 #pragma unroll
@@ -73,7 +71,7 @@ __global__ __launch_bounds__(64) void dual_small_kernel(const int64_t *__restric
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         const int rr = p * SPT + sub;
-        const bool have = blockIdx.x * NR + rr < count;
+        const bool have = blk * NR + rr < count;
         const int64_t u = have ? r0 + rel[p] : -1;
         kk[p] = have ? (int)(b1[p] - bb[p]) : 0;
         if (q == 0 && e == 0) {
@@ -211,27 +209,56 @@ __global__ __launch_bounds__(64) void dual_small_kernel(const int64_t *__restric
     }
 }
 
+// The two launch forms of a step kernel (see StepGrid): one step per workgroup, or a grid-stride walk from
+// step first_blk to the end of the list.
+template <int D, int G, bool LOOP>
+__global__ __launch_bounds__(64) void dual_small_kernel(const int64_t *__restrict__ indptr,
+                                                        const int32_t *__restrict__ indices,
+                                                        const float *__restrict__ values,
+                                                        const float *__restrict__ Z, float *__restrict__ R,
+                                                        int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
+                                                        const int32_t *__restrict__ count_ptr, int first_blk,
+                                                        int32_t *__restrict__ err_flag) {
+    extern __shared__ float lds[];
+    constexpr int NR = SmallCfg<D, G>::NR;
+    const int count = *count_ptr;
+    int blk = first_blk + blockIdx.x;
+    if constexpr (!LOOP) {
+        if (blk * NR < count) dual_small_step<D, G>(indptr, indices, values, Z, R, ldr, r0, list, count, err_flag, blk, lds);
+    } else {
+        for (; blk * NR < count; blk += gridDim.x) {
+            dual_small_step<D, G>(opaque(indptr), opaque(indices), opaque(values), opaque(Z), opaque(R), opaque(ldr), opaque(r0),
+                              opaque(list), opaque(count), opaque(err_flag), blk, opaque(lds));
+            wave_sync();  // the next step reuses the LDS buffers
+        }
+    }
+}
+
 template <int D>
 static void launch_small_typed(const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0,
-                               const int32_t *list, int count, int32_t *err, hipStream_t s) {
+                               const int32_t *list, const int32_t *count_dev, StepGrid g, int32_t *err,
+                               hipStream_t s) {
     using C = SmallCfg<D, SMALL_G>;
-    hipLaunchKernelGGL((dual_small_kernel<D, SMALL_G>), dim3((unsigned)((count + C::NR - 1) / C::NR)), dim3(64),
-                       C::LDS_FLOATS * sizeof(float), s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count, err);
+    if (g.known > 0)
+        hipLaunchKernelGGL((dual_small_kernel<D, SMALL_G, false>), dim3(g.known), dim3(64), C::LDS_FLOATS * sizeof(float),
+                           s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count_dev, 0, err);
+    if (g.rest > 0)
+        hipLaunchKernelGGL((dual_small_kernel<D, SMALL_G, true>), dim3(g.rest), dim3(64), C::LDS_FLOATS * sizeof(float),
+                           s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count_dev, (int)g.known, err);
 }
 
 #if SMALL_G == 8
 void launch_dual_small8(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                        int count, int32_t *err, hipStream_t s) {
+                        const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
 #else
 void launch_dual_small4(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                        int count, int32_t *err, hipStream_t s) {
+                        const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
 #endif
-    if (count <= 0) return;
     switch (d) {
-        case 16: launch_small_typed<16>(Y, Z, R, ldr, r0, list, count, err, s); break;
-        case 32: launch_small_typed<32>(Y, Z, R, ldr, r0, list, count, err, s); break;
-        case 64: launch_small_typed<64>(Y, Z, R, ldr, r0, list, count, err, s); break;
-        case 128: launch_small_typed<128>(Y, Z, R, ldr, r0, list, count, err, s); break;
+        case 16: launch_small_typed<16>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
+        case 32: launch_small_typed<32>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
+        case 64: launch_small_typed<64>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
+        case 128: launch_small_typed<128>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
     }
 }
 

@@ -25,19 +25,17 @@ template <int D, int KT> struct WideCfg {
 };
 
 template <int D, int KT>
-__global__ __launch_bounds__(64, 2) void dual_wide_kernel(const int64_t *__restrict__ indptr,
-                                                       const int32_t *__restrict__ indices,
-                                                       const float *__restrict__ values,
-                                                       const float *__restrict__ Z, float *__restrict__ R,
-                                                       int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
-                                                       int32_t *__restrict__ err_flag) {
+__device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indptr, const int32_t *__restrict__ indices,
+                                               const float *__restrict__ values, const float *__restrict__ Z,
+                                               float *__restrict__ R, int64_t ldr, int64_t r0,
+                                               const int32_t *__restrict__ list, int32_t *__restrict__ err_flag,
+                                               int item, float *lds) {
     using C = WideCfg<D, KT>;
     constexpr int K = C::K, NJ = D / 16;
-    extern __shared__ float lds[];
     float *tri = lds, *aux = lds + C::OFF_COL, *tbuf = lds + C::OFF_T;
     int32_t *ids = (int32_t *)(lds + C::OFF_ID);
-    const int lane = threadIdx.x, a = lane & 15, q = lane >> 4;
-    const int64_t u = r0 + list[blockIdx.x];
+    const int lane = opaque_tid(), a = lane & 15, q = lane >> 4;
+    const int64_t u = r0 + list[item];
     const int64_t b = indptr[u];
     const int k = (int)(indptr[u + 1] - b);  // <= K by the list's class
 
@@ -153,26 +151,61 @@ __global__ __launch_bounds__(64, 2) void dual_wide_kernel(const int64_t *__restr
     }
 }
 
+// The two launch forms of a step kernel (see StepGrid): one row per workgroup, or a grid-stride walk from
+// row first_item to the end of the list.
+template <int D, int KT, bool LOOP>
+__global__ __launch_bounds__(64, LOOP ? 1 : 2) void dual_wide_kernel(const int64_t *__restrict__ indptr,
+                                                          const int32_t *__restrict__ indices,
+                                                          const float *__restrict__ values,
+                                                          const float *__restrict__ Z, float *__restrict__ R,
+                                                          int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
+                                                          const int32_t *__restrict__ count_ptr, int first_item,
+                                                          int32_t *__restrict__ err_flag) {
+    extern __shared__ float lds[];
+    const int count = *count_ptr;
+    int item = first_item + blockIdx.x;
+    if constexpr (!LOOP) {
+        if (item < count) dual_wide_step<D, KT>(indptr, indices, values, Z, R, ldr, r0, list, err_flag, item, lds);
+    } else {
+        for (; item < count; item += gridDim.x) {
+            dual_wide_step<D, KT>(opaque(indptr), opaque(indices), opaque(values), opaque(Z), opaque(R), opaque(ldr),
+                                  opaque(r0), opaque(list), opaque(err_flag), item, opaque(lds));
+            wave_sync();  // the next step reuses the LDS buffers
+        }
+    }
+}
+
 #define ALS_WIDE_NAME2(kt) launch_dual_wide##kt
 #define ALS_WIDE_NAME(kt) ALS_WIDE_NAME2(kt)
 
 template <int D>
 static als_status wide_typed(als_ctx *ctx, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0,
-                             const int32_t *list, int count, int32_t *err, hipStream_t s) {
+                             const int32_t *list, const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
     using C = WideCfg<D, WIDE_KT>;
-    auto kern = dual_wide_kernel<D, WIDE_KT>;
-    ALS_HIP(ctx, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)(C::LDS_FLOATS * sizeof(float))));
-    hipLaunchKernelGGL(kern, dim3((unsigned)count), dim3(64), C::LDS_FLOATS * sizeof(float), s, Y->indptr, Y->indices,
-                       Y->values, Z, R, ldr, r0, list, err);
+    auto kern = dual_wide_kernel<D, WIDE_KT, false>;
+    auto kern_loop = dual_wide_kernel<D, WIDE_KT, true>;
+    constexpr int lds_bytes = (int)(C::LDS_FLOATS * sizeof(float));
+    static const hipError_t attr = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    static const hipError_t attr_loop =
+        hipFuncSetAttribute((const void *)kern_loop, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);  // both once per process
+    ALS_HIP(ctx, attr);
+    ALS_HIP(ctx, attr_loop);
+    if (g.known > 0)
+        hipLaunchKernelGGL(kern, dim3(g.known), dim3(64), lds_bytes, s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0,
+                           list, count_dev, 0, err);
+    if (g.rest > 0)
+        hipLaunchKernelGGL(kern_loop, dim3(g.rest), dim3(64), lds_bytes, s, Y->indptr, Y->indices, Y->values, Z, R, ldr,
+                           r0, list, count_dev, (int)g.known, err);
     return ALS_OK;
 }
 
 als_status ALS_WIDE_NAME(WIDE_KT)(als_ctx *ctx, int d, const als_csr *Y, const float *Z, float *R, int64_t ldr,
-                                  int64_t r0, const int32_t *list, int count, int32_t *err, hipStream_t s) {
-    if (d == 128) return wide_typed<128>(ctx, Y, Z, R, ldr, r0, list, count, err, s);
+                                  int64_t r0, const int32_t *list, const int32_t *count_dev, StepGrid g,
+                                  int32_t *err, hipStream_t s) {
+    if (g.known == 0 && g.rest == 0) return ALS_OK;
+    if (d == 128) return wide_typed<128>(ctx, Y, Z, R, ldr, r0, list, count_dev, g, err, s);
     if constexpr (WIDE_KT <= 4) {  // the dual form reaches k <= 64 at d = 64
-        if (d == 64) return wide_typed<64>(ctx, Y, Z, R, ldr, r0, list, count, err, s);
+        if (d == 64) return wide_typed<64>(ctx, Y, Z, R, ldr, r0, list, count_dev, g, err, s);
     }
     return fail(ctx, ALS_EDTYPE, "wide dual kernel: unsupported d");
 }

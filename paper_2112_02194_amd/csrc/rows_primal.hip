@@ -16,7 +16,7 @@
 // in a fixed order before the same factorisation.
 #include <type_traits>
 
-#include "als_internal.h"
+#include "dual_common.h"
 #include "tri_solve.h"
 
 namespace als {
@@ -40,7 +40,7 @@ __device__ __forceinline__ void accumulate_entries(const void *__restrict__ V, i
                                                    float (&bsum)[Geo<D>::NC]) {
     using G = Geo<D>;
     constexpr int NC = G::NC, TM = G::TM, KS = G::KS, U = 8;
-    const int lane = threadIdx.x & 63;
+    const int lane = opaque_tid() & 63;
     const int m = lane % TM, kk = lane / TM;
     const uint32_t ld32 = (uint32_t)ld;  // the leading dimension fits 32 bits (checked on the host)
     const bool first_row = __builtin_amdgcn_readfirstlane(I) == 0;
@@ -112,7 +112,7 @@ template <int D>
 __device__ __forceinline__ void cholesky_solve_lds(float *a, float *aux, int32_t *err_flag) {
     constexpr int LD = Team<D>::LD, T = Team<D>::THREADS, TY = T / 32;
     float *dinv = aux, *z = aux + D, *xout = aux + 2 * D, *bvec = aux + 3 * D;
-    const int t = threadIdx.x, tx = t & 31, ty = t >> 5;
+    const int t = opaque_tid(), tx = t & 31, ty = t >> 5;
     for (int k = 0; k < D; ++k) {
         const float pivot = a[k * LD + k];
         if (t == 0 && !(pivot > 0.f)) atomicOr(err_flag, 1);
@@ -161,7 +161,7 @@ template <int D> struct Packed {
 // rounded once to the table's element type.  The other wavefronts of the workgroup may have exited.
 template <int D, bool BF16>
 __device__ __forceinline__ void packed_solve_store(float *lds, void *X, int64_t xoff, int32_t *err_flag) {
-    const int lane = threadIdx.x & 63;
+    const int lane = opaque_tid() & 63;
     float *tbuf = lds + Packed<D>::OFF_T;
     const float *rhs = lds + Packed<D>::OFF_RHS;
     const float y0 = lane < D ? rhs[lane] : 0.f;
@@ -176,7 +176,7 @@ __device__ __forceinline__ void packed_solve_store(float *lds, void *X, int64_t 
 // ---------------------------------------------------------------------------------------------- conjugate gradients
 template <int D>
 __device__ __forceinline__ float block_dot(float v, float *red /* [THREADS/64] */) {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int lane = opaque_tid() & 63, w = opaque_tid() >> 6;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
     __syncthreads();  // red is free again
@@ -192,7 +192,7 @@ template <int D>
 __device__ __forceinline__ void cg_solve_lds(const float *a, float *aux, int max_iters, float tol) {
     constexpr int LD = Team<D>::LD;
     float *rvec = aux, *pvec = aux + D, *xvec = aux + 2 * D, *bvec = aux + 3 * D, *red = aux + 4 * D;
-    const int i = threadIdx.x;
+    const int i = opaque_tid();
     const bool mine = i < D;
     auto matvec = [&](const float *v) {  // row i of A times v (A symmetric: read column i, contiguous in LDS)
         float s = 0.f;
@@ -241,25 +241,23 @@ __device__ __forceinline__ void solve_spd_lds(float *a, float *aux, int32_t *err
 // ---------------------------------------------------------------------------------------------- kernels
 enum PrimalMode { MODE_FUSED = 0, MODE_SEGMENT = 1 };
 
-// MODE_FUSED:   work item = the whole row u = row_begin + row_list[item].
-// MODE_SEGMENT: work item = segment `item` of segs[]; raw partial statistics are written to
-//               partials[item][D*D + D] (row-major D x D, then b).
+// One work item.  `last`: the workgroup has no further item, so the wavefronts that do not solve may retire
+// as soon as their tiles are in LDS (their SIMD slots go to the next workgroup).  Returns false when the
+// calling wavefront has retired.
 template <int D, bool BF16, int MODE>
-__global__ __launch_bounds__(Team<D>::THREADS, 2) void primal_kernel(
+__device__ __forceinline__ bool primal_step(
     const int64_t *__restrict__ indptr, const int32_t *__restrict__ indices, const float *__restrict__ values,
     const void *__restrict__ V, int64_t ldv, const float *__restrict__ G, float alpha, float lambda,
     void *__restrict__ X, int64_t ldx, int64_t row_begin, const int32_t *__restrict__ row_list,
-    const Segment *__restrict__ segs, float *__restrict__ partials,
-    int32_t *__restrict__ err_flag, int solver, int cg_iters, float cg_tol) {
+    const Segment *__restrict__ segs, float *__restrict__ partials, int32_t *__restrict__ err_flag, int solver,
+    int cg_iters, float cg_tol, int64_t item, bool last, float *lds) {
     using GE = Geo<D>;
     constexpr int NC = GE::NC, TM = GE::TM, ACC = GE::ACC, LD = Team<D>::LD;
     typedef typename AccT<ACC>::type acc_t;
-    extern __shared__ float lds[];
     float *a = lds, *aux = lds + D * LD, *bvec = aux + 3 * D;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = opaque_tid() & 63, wave = opaque_tid() >> 6;
     const int m = lane % TM, kk = lane / TM;
-    const int64_t item = blockIdx.x;
     int64_t u = 0, begin, end;
     if constexpr (MODE == MODE_FUSED) {
         u = row_begin + row_list[item];
@@ -294,7 +292,8 @@ __global__ __launch_bounds__(Team<D>::THREADS, 2) void primal_kernel(
 #pragma unroll
             for (int j = 0; j < NC; ++j) out[D * D + NC * m + j] = bsum[j];
         }
-        return;
+        (void)last;
+        return true;
     } else {
         if constexpr (D >= 64) {
             if (solver == ALS_SOLVER_DIRECT) {  // uniform for the launch
@@ -314,9 +313,13 @@ __global__ __launch_bounds__(Team<D>::THREADS, 2) void primal_kernel(
                 }
                 __syncthreads();
                 // scalar test: the solver must not sit in (what looks like) divergent control flow
-                if (__builtin_amdgcn_readfirstlane(wave) != 0) return;
-                packed_solve_store<D, BF16>(lds, X, u * ldx, err_flag);
-                return;
+                if (__builtin_amdgcn_readfirstlane(wave) != 0) {
+                    if (last) return false;
+                } else {
+                    packed_solve_store<D, BF16>(lds, X, u * ldx, err_flag);
+                }
+                if (!last) __syncthreads();  // the solver is done with the LDS before the next row's tiles arrive
+                return true;
             }
         }
         // A = alpha*G + lambda*I + V_I^T V_I into LDS (entry (r,c) at a[c*LD + r])
@@ -332,12 +335,46 @@ __global__ __launch_bounds__(Team<D>::THREADS, 2) void primal_kernel(
             for (int j = 0; j < NC; ++j) bvec[NC * m + j] = bsum[j];
         }
         if (solver == ALS_SOLVER_CG) {  // warm start from the row's current content
-            for (int c = threadIdx.x; c < D; c += Team<D>::THREADS) aux[2 * D + c] = load_elem<BF16>(X, u * ldx + c);
+            for (int c = opaque_tid(); c < D; c += Team<D>::THREADS) aux[2 * D + c] = load_elem<BF16>(X, u * ldx + c);
         }
         __syncthreads();
         solve_spd_lds<D>(a, aux, err_flag, solver, cg_iters, cg_tol);
         const float *xout = aux + 2 * D;
-        for (int c = threadIdx.x; c < D; c += Team<D>::THREADS) store_elem<BF16>(X, u * ldx + c, xout[c]);
+        for (int c = opaque_tid(); c < D; c += Team<D>::THREADS) store_elem<BF16>(X, u * ldx + c, xout[c]);
+        if (!last) __syncthreads();  // before the next row's tiles overwrite the LDS
+        return true;
+    }
+}
+
+// MODE_FUSED:   work item = the whole row u = row_begin + row_list[item].
+// MODE_SEGMENT: work item = segment `item` of segs[]; raw partial statistics are written to
+//               partials[item][D*D + D] (row-major D x D, then b).
+// The two launch forms (see StepGrid): LOOP = false, workgroup b takes item first + b if there is one;
+// LOOP = true, grid-stride walk from item `first` on.  *count_ptr is the number of items (device memory).
+template <int D, bool BF16, int MODE, bool LOOP>
+__global__ __launch_bounds__(Team<D>::THREADS, LOOP ? 1 : 2) void primal_kernel(
+    const int64_t *__restrict__ indptr, const int32_t *__restrict__ indices, const float *__restrict__ values,
+    const void *__restrict__ V, int64_t ldv, const float *__restrict__ G, float alpha, float lambda,
+    void *__restrict__ X, int64_t ldx, int64_t row_begin, const int32_t *__restrict__ row_list,
+    const Segment *__restrict__ segs, float *__restrict__ partials, const int32_t *__restrict__ count_ptr, int first,
+    int32_t *__restrict__ err_flag, int solver, int cg_iters, float cg_tol) {
+    extern __shared__ float lds[];
+    const int64_t nitems = *count_ptr;
+    int64_t item = (int64_t)first + blockIdx.x;
+    if constexpr (!LOOP) {
+        if (item < nitems)
+            primal_step<D, BF16, MODE>(indptr, indices, values, V, ldv, G, alpha, lambda, X, ldx, row_begin, row_list, segs,
+                                       partials, err_flag, solver, cg_iters, cg_tol, item, true, lds);
+    } else {
+        for (; item < nitems; item += gridDim.x) {
+            const bool last = item + gridDim.x >= nitems;
+            if (!primal_step<D, BF16, MODE>(opaque(indptr), opaque(indices), opaque(values), opaque(V), opaque(ldv),
+                                            opaque(G), opaque(alpha), opaque(lambda), opaque(X), opaque(ldx),
+                                            opaque(row_begin), opaque(row_list), opaque(segs), opaque(partials),
+                                            opaque(err_flag), opaque(solver), opaque(cg_iters), opaque(cg_tol), item, last,
+                                            opaque(lds)))
+                return;
+        }
     }
 }
 
@@ -345,10 +382,13 @@ __global__ __launch_bounds__(Team<D>::THREADS, 2) void primal_kernel(
 // [256y, 256y+256) of long row x and overwrites the row's first partial with the sum.
 template <int D>
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const LongRow *__restrict__ long_rows,
-                                                              float *__restrict__ partials) {
-    const LongRow lr = long_rows[blockIdx.x];
-    const int e = blockIdx.y * 256 + threadIdx.x;
-    if (e >= D * D + D || lr.nseg <= 1) return;
+                                                              float *__restrict__ partials,
+                                                              const int32_t *__restrict__ n_long_ptr) {
+    const int n_long = *n_long_ptr;
+    for (int row = blockIdx.x; row < n_long; row += gridDim.x) {
+    const LongRow lr = long_rows[row];
+    const int e = blockIdx.y * 256 + opaque_tid();
+    if (e >= D * D + D || lr.nseg <= 1) continue;
     float *p0 = partials + (int64_t)lr.seg_first * (D * D + D) + e;
     float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
     int g = 0;
@@ -360,23 +400,23 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const LongRow *__r
     }
     for (; g < lr.nseg; ++g) s0 += p0[(int64_t)g * (D * D + D)];
     p0[0] = (s0 + s1) + (s2 + s3);
+    }
 }
 
-// Loads the summed statistics of one long row, adds alpha*G + lambda*I, solves, stores.
+// Loads the summed statistics of one long row, adds alpha*G + lambda*I, solves, stores.  `last` and the
+// return value as in primal_step.
 template <int D, bool BF16>
-__global__ __launch_bounds__(Team<D>::THREADS) void reduce_solve_kernel(
-    const LongRow *__restrict__ long_rows, const float *__restrict__ partials, const float *__restrict__ G,
-    float alpha, float lambda, void *__restrict__ X, int64_t ldx, int32_t *__restrict__ err_flag, int solver,
-    int cg_iters, float cg_tol) {
+__device__ __forceinline__ bool reduce_solve_step(const LongRow lr, const float *__restrict__ partials,
+                                                  const float *__restrict__ G, float alpha, float lambda,
+                                                  void *__restrict__ X, int64_t ldx, int32_t *__restrict__ err_flag,
+                                                  int solver, int cg_iters, float cg_tol, bool last, float *lds) {
     constexpr int LD = Team<D>::LD, T = Team<D>::THREADS;
-    extern __shared__ float lds[];
     float *a = lds, *aux = lds + D * LD, *bvec = aux + 3 * D;
-    const LongRow lr = long_rows[blockIdx.x];
     const float *p0 = partials + (int64_t)lr.seg_first * (D * D + D);
     if constexpr (D >= 64) {
         if (solver == ALS_SOLVER_DIRECT) {
             float *tri = lds, *rhs = lds + Packed<D>::OFF_RHS;
-            for (int e = threadIdx.x; e < D * D + D; e += T) {
+            for (int e = opaque_tid(); e < D * D + D; e += T) {
                 const float s = p0[e];
                 if (e < D * D) {
                     const int r = e / D, c = e % D;
@@ -386,12 +426,16 @@ __global__ __launch_bounds__(Team<D>::THREADS) void reduce_solve_kernel(
                 }
             }
             __syncthreads();
-            if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) != 0) return;
-            packed_solve_store<D, BF16>(lds, X, lr.row * ldx, err_flag);
-            return;
+            if (__builtin_amdgcn_readfirstlane(opaque_tid() >> 6) != 0) {
+                if (last) return false;
+            } else {
+                packed_solve_store<D, BF16>(lds, X, lr.row * ldx, err_flag);
+            }
+            if (!last) __syncthreads();
+            return true;
         }
     }
-    for (int e = threadIdx.x; e < D * D + D; e += T) {
+    for (int e = opaque_tid(); e < D * D + D; e += T) {
         const float s = p0[e];
         if (e < D * D) {
             const int r = e / D, c = e % D;
@@ -401,12 +445,37 @@ __global__ __launch_bounds__(Team<D>::THREADS) void reduce_solve_kernel(
         }
     }
     if (solver == ALS_SOLVER_CG) {
-        for (int c = threadIdx.x; c < D; c += T) aux[2 * D + c] = load_elem<BF16>(X, lr.row * ldx + c);
+        for (int c = opaque_tid(); c < D; c += T) aux[2 * D + c] = load_elem<BF16>(X, lr.row * ldx + c);
     }
     __syncthreads();
     solve_spd_lds<D>(a, aux, err_flag, solver, cg_iters, cg_tol);
     const float *xout = aux + 2 * D;
-    for (int c = threadIdx.x; c < D; c += T) store_elem<BF16>(X, lr.row * ldx + c, xout[c]);
+    for (int c = opaque_tid(); c < D; c += T) store_elem<BF16>(X, lr.row * ldx + c, xout[c]);
+    if (!last) __syncthreads();
+    return true;
+}
+
+template <int D, bool BF16, bool LOOP>
+__global__ __launch_bounds__(Team<D>::THREADS) void reduce_solve_kernel(
+    const LongRow *__restrict__ long_rows, const float *__restrict__ partials, const float *__restrict__ G,
+    float alpha, float lambda, void *__restrict__ X, int64_t ldx, const int32_t *__restrict__ n_long_ptr, int first,
+    int32_t *__restrict__ err_flag, int solver, int cg_iters, float cg_tol) {
+    extern __shared__ float lds[];
+    const int n_long = *n_long_ptr;
+    int row = first + (int)blockIdx.x;
+    if constexpr (!LOOP) {
+        if (row < n_long)
+            reduce_solve_step<D, BF16>(long_rows[row], partials, G, alpha, lambda, X, ldx, err_flag, solver, cg_iters,
+                                       cg_tol, true, lds);
+    } else {
+        for (; row < n_long; row += gridDim.x) {
+            const bool last = row + (int)gridDim.x >= n_long;
+            if (!reduce_solve_step<D, BF16>(long_rows[row], opaque(partials), opaque(G), opaque(alpha), opaque(lambda),
+                                            opaque(X), opaque(ldx), opaque(err_flag), opaque(solver), opaque(cg_iters),
+                                            opaque(cg_tol), last, opaque(lds)))
+                return;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------- launchers
@@ -420,49 +489,80 @@ template <int D> static size_t solve_lds_bytes(int solver) {
 template <int D, bool BF16>
 static als_status primal_typed(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
                                const als_params *prm, als_table *X, int64_t r0, const int32_t *row_list,
-                               int64_t nitems, hipStream_t s) {
-    if (nitems <= 0) return ALS_OK;
+                               const int32_t *count_dev, StepGrid g, hipStream_t s) {
+    if (g.known == 0 && g.rest == 0) return ALS_OK;
     int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
     const int cg_iters = prm->cg_max_iters > 0 ? prm->cg_max_iters : 2 * D;
     const float cg_tol = prm->cg_tol > 0.f ? prm->cg_tol : 1e-6f;
-    auto kern = primal_kernel<D, BF16, MODE_FUSED>;
-    ALS_HIP(ctx, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)Team<D>::LDS_BYTES));
+    auto kern = primal_kernel<D, BF16, MODE_FUSED, false>;
+    auto kern_loop = primal_kernel<D, BF16, MODE_FUSED, true>;
+    static const hipError_t attr = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                       (int)Team<D>::LDS_BYTES);
+    static const hipError_t attr_loop = hipFuncSetAttribute(
+        (const void *)kern_loop, hipFuncAttributeMaxDynamicSharedMemorySize, (int)Team<D>::LDS_BYTES);  // both once per process
+    ALS_HIP(ctx, attr);
+    ALS_HIP(ctx, attr_loop);
     const size_t lds_bytes = solve_lds_bytes<D>(prm->solver);
     timer_begin(ctx, T_PRIMAL, s);
-    hipLaunchKernelGGL(kern, dim3((unsigned)nitems), dim3(Team<D>::THREADS), lds_bytes, s, Y->indptr,
-                       Y->indices, Y->values, V->data, V->ld, G, prm->alpha, prm->lambda, X->data, X->ld, r0,
-                       row_list, (const Segment *)nullptr, (float *)nullptr, err, prm->solver, cg_iters, cg_tol);
+    if (g.known > 0)
+        hipLaunchKernelGGL(kern, dim3(g.known), dim3(Team<D>::THREADS), lds_bytes, s, Y->indptr, Y->indices, Y->values,
+                           V->data, V->ld, G, prm->alpha, prm->lambda, X->data, X->ld, r0, row_list,
+                           (const Segment *)nullptr, (float *)nullptr, count_dev, 0, err, prm->solver, cg_iters, cg_tol);
+    if (g.rest > 0)
+        hipLaunchKernelGGL(kern_loop, dim3(g.rest), dim3(Team<D>::THREADS), lds_bytes, s, Y->indptr, Y->indices,
+                           Y->values, V->data, V->ld, G, prm->alpha, prm->lambda, X->data, X->ld, r0, row_list,
+                           (const Segment *)nullptr, (float *)nullptr, count_dev, (int)g.known, err, prm->solver,
+                           cg_iters, cg_tol);
     timer_end(ctx, s);
     ALS_HIP(ctx, hipGetLastError());
     return ALS_OK;
 }
 
+// counters[0] = number of long rows, counters[1] = number of their segments (device memory).
 template <int D, bool BF16>
 static als_status long_typed(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
-                             const als_params *prm, als_table *X, const LongRow *long_rows, int n_long,
-                             const Segment *segs, int n_seg, hipStream_t s) {
-    if (n_long <= 0) return ALS_OK;
-    als_status st = ensure(ctx, ctx->seg_partials, (size_t)n_seg * (D * D + D) * sizeof(float));
+                             const als_params *prm, als_table *X, const LongRow *long_rows, const Segment *segs,
+                             const int32_t *counters, int64_t seg_capacity, StepGrid g_long, StepGrid g_seg,
+                             hipStream_t s) {
+    if (g_seg.known == 0 && g_seg.rest == 0) return ALS_OK;
+    als_status st = ensure(ctx, ctx->seg_partials, (size_t)seg_capacity * (D * D + D) * sizeof(float));
     if (st != ALS_OK) return st;
     int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
     const int cg_iters = prm->cg_max_iters > 0 ? prm->cg_max_iters : 2 * D;
     const float cg_tol = prm->cg_tol > 0.f ? prm->cg_tol : 1e-6f;
-    auto kseg = primal_kernel<D, BF16, MODE_SEGMENT>;
-    auto kred = reduce_solve_kernel<D, BF16>;
-    ALS_HIP(ctx, hipFuncSetAttribute((const void *)kred, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)Team<D>::LDS_BYTES));
+    auto kred = reduce_solve_kernel<D, BF16, false>;
+    auto kred_loop = reduce_solve_kernel<D, BF16, true>;
+    static const hipError_t attr = hipFuncSetAttribute((const void *)kred, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                       (int)Team<D>::LDS_BYTES);
+    static const hipError_t attr_loop = hipFuncSetAttribute(
+        (const void *)kred_loop, hipFuncAttributeMaxDynamicSharedMemorySize, (int)Team<D>::LDS_BYTES);  // both once per process
+    ALS_HIP(ctx, attr);
+    ALS_HIP(ctx, attr_loop);
+    float *partials = (float *)ctx->seg_partials.p;
     timer_begin(ctx, T_SEGMENT, s);
-    hipLaunchKernelGGL(kseg, dim3((unsigned)n_seg), dim3(Team<D>::THREADS), 0, s, Y->indptr, Y->indices, Y->values,
-                       V->data, V->ld, G, prm->alpha, prm->lambda, X->data, X->ld, (int64_t)0,
-                       (const int32_t *)nullptr, segs, (float *)ctx->seg_partials.p, err, 0, 0, 0.f);
+    if (g_seg.known > 0)
+        hipLaunchKernelGGL((primal_kernel<D, BF16, MODE_SEGMENT, false>), dim3(g_seg.known), dim3(Team<D>::THREADS), 0, s,
+                           Y->indptr, Y->indices, Y->values, V->data, V->ld, G, prm->alpha, prm->lambda, X->data, X->ld,
+                           (int64_t)0, (const int32_t *)nullptr, segs, partials, counters + 1, 0, err, 0, 0, 0.f);
+    if (g_seg.rest > 0)
+        hipLaunchKernelGGL((primal_kernel<D, BF16, MODE_SEGMENT, true>), dim3(g_seg.rest), dim3(Team<D>::THREADS), 0, s,
+                           Y->indptr, Y->indices, Y->values, V->data, V->ld, G, prm->alpha, prm->lambda, X->data, X->ld,
+                           (int64_t)0, (const int32_t *)nullptr, segs, partials, counters + 1, (int)g_seg.known, err, 0,
+                           0, 0.f);
     timer_end(ctx, s);
     timer_begin(ctx, T_REDUCE, s);
-    hipLaunchKernelGGL(reduce_partials_kernel<D>, dim3((unsigned)n_long, (D * D + D + 255) / 256), dim3(256), 0, s,
-                       long_rows, (float *)ctx->seg_partials.p);
-    hipLaunchKernelGGL(kred, dim3((unsigned)n_long), dim3(Team<D>::THREADS), solve_lds_bytes<D>(prm->solver), s, long_rows,
-                       (const float *)ctx->seg_partials.p, G, prm->alpha, prm->lambda, X->data, X->ld, err, prm->solver,
-                       cg_iters, cg_tol);
+    const unsigned red_blocks = std::max(1u, g_long.known + g_long.rest);  // grid-stride over the long rows
+    hipLaunchKernelGGL(reduce_partials_kernel<D>, dim3(red_blocks, (D * D + D + 255) / 256), dim3(256), 0, s, long_rows,
+                       partials, counters);
+    const size_t lds_bytes = solve_lds_bytes<D>(prm->solver);
+    if (g_long.known > 0)
+        hipLaunchKernelGGL(kred, dim3(g_long.known), dim3(Team<D>::THREADS), lds_bytes, s, long_rows,
+                           (const float *)partials, G, prm->alpha, prm->lambda, X->data, X->ld, counters, 0, err,
+                           prm->solver, cg_iters, cg_tol);
+    if (g_long.rest > 0)
+        hipLaunchKernelGGL(kred_loop, dim3(g_long.rest), dim3(Team<D>::THREADS), lds_bytes, s, long_rows,
+                           (const float *)partials, G, prm->alpha, prm->lambda, X->data, X->ld, counters,
+                           (int)g_long.known, err, prm->solver, cg_iters, cg_tol);
     timer_end(ctx, s);
     ALS_HIP(ctx, hipGetLastError());
     return ALS_OK;
@@ -479,16 +579,17 @@ static als_status long_typed(als_ctx *ctx, const als_csr *Y, const als_table *V,
 
 als_status launch_primal_fused(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
                                const als_params *prm, als_table *X, int64_t r0, const int32_t *row_list,
-                               int64_t nitems, hipStream_t s) {
+                               const int32_t *count_dev, StepGrid g, hipStream_t s) {
     const bool bf = V->dtype == ALS_BF16;
-    ALS_DISPATCH(primal_typed, V->d, bf, ctx, Y, V, G, prm, X, r0, row_list, nitems, s);
+    ALS_DISPATCH(primal_typed, V->d, bf, ctx, Y, V, G, prm, X, r0, row_list, count_dev, g, s);
 }
 
 als_status launch_primal_long(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
-                              const als_params *prm, als_table *X, const LongRow *long_rows, int n_long,
-                              const Segment *segs, int n_seg, hipStream_t s) {
+                              const als_params *prm, als_table *X, const LongRow *long_rows, const Segment *segs,
+                              const int32_t *counters, int64_t seg_capacity, StepGrid g_long, StepGrid g_seg,
+                              hipStream_t s) {
     const bool bf = V->dtype == ALS_BF16;
-    ALS_DISPATCH(long_typed, V->d, bf, ctx, Y, V, G, prm, X, long_rows, n_long, segs, n_seg, s);
+    ALS_DISPATCH(long_typed, V->d, bf, ctx, Y, V, G, prm, X, long_rows, segs, counters, seg_capacity, g_long, g_seg, s);
 }
 
 }  // namespace als

@@ -40,7 +40,7 @@ __device__ __forceinline__ void tri_solve(float *tri, float *aux /* [192] */, fl
     static_assert(K % 16 == 0 && K >= 16 && K <= 128, "unsupported system size");
     constexpr bool TWO = K > 64;
     constexpr int NT = K / 16;
-    const int lane = threadIdx.x & 63;
+    const int lane = opaque_tid() & 63;
     const int ra = lane, rb = 64 + lane;
     const bool hasa = ra < K, hasb = TWO && rb < K;
     const int a = lane & 15, q = lane >> 4;

@@ -278,3 +278,33 @@ def test_argument_errors_leave_outputs_untouched(ctx, gpu_device):
     with pytest.raises(als.AlsError):
         als.als_check_csr(ctx, als.Csr(100, 80, Y.indptr, bad_indices))
     als.als_check_csr(ctx, Y)
+
+
+def test_epoch_is_enqueued_without_waiting_for_the_gpu(ctx, gpu_device):
+    """als_epoch returns while the GPU is still busy with work queued before it: nothing in it waits for the
+    device or copies anything back (the row-class counts stay in device memory)."""
+    import time
+    say("als_epoch asynchronous")
+    p = make_problem("c3", rows=200000, cols=200000, d=128)
+    Y, Yt = to_dev(p, gpu_device)
+    W, H = p.W0.to(gpu_device), p.H0.to(gpu_device)
+    prm = als.make_params(p.alpha, p.lam)
+    als.als_epoch(ctx, Y, Yt, W, H, prm)  # first call: workspaces are allocated here
+    torch.cuda.synchronize()
+    ref_W, ref_H = W.clone(), H.clone()
+    W.copy_(p.W0.to(gpu_device)); H.copy_(p.H0.to(gpu_device))
+    a = torch.randn(8192, 8192, device=gpu_device)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(40):
+        a = (a @ a) * 1e-4  # roughly half a second of queued work
+    t_queue = time.perf_counter() - t0
+    als.als_epoch(ctx, Y, Yt, W, H, prm)
+    t_call = time.perf_counter() - t0 - t_queue
+    busy = not torch.cuda.current_stream().query()
+    torch.cuda.synchronize()
+    t_all = time.perf_counter() - t0
+    say(f"  queued {t_queue * 1e3:.1f} ms of launches, als_epoch returned after {t_call * 1e3:.2f} ms, "
+        f"GPU finished after {t_all * 1e3:.0f} ms")
+    assert busy and t_call < 0.25 * t_all
+    assert torch.equal(W, ref_W) and torch.equal(H, ref_H)  # same bits with and without launch-size hints

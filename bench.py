@@ -29,9 +29,8 @@ def measured_traffic(workload, kernel):
         return None
     with open(path) as f:
         table = json.load(f)
-    key = kernel.replace(" ", "")
     for entry in table.get(workload, []):
-        if entry["kernel"].replace(" ", "").startswith(key.split("(")[0]):
+        if entry["kernel"] == kernel:
             return entry["bytes_per_launch"]
     return None
 
@@ -184,13 +183,16 @@ def main():
     deg = {"row": p.indptr[1:] - p.indptr[:-1], "col": p.t_indptr[1:] - p.t_indptr[:-1]}
     dual_max = 0 if args.path == "primal" else {16: 16, 32: 32, 64: 64, 128: 128}[d]
     bounds = [("dual_k4", 0, 4), ("dual_k8", 4, 8)] + [(f"dual_k{16 * (c + 1)}", max(16 * c, 8), 16 * (c + 1)) for c in range(8)]
-    kernel_names = {"dual_k4": f"dual_small_kernel<{d}, 4>", "dual_k8": f"dual_small_kernel<{d}, 8>",
-                    "dual_k16": f"dual_rows_kernel<{d}>", "dual_k32": f"dual_multi_kernel<{d}, 2>"}
+    bft = "true" if es == 2 else "false"  # the kernels' template arguments as rocprofv3 prints them
+    kernel_names = {"dual_k4": f"dual_small_kernel<{d},4,false>", "dual_k8": f"dual_small_kernel<{d},8,false>",
+                    "dual_k16": f"dual_rows_kernel<{d},false>", "dual_k32": f"dual_multi_kernel<{d},2,false>"}
     for c in range(2, 8):
-        kernel_names[f"dual_k{16 * (c + 1)}"] = f"dual_wide_kernel<{d}, {c + 1}>"
-    kernel_names.update({"gramian": f"gramian_partial_kernel<{d}>", "transform_z": f"transform_kernel<{d}> (Z = V L^-T)",
-                         "transform_x": f"transform_kernel<{d}> (X = R L^-1)", "primal": f"primal_kernel<{d}> (fused)",
-                         "segment": f"primal_kernel<{d}> (segments)"})
+        kernel_names[f"dual_k{16 * (c + 1)}"] = f"dual_wide_kernel<{d},{c + 1},false>"
+    kernel_names.update({"gramian": f"gramian_partial_kernel<{d},{bft}>",
+                         "transform_z": f"transform_kernel<{d},{bft},false,true>",    # Z = V L^-T
+                         "transform_x": f"transform_kernel<{d},false,{bft},false>",   # X = R L^-1
+                         "primal": f"primal_kernel<{d},{bft},0,false>",               # one workgroup per row
+                         "segment": f"primal_kernel<{d},{bft},1,false>"})             # segments of long rows
     work = {}
     long_nnz = prim_rows = prim_nnz = 0
     for kdeg in deg.values():

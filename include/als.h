@@ -148,6 +148,17 @@ als_status als_epoch(als_ctx *ctx, const als_csr *Y, const als_csr *Yt, als_tabl
 als_status als_loss(als_ctx *ctx, const als_csr *Y, const als_table *W, const als_table *H,
                     const als_params *params, double *loss_host, void *stream);
 
+/* Exact top-k retrieval by inner product (the retrieval step of Section 4.6; with rows folded in by
+ * als_solve_rows from part of their links it gives the Recall@K evaluation of Section 5):
+ * for every row q of Q [nq x d] the k rows i of H [n x d] with the largest <Q[q], H[i]>, leaving out the
+ * column ids stored in row q of `exclude` (nq rows, n columns; its values are not read; may be NULL).
+ * ids: device int32 [nq*k], scores: device fp32 [nq*k], row q at offset q*k, best first, equal scores by
+ * ascending id; where fewer than k rows are admissible the tail holds id -1 and score -inf.  Products and
+ * sums are fp32 (bf16 tables are widened exactly).  1 <= k <= ALS_TOPK_MAX_K.  Asynchronous on `stream`. */
+#define ALS_TOPK_MAX_K 64
+als_status als_topk(als_ctx *ctx, const als_table *Q, const als_table *H, const als_csr *exclude, int32_t k,
+                    int32_t *ids, float *scores, void *stream);
+
 /* Synchronise `stream` and report (then clear) the device-side error flag. */
 als_status als_status_sync(als_ctx *ctx, void *stream);
 

@@ -142,3 +142,36 @@ def loss(Y, W, H, alpha, lam, literal=False):
     n = H.shape[0]
     fn = _load().oracle_loss_literal if literal else _load().oracle_loss
     return float(fn(_ptr(ip), _ptr(ix), _ptr(vv), m, n, _ptr(W), _ptr(H), d, float(alpha), float(lam)))
+
+
+def topk(Q, H, k, exclude=None):
+    """Exact top-k by inner product, the plain definition: all scores Q H^T in fp64, per query the k largest,
+    equal scores by ascending id; `exclude` = (indptr, indices) of ids never returned per query.
+    Returns (ids [nq, k] with -1 where fewer than k rows are admissible, scores [nq, k] with -inf there)."""
+    Q, H = _f64(Q), _f64(H)
+    S = Q @ H.T
+    if exclude is not None:
+        ip, ix = np.asarray(exclude[0]), np.asarray(exclude[1])
+        for q in range(Q.shape[0]):
+            S[q, ix[ip[q]:ip[q + 1]]] = -np.inf
+    order = np.argsort(-S, axis=1, kind="stable")[:, :k]  # stable: equal scores stay in id order
+    sc = np.take_along_axis(S, order, axis=1)
+    ids = np.where(np.isfinite(sc), order, -1).astype(np.int64)
+    if ids.shape[1] < k:
+        pad = k - ids.shape[1]
+        ids = np.pad(ids, ((0, 0), (0, pad)), constant_values=-1)
+        sc = np.pad(sc, ((0, 0), (0, pad)), constant_values=-np.inf)
+    return ids, sc
+
+
+def recall_at_k(ids, held_indptr, held_indices):
+    """Recall@K per query: |top-K ids that are held-out links| / min(K, number of held-out links); queries
+    without a held-out link are left out (NaN)."""
+    ids = np.asarray(ids)
+    ip, ix = np.asarray(held_indptr), np.asarray(held_indices)
+    out = np.full(ids.shape[0], np.nan)
+    for q in range(ids.shape[0]):
+        want = set(ix[ip[q]:ip[q + 1]].tolist())
+        if want:
+            out[q] = len(want.intersection(ids[q].tolist())) / min(ids.shape[1], len(want))
+    return out

@@ -24,7 +24,7 @@ SOLVER_DIRECT, SOLVER_CG = 0, 1
 
 EXPORTS = ["als_create", "als_destroy", "als_gramian", "als_solve_rows", "als_epoch", "als_loss",
            "als_status_sync", "als_check_csr", "als_copy_probe", "als_set_timing", "als_get_timing",
-           "als_strerror", "als_last_error", "als_gramian_static", "als_static_last_error"]
+           "als_strerror", "als_last_error", "als_gramian_static", "als_static_last_error", "als_topk"]
 
 
 class c_als_csr(ctypes.Structure):
@@ -81,6 +81,8 @@ def load_library(path: str = LIB_PATH):
     lib.als_last_error.restype = ctypes.c_char_p
     lib.als_gramian_static.argtypes = [i32, P(c_als_table), vp, vp]
     lib.als_gramian_static.restype = i32
+    lib.als_topk.argtypes = [vp, P(c_als_table), P(c_als_table), P(c_als_csr), i32, vp, vp, vp]
+    lib.als_topk.restype = i32
     lib.als_static_last_error.argtypes = []
     lib.als_static_last_error.restype = ctypes.c_char_p
     _lib = lib
@@ -205,6 +207,17 @@ def als_loss(ctx: Context, Y: Csr, W: torch.Tensor, H: torch.Tensor, params: c_a
     ctx._check(ctx.lib.als_loss(ctx.handle, ctypes.byref(cy), ctypes.byref(tw), ctypes.byref(th),
                                 ctypes.byref(params), ctypes.byref(out), _stream()))
     return out.value
+
+
+def als_topk(ctx: Context, Q: torch.Tensor, H: torch.Tensor, k: int, exclude: Optional[Csr] = None):
+    """Best k rows of H per row of Q by inner product -> (ids int32 [nq, k], scores fp32 [nq, k])."""
+    tq, th = _table(Q), _table(H)
+    ids = torch.empty((Q.shape[0], k), dtype=torch.int32, device=Q.device)
+    scores = torch.empty((Q.shape[0], k), dtype=torch.float32, device=Q.device)
+    ex = exclude.c() if exclude is not None else None
+    ctx._check(ctx.lib.als_topk(ctx.handle, ctypes.byref(tq), ctypes.byref(th), ctypes.byref(ex) if ex is not None else None,
+                                k, ids.data_ptr(), scores.data_ptr(), _stream()))
+    return ids, scores
 
 
 def als_status_sync(ctx: Context) -> None:

@@ -23,6 +23,7 @@ UNITS = [
     ("rows_primal.hip", "rows_primal", []),
     ("solve_rows.hip", "solve_rows", []),
     ("loss.hip", "loss", []),
+    ("topk.hip", "topk", []),
     ("dual_prepare.hip", "dual_prepare", []),
     ("dual_rows.hip", "dual_rows", []),
     ("dual_small.hip", "dual_small_g8", ["-DSMALL_G=8"]),

@@ -172,7 +172,7 @@ als_status als_destroy(als_ctx *ctx) {
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
     DevBuf *bufs[] = {&ctx->gram_partials, &ctx->lists, &ctx->seg_partials, &ctx->ztable, &ctx->rtable, &ctx->small,
-                      &ctx->loss_partials, &ctx->gram_w, &ctx->gram_h};
+                      &ctx->loss_partials, &ctx->topk_partials, &ctx->gram_w, &ctx->gram_h};
     for (DevBuf *b : bufs)
         if (b->p) (void)hipFree(b->p);
     if (ctx->hint_counts) (void)hipHostFree(ctx->hint_counts);
@@ -281,6 +281,26 @@ als_status als_loss(als_ctx *ctx, const als_csr *Y, const als_table *W, const al
     if ((st = als_status_sync(ctx, stream)) != ALS_OK) return st;
     *loss_host = ctx->host_scalar[0];
     return ALS_OK;
+}
+
+als_status als_topk(als_ctx *ctx, const als_table *Q, const als_table *H, const als_csr *exclude, int32_t k,
+                    int32_t *ids, float *scores, void *stream) {
+    if (!ctx) return ALS_EINVAL;
+    als_status st;
+    if ((st = check_table(ctx, Q, "Q")) != ALS_OK) return st;
+    if ((st = check_table(ctx, H, "H")) != ALS_OK) return st;
+    if (Q->d != H->d) return fail(ctx, ALS_ESHAPE, "Q and H differ in d");
+    if (Q->dtype != H->dtype) return fail(ctx, ALS_EDTYPE, "Q and H differ in dtype");
+    if (k < 1 || k > ALS_TOPK_MAX_K) return fail(ctx, ALS_EINVAL, "k must be in [1, ALS_TOPK_MAX_K]");
+    if (H->rows > INT32_MAX) return fail(ctx, ALS_ESHAPE, "item ids must fit int32");
+    if (!ids || !scores) return fail(ctx, ALS_EINVAL, "ids or scores is null");
+    if (exclude) {
+        if ((st = check_csr_args(ctx, exclude, "exclude")) != ALS_OK) return st;
+        if (exclude->rows != Q->rows || exclude->cols != H->rows)
+            return fail(ctx, ALS_ESHAPE, "exclude must have one row per query and one column per item");
+    }
+    if (Q->rows == 0) return ALS_OK;
+    return launch_topk(ctx, Q, H, exclude, k, ids, scores, (hipStream_t)stream);
 }
 
 als_status als_check_csr(als_ctx *ctx, const als_csr *Y, void *stream) {

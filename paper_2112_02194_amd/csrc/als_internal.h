@@ -150,6 +150,7 @@ struct als_ctx {
     als::DevBuf rtable;         // fp32 [rows][d] untransformed dual solutions when the output table is bf16
     als::DevBuf small;          // counters, flags, factor matrices, scalars
     als::DevBuf loss_partials;  // fp64 per-workgroup sums
+    als::DevBuf topk_partials;  // per slice and query: best k scores and ids
     als::DevBuf gram_w, gram_h; // fp32 [d*d] Gramians used by als_epoch / als_loss
     int32_t *host_counters = nullptr;  // pinned, 16 ints
     double *host_scalar = nullptr;     // pinned, 2 doubles
@@ -215,6 +216,8 @@ als_status launch_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V,
 als_status launch_loss(als_ctx *ctx, const als_csr *Y, const als_table *W, const als_table *H,
                        const float *GW, const float *GH, const als_params *prm, double *out_dev, hipStream_t s);
 als_status launch_check_csr(als_ctx *ctx, const als_csr *Y, int32_t *flag_dev, hipStream_t s);
+als_status launch_topk(als_ctx *ctx, const als_table *Q, const als_table *H, const als_csr *ex, int k, int32_t *ids,
+                       float *scores, hipStream_t s);
 als_status launch_copy_probe(als_ctx *ctx, const void *src, void *dst, int64_t bytes, hipStream_t s);
 
 }  // namespace als

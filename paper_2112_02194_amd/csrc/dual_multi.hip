@@ -72,14 +72,17 @@ __device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indp
     }
 
     // ---- 1. S of every row, packed lower triangle in LDS
-    int32_t idv[4][M];  // the column ids of all four rows first: one wait, not one per row
+    // the column ids of all four rows first: one wait, not one per row.  A slot past the row's k holds the id of
+    // the row's first entry with the top bit set: no load for the products, and a harmless, in-range row of the
+    // row's own for the second gather (where such a slot meets t = 0)
+    int32_t idv[4][M];
 #pragma unroll
     for (int p = 0; p < 4; ++p)
 #pragma unroll
         for (int t = 0; t < M; ++t) {
             const int e = 16 * t + a;
-            const int32_t id = indices[b[p] + (e < k[p] ? e : 0)];  // clamped: unconditional load, masked below
-            idv[p][t] = e < k[p] ? id : -1;
+            const int32_t id = indices[b[p] + (e < k[p] ? e : 0)];  // clamped: unconditional load
+            idv[p][t] = e < k[p] ? id : (id | (int32_t)0x80000000);
         }
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
@@ -88,7 +91,7 @@ __device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indp
         for (int t = 0; t < M; ++t) {
             const int e = 16 * t + a;
             const int32_t id = idv[p][t];
-            if (q == 0) ids[p * K + e] = id;
+            if (q == 0) ids[p * K + e] = id & 0x7fffffff;
 #pragma unroll
             for (int j = 0; j < NJ; ++j) z[t][j] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (id >= 0) {  // one masked region per tile, not one per load
@@ -243,7 +246,7 @@ __device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indp
         // entries per row and round (measured: 16 eight-byte loads in flight are best at d = 128, 32 four-byte
         // loads at d <= 64)
         constexpr int EPR = CPL == 2 ? 4 : 8, NQ = EPR / 4;
-        const int kmaxr = (kmax + EPR - 1) / EPR * EPR;  // padded entries have t = 0 and id -1 (row 0 is read instead)
+        const int kmaxr = (kmax + EPR - 1) / EPR * EPR;  // padded entries have t = 0 and the id of the row's first entry
         for (int e0 = 0; e0 < kmaxr; e0 += EPR) {
             int4 idq[4][NQ];
             float4 teq[4][NQ];
@@ -263,7 +266,7 @@ __device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indp
                         const int id[4] = {idq[p][h].x, idq[p][h].y, idq[p][h].z, idq[p][h].w};
 #pragma unroll
                         for (int x = 0; x < 4; ++x) {
-                            const float *zr = zcol + (int64_t)(id[x] < 0 ? 0 : id[x]) * D;
+                            const float *zr = zcol + (int64_t)id[x] * D;
                             if constexpr (CPL == 2) zz[p][4 * h + x] = *(const float2 *)zr;
                             else zz[p][4 * h + x] = make_float2(zr[0], 0.f);
                         }

@@ -44,8 +44,9 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
         const int e = 16 * t + a;
-        myid[t] = e < k ? indices[b + e] : -1;
-        if (q == 0) ids[e] = myid[t];
+        const int32_t id = indices[b + (e < k ? e : 0)];  // a slot past k: the row's first entry (meets t = 0 below)
+        myid[t] = e < k ? id : -1;
+        if (q == 0) ids[e] = id;
     }
     // the first RT tiles stay in registers for the whole phase (one round of loads, all in flight
     // together), already cut into the hi/lo bf16 operands of the split products (dual_common.h); later
@@ -121,7 +122,7 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
         float rv[CPL];
 #pragma unroll
         for (int c = 0; c < CPL; ++c) rv[c] = 0.f;
-        const int kp8 = (k + 7) & ~7;  // padded entries have t = 0 and id -1 (row 0 is read instead)
+        const int kp8 = (k + 7) & ~7;  // padded entries have t = 0 and the id of the row's first entry
         for (int e0 = 0; e0 < kp8; e0 += 8) {
             float zz[8][CPL];
             // ids and t of the round with 16-byte LDS reads, before the first load is issued
@@ -132,7 +133,7 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int id = idr[i];
-                const float *zp = Z + (int64_t)(id < 0 ? 0 : id) * D + CPL * lane;
+                const float *zp = Z + (int64_t)id * D + CPL * lane;
                 if constexpr (CPL == 2) {
                     const float2 t2 = *(const float2 *)zp;
                     zz[i][0] = t2.x;

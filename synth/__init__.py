@@ -10,6 +10,7 @@ from .matrices import (  # noqa: F401
     csr_from_edges,
     extract_rows,
     hash_u64,
+    holdout_split,
     init_table,
     make_problem,
     transpose_csr,

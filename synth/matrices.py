@@ -449,6 +449,44 @@ def make_problem(kind: str, device="cpu", rows: Optional[int] = None, cols: Opti
                          indptr, indices, vals, t_indptr, t_indices, t_vals, W0, H0)
 
 
+def _select_entries(indptr: torch.Tensor, indices: torch.Tensor, rows: torch.Tensor, keep: torch.Tensor):
+    """CSR of the listed rows restricted to the entries flagged in `keep` (one flag per entry of the matrix)."""
+    starts, lens = indptr[rows], indptr[rows + 1] - indptr[rows]
+    ptr = torch.zeros(rows.numel() + 1, dtype=torch.int64, device=indptr.device)
+    torch.cumsum(lens, 0, out=ptr[1:])
+    pos = torch.repeat_interleave(starts - ptr[:-1], lens) + torch.arange(int(ptr[-1]), device=indptr.device)
+    owner = torch.repeat_interleave(torch.arange(rows.numel(), device=indptr.device), lens)
+    sel = keep[pos]
+    counts = torch.bincount(owner[sel], minlength=rows.numel())
+    out_ptr = torch.zeros(rows.numel() + 1, dtype=torch.int64, device=indptr.device)
+    torch.cumsum(counts, 0, out=out_ptr[1:])
+    return out_ptr, indices[pos[sel]].contiguous()
+
+
+def holdout_split(indptr: torch.Tensor, indices: torch.Tensor, seed: int, test_fraction: float = 0.1,
+                  heldout_fraction: float = 0.25):
+    """Row split in the manner of the paper's Section 5 (strong generalisation): a hashed `test_fraction` of
+    the rows are test rows and leave the training matrix; of each test row's links a hashed
+    `heldout_fraction` are held out (to be predicted), the others are given (to fold the row in).
+
+    Returns a dict: train_rows, test_rows (int64 row ids), train = (indptr, indices) over the training rows
+    in order, given and held = (indptr, indices) over the test rows in order.  Index plumbing only."""
+    dev = indptr.device
+    m = indptr.numel() - 1
+    r = torch.arange(m, device=dev, dtype=torch.int64)
+    is_test = uniform01(hash_u64(seed, 21, r)) < test_fraction
+    test_rows, train_rows = torch.nonzero(is_test).flatten(), torch.nonzero(~is_test).flatten()
+    owner = _expand_rows(indptr)
+    held = uniform01(hash_u64(seed, 23, owner, indices.to(torch.int64))) < heldout_fraction
+    everything = torch.ones_like(held)
+    return {
+        "train_rows": train_rows, "test_rows": test_rows,
+        "train": _select_entries(indptr, indices, train_rows, everything),
+        "given": _select_entries(indptr, indices, test_rows, ~held),
+        "held": _select_entries(indptr, indices, test_rows, held),
+    }
+
+
 def extract_rows(indptr: torch.Tensor, indices: torch.Tensor, values: Optional[torch.Tensor], rows: torch.Tensor):
     """Sub-matrix made of the listed rows, with its column ids renumbered densely.
 

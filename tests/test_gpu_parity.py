@@ -308,3 +308,55 @@ def test_epoch_is_enqueued_without_waiting_for_the_gpu(ctx, gpu_device):
         f"GPU finished after {t_all * 1e3:.0f} ms")
     assert busy and t_call < 0.25 * t_all
     assert torch.equal(W, ref_W) and torch.equal(H, ref_H)  # same bits with and without launch-size hints
+
+
+@pytest.mark.parametrize("d", [32, 128])
+def test_unsorted_and_duplicate_entries_match_the_oracle(ctx, gpu_device, d):
+    """Entries of a row in arbitrary order, and the same column stored more than once: every stored entry is one
+    more term of the sums of Eq. 4 (no merging), in the oracle and in the library alike, on the same arrays."""
+    say(f"solve_rows with shuffled and duplicated entries d={d}")
+    p = make_problem("c1", rows=700, cols=900, d=d, values="uniform")
+    gen = torch.Generator().manual_seed(77 + d)
+    ip = p.indptr.tolist()
+    new_idx, new_val, new_ptr = [], [], [0]
+    for u in range(p.rows):
+        idx, val = p.indices[ip[u]:ip[u + 1]], p.values[ip[u]:ip[u + 1]]
+        if idx.numel() and u % 3 == 0:  # repeat some of the row's entries, with other labels
+            rep = torch.randint(0, idx.numel(), (1 + idx.numel() // 4,), generator=gen)
+            idx = torch.cat([idx, idx[rep]])
+            val = torch.cat([val, 0.5 + torch.rand(rep.numel(), generator=gen)])
+        perm = torch.randperm(idx.numel(), generator=gen)
+        new_idx.append(idx[perm]); new_val.append(val[perm]); new_ptr.append(new_ptr[-1] + idx.numel())
+    p.indices, p.values = torch.cat(new_idx), torch.cat(new_val)
+    p.indptr = torch.tensor(new_ptr, dtype=torch.int64)
+    assert int((p.indptr[1:] - p.indptr[:-1]).max()) > 40
+    _solve_case(ctx, gpu_device, p, als.PATH_AUTO, scale_v=8.0)                  # every row in the k x k form
+    _solve_case(ctx, gpu_device, p, als.PATH_AUTO, scale_v=8.0, dual_max_k=16)   # longer rows in the d x d form
+    _solve_case(ctx, gpu_device, p, als.PATH_PRIMAL, scale_v=8.0, split=20)      # and cut into segments
+
+
+def test_a_bad_table_row_only_reaches_the_rows_that_reference_it(ctx, gpu_device):
+    """Row 0 of the fixed table is not finite and no solved row references column 0: every result is finite and
+    matches the oracle (entry slots a kernel pads a row with must not read some other row of the table)."""
+    say("solve_rows with a non-finite, unreferenced table row")
+    p = make_problem("c1", rows=4 * 141, cols=3000, d=128, values="uniform")
+    gen = torch.Generator().manual_seed(5)
+    lengths = (torch.arange(4 * 141) % 141)[torch.randperm(4 * 141, generator=gen)]
+    cols = [1 + torch.randperm(p.cols - 1, generator=gen)[:int(k)].sort().values for k in lengths]  # never column 0
+    p.indptr = torch.zeros(4 * 141 + 1, dtype=torch.int64)
+    p.indptr[1:] = torch.cumsum(lengths, 0)
+    p.indices = torch.cat(cols).to(torch.int32)
+    p.values = 0.5 + torch.rand(int(p.indptr[-1]), generator=gen)
+    Y, _ = to_dev(p, gpu_device)
+    V = (p.H0 * 8.0).clone()
+    G = als.als_gramian(ctx, V.to(gpu_device))  # from the clean table
+    Gh = oracle.gramian(f64(V))
+    V[0] = float("nan")
+    V[0, 1::2] = float("inf")
+    X = torch.zeros(p.rows, p.d, device=gpu_device)
+    als.als_solve_rows(ctx, Y, V.to(gpu_device), G, als.make_params(p.alpha, p.lam), X)
+    als.als_status_sync(ctx)
+    ref = oracle.solve_rows(*host_csr(p.indptr, p.indices, p.values), f64(V), Gh, p.alpha, p.lam, None, "f32")
+    got = f64(X)
+    assert np.isfinite(ref).all() and np.isfinite(got).all()
+    assert rel_fro(got, ref) <= 1e-4 and max_row_err(got, ref) <= 1e-4

@@ -232,3 +232,27 @@ def test_storage_rounding_matches_library_casts():
     assert np.array_equal(oracle.round_storage(x, "f64"), x)
     X = oracle.half_epoch(*random_problem(6, 9, 4)[:3], RNG.normal(0, 1, (9, 4)), 0.1, 0.01, storage="bf16")
     assert np.array_equal(X, torch.from_numpy(X).bfloat16().double().numpy())
+
+
+def test_topk_and_recall_against_brute_force():
+    """oracle.topk / recall_at_k pinned to a pure-Python evaluation on tiny inputs: every score by a literal
+    dot product, candidates sorted as (-score, id) tuples, exclusions removed, including exact ties."""
+    rng = np.random.default_rng(11)
+    Q = rng.integers(-3, 4, size=(7, 5)).astype(np.float64)   # small integers: many exactly equal scores
+    H = rng.integers(-3, 4, size=(23, 5)).astype(np.float64)
+    ex_ptr = np.array([0, 0, 3, 3, 10, 10, 11, 11 + 22], dtype=np.int64)
+    ex_idx = np.concatenate([[4, 9, 0], np.arange(3, 10), [22], np.arange(22)]).astype(np.int32)
+    for k in (1, 4, 23, 30):
+        ids, sc = oracle.topk(Q, H, k, (ex_ptr, ex_idx))
+        for q in range(7):
+            banned = set(ex_idx[ex_ptr[q]:ex_ptr[q + 1]].tolist())
+            cand = sorted((-sum(Q[q, c] * H[i, c] for c in range(5)), i) for i in range(23) if i not in banned)
+            want = [i for _, i in cand[:k]] + [-1] * max(0, k - len(cand))
+            assert ids[q].tolist() == want
+            assert all(sc[q, r] == -cand[r][0] for r in range(min(k, len(cand))))
+    ids, _ = oracle.topk(Q, H, 4)
+    held_ptr = np.array([0, 2, 2, 3, 4, 5, 6, 12], dtype=np.int64)
+    held_idx = np.array([ids[0, 0], ids[0, 3], ids[2, 1], 99, ids[4, 2], 99, *ids[6, :4], 97, 98], dtype=np.int64)
+    rec = oracle.recall_at_k(ids, held_ptr, held_idx)
+    assert rec[0] == 1.0 and np.isnan(rec[1]) and rec[2] == 1.0 and rec[3] == 0.0 and rec[4] == 1.0 and rec[5] == 0.0
+    assert rec[6] == 1.0  # six held-out links, four of them retrieved: 4 / min(4, 6)

@@ -11,7 +11,7 @@
 // relative error of 1.3e-5 on the diagonal (sums of squares), all of one sign.
 #include <mutex>
 
-#include "als_internal.h"
+#include "dual_common.h"
 
 namespace als {
 
@@ -102,6 +102,120 @@ __global__ __launch_bounds__(GRAM_THREADS, 2) void gramian_partial_kernel(const 
     }
 }
 
+// ---------------------------------------------------------------------------------------------- bf16 tables
+// The same contraction for bf16 tables (d = 64, 128) on the bf16 matrix cores, where a table pass is bound
+// by HBM instead of by the fp32 matrix-core rate.  v_mfma_f32_32x32x16_bf16 wants, per lane, eight
+// consecutive entries along the contraction index, which here is the table row - but a lane loads eight
+// consecutive COLUMNS of one row (16 bytes).  The matrix core does the transposition itself: multiplying the
+// 32 rows x 16 columns piece as loaded (rows = M, columns = K) by a constant 0/1 selection matrix leaves
+// the piece in the accumulator layout, where a lane holds 16 rows of ONE column; products with 1 and sums
+// with 0 are exact, so cutting the fp32 results back to bf16 loses nothing, and the packed registers are
+// the K-contiguous operands of the Gramian products (both operands come from the same registers, so the
+// order in which rows sit in the K slots does not matter).  Per 32 table rows and d = 128: 8 selection
+// products + 20 Gramian products (upper block triangle) of 32 clocks each.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int D>
+__global__ __launch_bounds__(GRAM_THREADS, 1) void gramian_bf16_kernel(const uint16_t *__restrict__ V, int64_t rows,
+                                                                       int64_t ld, float *__restrict__ partials) {
+    constexpr int NB = D / 32, NCH = D / 16;  // column blocks of 32, loaded pieces of 16 columns
+    __shared__ float red[D * D];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 31, kq = lane >> 5;
+    const int64_t wave_id = (int64_t)blockIdx.x * (GRAM_THREADS / 64) + wave;
+    const int64_t nwaves = (int64_t)gridDim.x * (GRAM_THREADS / 64);
+
+    // selection operands: sel[h] (K = 16 piece columns, N = 32 block columns) has a one at (k, 16 h + k)
+    bf16x8 sel[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        u32x4 w = {0u, 0u, 0u, 0u};
+        const int k = m - 16 * h - 8 * kq;  // the K slot of this lane (8 kq + e) that equals column m - 16 h
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (k == e) w[e / 2] = (e & 1) ? 0x3F800000u : 0x00003F80u;  // bf16 1.0 in the upper / lower half
+        sel[h] = __builtin_bit_cast(bf16x8, w);
+    }
+    floatx16 acc[NB][NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // 32 rows per step (lane (m, kq) loads columns 16 c + 8 kq .. of row r0 + m); the loads of the next step are
+    // issued before the products of the current one
+    auto issue = [&](int64_t r0, u32x4 (&raw)[NCH]) {
+        const int64_t r = r0 + m;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) raw[c] = u32x4{0u, 0u, 0u, 0u};
+        if (r < rows) {
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) raw[c] = *(const u32x4 *)(V + r * ld + 16 * c + 8 * kq);
+        }
+    };
+    auto consume = [&](u32x4 (&raw)[NCH]) {
+        bf16x8 op[NB][2];  // per column block: rows 0..15 and 16..31 of the step in the K slots
+#pragma unroll
+        for (int g = 0; g < NB; ++g) {
+            floatx16 t;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) t[v] = 0.f;
+            t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw[2 * g]), sel[0], t, 0, 0, 0);
+            t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw[2 * g + 1]), sel[1], t, 0, 0, 0);
+            // t[v] = V[r0 + 8 (v / 4) + 4 kq + v % 4][32 g + m], exactly a bf16 value
+#pragma unroll
+            for (int x = 0; x < 2; ++x) {
+                const u32x4 w = {__builtin_amdgcn_perm(__float_as_uint(t[8 * x + 1]), __float_as_uint(t[8 * x + 0]), 0x07060302u),
+                                 __builtin_amdgcn_perm(__float_as_uint(t[8 * x + 3]), __float_as_uint(t[8 * x + 2]), 0x07060302u),
+                                 __builtin_amdgcn_perm(__float_as_uint(t[8 * x + 5]), __float_as_uint(t[8 * x + 4]), 0x07060302u),
+                                 __builtin_amdgcn_perm(__float_as_uint(t[8 * x + 7]), __float_as_uint(t[8 * x + 6]), 0x07060302u)};
+                op[g][x] = __builtin_bit_cast(bf16x8, w);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int j = i; j < NB; ++j) {  // upper block triangle; the result is symmetric
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[i][0], op[j][0], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[i][1], op[j][1], acc[i][j], 0, 0, 0);
+            }
+    };
+    u32x4 ra[NCH], rb[NCH];
+    const int64_t step = nwaves * 32;
+    int64_t r0 = wave_id * 32;
+    issue(r0, ra);
+    for (; r0 < rows; r0 += 2 * step) {
+        issue(r0 + step, rb);  // past the end: zeros, no loads
+        consume(ra);
+        issue(r0 + 2 * step, ra);
+        if (r0 + step < rows) consume(rb);
+    }
+
+    // fixed-order sum of the four wavefronts through LDS: acc[i][j][v] = G[32 i + row(v)][32 j + m]
+    for (int w = 0; w < GRAM_THREADS / 64; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+#pragma unroll
+                for (int j = i; j < NB; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int r = 32 * i + 8 * (v >> 2) + 4 * kq + (v & 3), c = 32 * j + m;
+                        if (w == 0) red[r * D + c] = acc[i][j][v];
+                        else red[r * D + c] += acc[i][j][v];
+                    }
+        }
+        __syncthreads();
+    }
+    float *out = partials + (int64_t)blockIdx.x * D * D;
+    for (int e = threadIdx.x; e < D * D; e += GRAM_THREADS) {
+        const int r = e / D, c = e % D;
+        out[e] = (r / 32) <= (c / 32) ? red[r * D + c] : red[c * D + r];
+    }
+}
+
 // Stage 2: slice y of gridDim.y adds the partials b = y, y + gridDim.y, ... in fp64.
 template <int D>
 __global__ __launch_bounds__(256) void gramian_slice_kernel(const float *__restrict__ partials, int nblocks,
@@ -125,8 +239,13 @@ __global__ __launch_bounds__(256) void gramian_reduce_kernel(const double *__res
     G[e] = (float)s;
 }
 
-template <int D> static int gramian_blocks(int64_t rows) {
-    const int64_t per_block = (int64_t)(GRAM_THREADS / 64) * Geo<D>::KS * GRAM_CHAIN;
+template <int D, bool BF16> constexpr bool gram_bf16_cores() { return BF16 && D >= 64; }
+
+template <int D, bool BF16 = false> static int gramian_blocks(int64_t rows) {
+    // rows a workgroup may take so that no accumulator sees more than GRAM_CHAIN matrix-core additions
+    // (the bf16 kernel adds twice per 32-row step)
+    const int64_t per_block = gram_bf16_cores<D, BF16>() ? (int64_t)(GRAM_THREADS / 64) * 32 * (GRAM_CHAIN / 2)
+                                                         : (int64_t)(GRAM_THREADS / 64) * Geo<D>::KS * GRAM_CHAIN;
     return (int)std::min<int64_t>(GRAM_MAX_BLOCKS, std::max<int64_t>(1, (rows + per_block - 1) / per_block));
 }
 
@@ -135,8 +254,12 @@ template <int D, bool BF16>
 static void gramian_enqueue(const als_table *V, float *G, void *work, int nblocks, int nslices, hipStream_t s) {
     float *partials = (float *)work;
     double *slices = (double *)((char *)work + (size_t)nblocks * D * D * sizeof(float));
-    hipLaunchKernelGGL((gramian_partial_kernel<D, BF16>), dim3(nblocks), dim3(GRAM_THREADS), 0, s, V->data, V->rows,
-                       V->ld, partials);
+    if constexpr (gram_bf16_cores<D, BF16>())
+        hipLaunchKernelGGL((gramian_bf16_kernel<D>), dim3(nblocks), dim3(GRAM_THREADS), 0, s, (const uint16_t *)V->data,
+                           V->rows, V->ld, partials);
+    else
+        hipLaunchKernelGGL((gramian_partial_kernel<D, BF16>), dim3(nblocks), dim3(GRAM_THREADS), 0, s, V->data, V->rows,
+                           V->ld, partials);
     hipLaunchKernelGGL((gramian_slice_kernel<D>), dim3((D * D + 255) / 256, nslices), dim3(256), 0, s,
                        (const float *)partials, nblocks, slices);
     hipLaunchKernelGGL((gramian_reduce_kernel<D>), dim3((D * D + 255) / 256), dim3(256), 0, s,
@@ -145,7 +268,7 @@ static void gramian_enqueue(const als_table *V, float *G, void *work, int nblock
 
 template <int D, bool BF16>
 static als_status gramian_typed(als_ctx *ctx, const als_table *V, float *G, hipStream_t s) {
-    const int nblocks = gramian_blocks<D>(V->rows);
+    const int nblocks = gramian_blocks<D, BF16>(V->rows);
     const int nslices = std::min(nblocks, GRAM_SLICES);
     als_status st = ensure(ctx, ctx->gram_partials, (size_t)nblocks * D * D * sizeof(float) +
                                                         (size_t)nslices * D * D * sizeof(double));
@@ -198,7 +321,7 @@ hipError_t gramian_static_setup(int device) {
 
 template <int D, bool BF16>
 static als_status gramian_static_typed(const als_table *V, float *G, void *work, hipStream_t s) {
-    const int nblocks = gramian_blocks<D>(V->rows);  // <= STATIC_BLOCKS: the caller has checked the row count
+    const int nblocks = gramian_blocks<D, BF16>(V->rows);  // <= STATIC_BLOCKS: the caller has checked the row count
     gramian_enqueue<D, BF16>(V, G, work, nblocks, std::min(nblocks, STATIC_SLICES), s);
     return hipGetLastError() == hipSuccess ? ALS_OK : ALS_EHIP;
 }

@@ -95,6 +95,115 @@ __device__ __forceinline__ void accumulate_entries(const void *__restrict__ V, i
     }
 }
 
+// ---------------------------------------------------------------------------------------------- accumulate, bf16 tables
+// The same statistics for bf16 tables with d = 64 or 128 on the bf16 matrix cores (16 times the fp32 rate;
+// bf16 x bf16 products are exact in fp32, so nothing changes numerically except the order of the sums).  A
+// step takes 32 entries: lane (m, kq) loads columns 16 c + 8 kq .. of entry m (16 bytes per piece); the
+// matrix core transposes each 32-column block by a product with a constant 0/1 selection operand (see
+// gramian_bf16_kernel: exact), the packed results are the K-contiguous operands (K = the step's entries) of
+// the block products V_I^T V_I.  Every wavefront gathers and transposes all entries but owns only the block
+// pairs p with p % 4 == wave of the upper block triangle (ten pairs at d = 128, three at d = 64), so that it
+// carries at most three accumulator tiles.  b = sum y v is formed by wavefront 0 from the transposed fp32
+// values.  On return acc[p / 4] holds pair p = (gi, gj): element v of lane (m, kq) is entry
+// (32 gi + 8 (v / 4) + 4 kq + v % 4, 32 gj + m); lanes with kq == 0 of wavefront 0 hold b[32 g + m] in bsum[g].
+template <int D> struct BlockPairs {
+    static constexpr int NB = D / 32, COUNT = NB * (NB + 1) / 2;
+    static constexpr int first(int p) {  // pairs in the order (0,0) (0,1) .. (0,NB-1) (1,1) ..
+        int g = 0;
+        while (p >= NB - g) {
+            p -= NB - g;
+            ++g;
+        }
+        return g;
+    }
+    static constexpr int second(int p) {
+        int g = 0;
+        while (p >= NB - g) {
+            p -= NB - g;
+            ++g;
+        }
+        return g + p;
+    }
+};
+
+template <int D>
+__device__ __forceinline__ void accumulate_entries_bf16(const uint16_t *__restrict__ V, int64_t ld,
+                                                        const int32_t *__restrict__ indices,
+                                                        const float *__restrict__ values, int64_t begin, int64_t end,
+                                                        int wave, floatx16 (&acc)[3], float (&bsum)[4]) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    using BP = BlockPairs<D>;
+    constexpr int NB = D / 32, NCH = D / 16;
+    const int lane = opaque_tid() & 63, m = lane & 31, kq = lane >> 5;
+    const uint32_t ld32 = (uint32_t)ld;
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    bf16x8 sel[2];  // selection operands: sel[h] has a one at (k, 16 h + k)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        u32x4 w = {0u, 0u, 0u, 0u};
+        const int k = m - 16 * h - 8 * kq;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (k == e) w[e / 2] = (e & 1) ? 0x3F800000u : 0x00003F80u;
+        sel[h] = __builtin_bit_cast(bf16x8, w);
+    }
+    for (int64_t base = begin; base < end; base += 64) {
+        const int64_t p = base + lane;
+        const int myidx = p < end ? indices[p] : -1;
+        const float myy = p < end ? (values ? values[p] : 1.f) : 0.f;
+        const int cnt = (int)((end - base) < 64 ? (end - base) : 64);
+        for (int s0 = 0; s0 < cnt; s0 += 32) {
+            const int idx = __shfl(myidx, s0 + m);
+            u32x4 raw[NCH];
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) raw[c] = u32x4{0u, 0u, 0u, 0u};
+            if (idx >= 0) {
+                const uint16_t *row = V + (int64_t)((uint64_t)(uint32_t)idx * ld32) + 8 * kq;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) raw[c] = *(const u32x4 *)(row + 16 * c);
+            }
+            bf16x8 op[NB][2];
+#pragma unroll
+            for (int g = 0; g < NB; ++g) {
+                floatx16 t;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) t[v] = 0.f;
+                t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw[2 * g]), sel[0], t, 0, 0, 0);
+                t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw[2 * g + 1]), sel[1], t, 0, 0, 0);
+                // t[v] = V[entry s0 + 8 (v / 4) + 4 kq + v % 4][32 g + m]
+#pragma unroll
+                for (int x = 0; x < 2; ++x) {
+                    const u32x4 w = {__builtin_amdgcn_perm(__float_as_uint(t[8 * x + 1]), __float_as_uint(t[8 * x + 0]), 0x07060302u),
+                                     __builtin_amdgcn_perm(__float_as_uint(t[8 * x + 3]), __float_as_uint(t[8 * x + 2]), 0x07060302u),
+                                     __builtin_amdgcn_perm(__float_as_uint(t[8 * x + 5]), __float_as_uint(t[8 * x + 4]), 0x07060302u),
+                                     __builtin_amdgcn_perm(__float_as_uint(t[8 * x + 7]), __float_as_uint(t[8 * x + 6]), 0x07060302u)};
+                    op[g][x] = __builtin_bit_cast(bf16x8, w);
+                }
+                if (wave_s == 0) {  // scalar branch: the right-hand side rides in wavefront 0
+                    if (values) {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) bsum[g] += __shfl(myy, s0 + 8 * (v >> 2) + 4 * kq + (v & 3)) * t[v];
+                    } else {  // y = 1; slots without an entry hold zeros
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) bsum[g] += t[v];
+                    }
+                }
+            }
+            static_for<0, BP::COUNT>([&](auto pp) {
+                constexpr int pr = decltype(pp)::value, gi = BP::first(pr), gj = BP::second(pr);
+                if (wave_s == pr % 4) {
+                    acc[pr / 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[gi][0], op[gj][0], acc[pr / 4], 0, 0, 0);
+                    acc[pr / 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[gi][1], op[gj][1], acc[pr / 4], 0, 0, 0);
+                }
+            });
+        }
+    }
+    if (wave_s == 0) {
+#pragma unroll
+        for (int g = 0; g < NB; ++g) bsum[g] += __shfl_xor(bsum[g], 32);
+    }
+}
+
 // Sum bsum over the KS lanes that hold the same columns; afterwards lanes with kk == 0 hold b.
 template <int D> __device__ __forceinline__ void fold_b(float (&bsum)[Geo<D>::NC]) {
     constexpr int TM = Geo<D>::TM, KS = Geo<D>::KS, NC = Geo<D>::NC;
@@ -268,30 +377,66 @@ __device__ __forceinline__ bool primal_step(
         end = segs[item].end;
     }
 
-    acc_t acc[NC];
+    // The statistics are accumulated in one of two register layouts (fp32 matrix cores: tile-row `wave` of the
+    // column-interleaved tiles; bf16 tables with d >= 64: block pairs of the upper block triangle, see
+    // accumulate_entries_bf16) and handed, element by element, to whatever wants them: deliver(put, put_b)
+    // calls put(r, c, value) for entries of V_I^T V_I - every (r, c) with c <= r at least once, possibly also
+    // the mirror (c, r) - and put_b(c, value) for the entries of b.
+    constexpr bool CORES16 = BF16 && D >= 64;
+    acc_t acc[CORES16 ? 1 : NC];
+    floatx16 acc16[CORES16 ? 3 : 1];
     float bsum[NC];
 #pragma unroll
-    for (int j = 0; j < NC; ++j) {
-        bsum[j] = 0.f;
+    for (int j = 0; j < NC; ++j) bsum[j] = 0.f;
+    if constexpr (CORES16) {
 #pragma unroll
-        for (int v = 0; v < ACC; ++v) acc[j][v] = 0.f;
-    }
-    accumulate_entries<D, BF16>(V, ldv, indices, values, begin, end, wave, acc, bsum);
-    fold_b<D>(bsum);
-
-    if constexpr (MODE == MODE_SEGMENT) {
-        float *out = partials + item * (int64_t)(D * D + D);
+        for (int j = 0; j < 3; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc16[j][v] = 0.f;
+        accumulate_entries_bf16<D>((const uint16_t *)V, ldv, indices, values, begin, end, wave, acc16, bsum);
+    } else {
 #pragma unroll
         for (int j = 0; j < NC; ++j)
 #pragma unroll
-            for (int v = 0; v < ACC; ++v) {
-                const int r = NC * acc_row<D>(v, lane) + wave, c = NC * m + j;
-                out[r * D + c] = acc[j][v];
-            }
-        if (wave == 0 && kk == 0) {
+            for (int v = 0; v < ACC; ++v) acc[j][v] = 0.f;
+        accumulate_entries<D, BF16>(V, ldv, indices, values, begin, end, wave, acc, bsum);
+        fold_b<D>(bsum);
+    }
+    auto deliver = [&](auto &&put, auto &&put_b) {
+        if constexpr (CORES16) {
+            using BP = BlockPairs<D>;
+            const int m32 = lane & 31, kq = lane >> 5;
+            const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+            static_for<0, BP::COUNT>([&](auto pp) {
+                constexpr int pr = decltype(pp)::value, gi = BP::first(pr), gj = BP::second(pr);
+                if (wave_s == pr % 4) {
 #pragma unroll
-            for (int j = 0; j < NC; ++j) out[D * D + NC * m + j] = bsum[j];
+                    for (int v = 0; v < 16; ++v) {
+                        const int r = 32 * gi + 8 * (v >> 2) + 4 * kq + (v & 3), c = 32 * gj + m32;
+                        put(r, c, acc16[pr / 4][v]);
+                        if constexpr (gi != gj) put(c, r, acc16[pr / 4][v]);
+                    }
+                }
+            });
+            if (wave_s == 0 && kq == 0) {
+#pragma unroll
+                for (int g = 0; g < D / 32; ++g) put_b(32 * g + m32, bsum[g]);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NC; ++j)
+#pragma unroll
+                for (int v = 0; v < ACC; ++v) put(NC * acc_row<D>(v, lane) + wave, NC * m + j, acc[j][v]);
+            if (wave == 0 && kk == 0) {
+#pragma unroll
+                for (int j = 0; j < NC; ++j) put_b(NC * m + j, bsum[j]);
+            }
         }
+    };
+
+    if constexpr (MODE == MODE_SEGMENT) {
+        float *out = partials + item * (int64_t)(D * D + D);
+        deliver([&](int r, int c, float v) { out[r * D + c] = v; }, [&](int c, float v) { out[D * D + c] = v; });
         (void)last;
         return true;
     } else {
@@ -299,18 +444,11 @@ __device__ __forceinline__ bool primal_step(
             if (solver == ALS_SOLVER_DIRECT) {  // uniform for the launch
                 // lower triangle of A = alpha*G + lambda*I + V_I^T V_I, packed, then one wavefront solves
                 float *tri = lds, *rhs = lds + Packed<D>::OFF_RHS;
-#pragma unroll
-                for (int j = 0; j < NC; ++j)
-#pragma unroll
-                    for (int v = 0; v < ACC; ++v) {
-                        const int r = NC * acc_row<D>(v, lane) + wave, c = NC * m + j;
-                        if (c <= r)
-                            tri[tri_row(r) + c] = acc[j][v] + alpha * G[r * D + c] + (r == c ? lambda : 0.f);
-                    }
-                if (wave == 0 && kk == 0) {
-#pragma unroll
-                    for (int j = 0; j < NC; ++j) rhs[NC * m + j] = bsum[j];
-                }
+                deliver(
+                    [&](int r, int c, float v) {
+                        if (c <= r) tri[tri_row(r) + c] = v + alpha * G[r * D + c] + (r == c ? lambda : 0.f);
+                    },
+                    [&](int c, float v) { rhs[c] = v; });
                 __syncthreads();
                 // scalar test: the solver must not sit in (what looks like) divergent control flow
                 if (__builtin_amdgcn_readfirstlane(wave) != 0) {
@@ -323,17 +461,8 @@ __device__ __forceinline__ bool primal_step(
             }
         }
         // A = alpha*G + lambda*I + V_I^T V_I into LDS (entry (r,c) at a[c*LD + r])
-#pragma unroll
-        for (int j = 0; j < NC; ++j)
-#pragma unroll
-            for (int v = 0; v < ACC; ++v) {
-                const int r = NC * acc_row<D>(v, lane) + wave, c = NC * m + j;
-                a[c * LD + r] = acc[j][v] + alpha * G[r * D + c] + (r == c ? lambda : 0.f);
-            }
-        if (wave == 0 && kk == 0) {
-#pragma unroll
-            for (int j = 0; j < NC; ++j) bvec[NC * m + j] = bsum[j];
-        }
+        deliver([&](int r, int c, float v) { a[c * LD + r] = v + alpha * G[r * D + c] + (r == c ? lambda : 0.f); },
+                [&](int c, float v) { bvec[c] = v; });
         if (solver == ALS_SOLVER_CG) {  // warm start from the row's current content
             for (int c = opaque_tid(); c < D; c += Team<D>::THREADS) aux[2 * D + c] = load_elem<BF16>(X, u * ldx + c);
         }

@@ -24,11 +24,14 @@ def ctx(gpu_device):
     c.close()
 
 
-@pytest.mark.parametrize("kind,rows", [("c2", 40000), ("c3", 60000), ("c4", 80000), ("c5", 40000)])
-def test_scaled_configuration_one_epoch(ctx, gpu_device, kind, rows):
-    """One full epoch (both halves, both Gramians) and the loss, every row compared."""
-    say(f"scaled {kind} rows={rows}")
-    p = make_problem(kind, rows=rows, cols=rows)
+@pytest.mark.parametrize("kind,rows,dtype", [("c2", 40000, None), ("c3", 60000, None), ("c4", 80000, None),
+                                             ("c5", 40000, None), ("c2", 40000, "bf16"), ("c3", 60000, "bf16"),
+                                             ("c4", 80000, "bf16")])
+def test_scaled_configuration_one_epoch(ctx, gpu_device, kind, rows, dtype):
+    """One full epoch (both halves, both Gramians) and the loss, every row compared; configurations 2-4 also with
+    bf16-stored tables (the precision policy of the paper's Section 4.4 on their shapes)."""
+    say(f"scaled {kind} rows={rows} dtype={dtype or 'as configured'}")
+    p = make_problem(kind, rows=rows, cols=rows, dtype=dtype)
     Y, Yt = to_dev(p, gpu_device)
     W, H = p.W0.to(gpu_device), p.H0.to(gpu_device)
     prm = als.make_params(p.alpha, p.lam)

@@ -227,7 +227,7 @@ def main():
     sd = stages[dom]
     per_launch = sd["algorithmic_per_epoch"] / max(sd["launches_per_epoch"], 1.0)
     roof = {"kernel": sd["kernel"], "bound": sd["bound"], "achieved": sd["achieved"], "peak": sd["peak"], "unit": sd["unit"],
-            "frac": sd["frac"], "traffic": None if args.rows else measured_traffic(args.workload, sd["kernel"]),
+            "frac": sd["frac"], "traffic": measured_traffic(f"{args.workload}@{args.rows}" if args.rows else args.workload, sd["kernel"]),
             "avg_launch_ms": sd["ms_per_epoch"] / max(sd["launches_per_epoch"], 1.0), "launches": sd["launches_per_epoch"] * nsteps,
             "algorithmic_per_launch": per_launch,
             "share_of_epoch": sd["ms_per_epoch"] / ms_per_step}

@@ -5,6 +5,10 @@
         per kernel: dispatches, total / average / min / max duration
     python profile_summary.py counters <results.db> [--all]
         per kernel and counter of a --pmc run: dispatches, average per dispatch, total
+    python profile_summary.py mfma <results.db>
+        matrix-core busy share per kernel from a run with --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_MFMA
+        GRBM_GUI_ACTIVE (...): busy cycles summed over the chip / (GRBM_GUI_ACTIVE summed over the 8 XCDs x 128
+        SIMDs per XCD), i.e. the share of all SIMD cycles in which a matrix instruction executes
     python profile_summary.py traffic <workload> <fetch.db> <write.db> [--json FILE]
         HBM bytes per launch of every kernel from a FETCH_SIZE run and a WRITE_SIZE run, each counter scaled
         by what it reads for the library's plain copy kernel (als::copy_probe_kernel, which both runs must
@@ -62,6 +66,23 @@ def counters(db: str, only_lib: bool = True) -> str:
     return "\n".join(out)
 
 
+def mfma(db: str) -> str:
+    rows = {}
+    for name, counter, calls, _avg, total, us in _counter_rows(db):
+        rows.setdefault(short_name(name), {})[counter] = (calls, total, us)
+    out = [f"{'kernel':64s} {'dispatches':>10} {'avg_us':>10} {'MFMA instr/disp':>16} {'MFMA busy % of SIMD cycles':>28}"]
+    order = sorted(rows, key=lambda n: -rows[n].get("SQ_VALU_MFMA_BUSY_CYCLES", (0, 0, 0))[1])
+    for name in order:
+        c = rows[name]
+        if "GRBM_GUI_ACTIVE" not in c or "SQ_VALU_MFMA_BUSY_CYCLES" not in c:
+            continue
+        disp = max(1, c["GRBM_GUI_ACTIVE"][0] // 8)  # one GRBM sample per XCD and dispatch
+        busy = 100.0 * c["SQ_VALU_MFMA_BUSY_CYCLES"][1] / (c["GRBM_GUI_ACTIVE"][1] * 128.0)
+        insts = c.get("SQ_INSTS_MFMA", (0, 0.0, 0))[1] / disp
+        out.append(f"{name[:64]:64s} {disp:10d} {c['GRBM_GUI_ACTIVE'][2]:10.1f} {insts:16.3e} {busy:28.1f}")
+    return "\n".join(out)
+
+
 def traffic(workload: str, fetch_db: str, write_db: str, json_path: str | None = None) -> str:
     fetch = {short_name(r[0]): r for r in _counter_rows(fetch_db) if r[1] == "FETCH_SIZE"}
     write = {short_name(r[0]): r for r in _counter_rows(write_db) if r[1] == "WRITE_SIZE"}
@@ -105,6 +126,8 @@ if __name__ == "__main__":
         print(trace(a[1], only_lib))
     elif len(a) >= 2 and a[0] == "counters":
         print(counters(a[1], only_lib))
+    elif len(a) >= 2 and a[0] == "mfma":
+        print(mfma(a[1]))
     elif len(a) >= 4 and a[0] == "traffic":
         jp = a[a.index("--json") + 1] if "--json" in a else None
         print(traffic(a[1], a[2], a[3], jp))

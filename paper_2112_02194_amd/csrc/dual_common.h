@@ -105,9 +105,78 @@ __device__ __forceinline__ floatx4 split_mfma(const SplitOperand &a, const Split
     return acc;
 }
 
+// ---------------------------------------------------------------------------------------------- the table Z
+// The row kernels read the transformed table Z = V L^-T either as fp32 (fp32 tables) or as bf16 (ZB: bf16
+// tables with d >= 32, where Z is rounded once to the tables' own element type).  A lane (a, q) of a
+// 16-entry tile holds an entry's row as 16-byte pieces: piece j covers columns (4 j + q) * EPP .. with EPP = 4
+// (fp32) or 8 (bf16) elements, so that a bf16 piece is, as loaded, one operand of v_mfma_f32_16x16x32_bf16.
+template <bool ZB> struct ZT {
+    static constexpr int ES = ZB ? 2 : 4, EPP = 16 / ES;
+};
+template <int D, bool ZB> constexpr int z_pieces() { return D * ZT<ZB>::ES / 64; }
+
+template <int D, bool ZB> __device__ __forceinline__ float4 load_piece(const void *Z, int64_t id, int j, int q) {
+    return *(const float4 *)((const char *)Z + (id * D + (4 * j + q) * ZT<ZB>::EPP) * ZT<ZB>::ES);
+}
+
+// CPL adjacent columns starting at column CPL * lane of the row stored at `row` (global memory or LDS), as fp32
+template <bool ZB, int CPL> __device__ __forceinline__ void row_cols(const void *row, int lane, float (&c)[CPL]) {
+    if constexpr (!ZB) {
+        if constexpr (CPL == 2) {
+            const float2 v = *(const float2 *)((const float *)row + 2 * lane);
+            c[0] = v.x;
+            c[1] = v.y;
+        } else {
+            c[0] = ((const float *)row)[lane];
+        }
+    } else {
+        if constexpr (CPL == 2) {
+            const uint32_t v = ((const uint32_t *)row)[lane];
+            c[0] = __uint_as_float(v << 16);
+            c[1] = __uint_as_float(v & 0xffff0000u);
+        } else {
+            c[0] = __uint_as_float((uint32_t)((const uint16_t *)row)[lane] << 16);
+        }
+    }
+}
+
+// acc += A B^T over all columns of two entries' bf16 rows held as NP pieces each
+template <int NP> __device__ __forceinline__ floatx4 mfma_pieces_bf16(const float4 (&A)[NP], const float4 (&B)[NP], floatx4 acc) {
+#pragma unroll
+    for (int j = 0; j < NP; ++j)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[j]), __builtin_bit_cast(bf16x8, B[j]), acc, 0, 0, 0);
+    return acc;
+}
+
+// A lane's share of a 16-entry tile (d >= 32) ready for the S products: the bf16 pieces as loaded, or the hi/lo
+// operands cut from fp32 pieces.
+template <int D, bool ZB> struct TileOperand {
+    static constexpr int N = D / 32;
+    typename std::conditional<ZB, float4, SplitOperand>::type v[N];
+    __device__ __forceinline__ void set(const float4 (&raw)[z_pieces<D, ZB>()]) {
+#pragma unroll
+        for (int h = 0; h < N; ++h) {
+            if constexpr (ZB) v[h] = raw[h];
+            else v[h] = split_operand(raw[2 * h], raw[2 * h + 1]);
+        }
+    }
+};
+template <int D, bool ZB>
+__device__ __forceinline__ floatx4 tile_product(const TileOperand<D, ZB> &A, const TileOperand<D, ZB> &B, floatx4 acc) {
+#pragma unroll
+    for (int h = 0; h < D / 32; ++h) {
+        if constexpr (ZB)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A.v[h]), __builtin_bit_cast(bf16x8, B.v[h]), acc, 0, 0, 0);
+        else
+            acc = split_mfma(A.v[h], B.v[h], acc);
+    }
+    return acc;
+}
+
 // per-class launchers, one translation unit each (they compile in parallel)
 // (`count_dev`: device address of the list's length; `g`: see StepGrid)
-void launch_dual_k16(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                     const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s);
+// `zb16`: Z is stored as bf16
+void launch_dual_k16(int d, const als_csr *Y, const void *Z, bool zb16, float *R, int64_t ldr, int64_t r0,
+                     const int32_t *list, const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s);
 
 }  // namespace als

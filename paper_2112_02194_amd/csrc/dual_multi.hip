@@ -27,15 +27,15 @@ template <int D, int M> struct MultiCfg {
 };
 
 // One step: the four rows list[4 blk .. 4 blk + 3] (blk * 4 < count).
-template <int D, int M>
+template <int D, int M, bool ZB>
 __device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indptr,
                                                 const int32_t *__restrict__ indices,
-                                                const float *__restrict__ values, const float *__restrict__ Z,
+                                                const float *__restrict__ values, const void *__restrict__ Z,
                                                 float *__restrict__ R, int64_t ldr, int64_t r0,
                                                 const int32_t *__restrict__ list, int count,
                                                 int32_t *__restrict__ err_flag, int blk, float *lds) {
     using C = MultiCfg<D, M>;
-    constexpr int K = C::K, TRI = C::TRI, NJ = D / 16, CPL = D >= 128 ? 2 : 1;
+    constexpr int K = C::K, TRI = C::TRI, NJ = z_pieces<D, ZB>(), CPL = D >= 128 ? 2 : 1;
     float *tri = lds, *tbuf = lds + C::OFF_T;
     int32_t *ids = (int32_t *)(lds + C::OFF_ID);
     // Accesses to the packed triangle are never put under a lane-dependent branch (a branch per element costs
@@ -96,11 +96,11 @@ __device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indp
             for (int j = 0; j < NJ; ++j) z[t][j] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (id >= 0) {  // one masked region per tile, not one per load
 #pragma unroll
-                for (int j = 0; j < NJ; ++j) z[t][j] = *(const float4 *)(Z + (int64_t)id * D + (4 * j + q) * 4);
+                for (int j = 0; j < NJ; ++j) z[t][j] = load_piece<D, ZB>(Z, id, j, q);
             }
         }
         SplitOperand zs[M][NJ / 2 > 0 ? NJ / 2 : 1];
-        if constexpr (NJ >= 2) {
+        if constexpr (!ZB && NJ >= 2) {
 #pragma unroll
             for (int t = 0; t < M; ++t)
 #pragma unroll
@@ -112,7 +112,9 @@ __device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indp
 #pragma unroll
             for (int t2 = 0; t2 <= t1; ++t2) {
                 floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
-                if constexpr (NJ >= 2) {
+                if constexpr (ZB) {  // bf16 rows are matrix-core operands as loaded
+                    acc = mfma_pieces_bf16<NJ>(z[t2], z[t1], acc);
+                } else if constexpr (NJ >= 2) {
 #pragma unroll
                     for (int h = 0; h < NJ / 2; ++h) acc = split_mfma(zs[t2][h], zs[t1][h], acc);
                 } else {
@@ -242,7 +244,7 @@ __device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indp
     {
         float r0v[4] = {0.f, 0.f, 0.f, 0.f}, r1v[4] = {0.f, 0.f, 0.f, 0.f};
         const bool col_ok = lane * CPL < D;
-        const float *zcol = Z + (col_ok ? CPL * lane : 0);  // lanes without a column (d = 32) read column 0
+        const int zlane = col_ok ? lane : 0;  // lanes without a column (d = 32) read column 0
         // entries per row and round (measured: 16 eight-byte loads in flight are best at d = 128, 32 four-byte
         // loads at d <= 64)
         constexpr int EPR = CPL == 2 ? 4 : 8, NQ = EPR / 4;
@@ -257,7 +259,7 @@ __device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indp
                     idq[p][h] = *(const int4 *)(ids + p * K + e0 + 4 * h);
                     teq[p][h] = *(const float4 *)(tbuf + p * K + e0 + 4 * h);
                 }
-            float2 zz[4][EPR];
+            float zz[4][EPR][CPL];
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
                 if (e0 < k[p]) {  // uniform
@@ -266,9 +268,7 @@ __device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indp
                         const int id[4] = {idq[p][h].x, idq[p][h].y, idq[p][h].z, idq[p][h].w};
 #pragma unroll
                         for (int x = 0; x < 4; ++x) {
-                            const float *zr = zcol + (int64_t)id[x] * D;
-                            if constexpr (CPL == 2) zz[p][4 * h + x] = *(const float2 *)zr;
-                            else zz[p][4 * h + x] = make_float2(zr[0], 0.f);
+                            row_cols<ZB, CPL>((const char *)Z + (int64_t)id[x] * D * ZT<ZB>::ES, zlane, zz[p][4 * h + x]);
                         }
                     }
                 }
@@ -281,8 +281,8 @@ __device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indp
                         const float te[4] = {teq[p][h].x, teq[p][h].y, teq[p][h].z, teq[p][h].w};
 #pragma unroll
                         for (int x = 0; x < 4; ++x) {
-                            r0v[p] += te[x] * zz[p][4 * h + x].x;
-                            r1v[p] += te[x] * zz[p][4 * h + x].y;
+                            r0v[p] += te[x] * zz[p][4 * h + x][0];
+                            if constexpr (CPL == 2) r1v[p] += te[x] * zz[p][4 * h + x][1];
                         }
                     }
                 }
@@ -302,11 +302,11 @@ __device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indp
 // length the host knows from the previous call).  LOOP = true: grid-stride walk from first_blk to the end of
 // the list, correct for any grid size (the length is only known on the device); the step inlined into a
 // loop needs about twice the registers, so this form only serves what the first form did not cover.
-template <int D, int M, bool LOOP>
+template <int D, int M, bool ZB, bool LOOP>
 __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restrict__ indptr,
                                                         const int32_t *__restrict__ indices,
                                                         const float *__restrict__ values,
-                                                        const float *__restrict__ Z, float *__restrict__ R,
+                                                        const void *__restrict__ Z, float *__restrict__ R,
                                                         int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
                                                         const int32_t *__restrict__ count_ptr, int first_blk,
                                                         int32_t *__restrict__ err_flag) {
@@ -314,36 +314,39 @@ __global__ __launch_bounds__(64) void dual_multi_kernel(const int64_t *__restric
     const int count = *count_ptr;
     int blk = first_blk + blockIdx.x;
     if constexpr (!LOOP) {
-        if (blk * 4 < count) dual_multi_step<D, M>(indptr, indices, values, Z, R, ldr, r0, list, count, err_flag, blk, lds);
+        if (blk * 4 < count) dual_multi_step<D, M, ZB>(indptr, indices, values, Z, R, ldr, r0, list, count, err_flag, blk, lds);
     } else {
         for (; blk * 4 < count; blk += gridDim.x) {
-            dual_multi_step<D, M>(opaque(indptr), opaque(indices), opaque(values), opaque(Z), opaque(R), opaque(ldr),
+            dual_multi_step<D, M, ZB>(opaque(indptr), opaque(indices), opaque(values), opaque(Z), opaque(R), opaque(ldr),
                                   opaque(r0), opaque(list), opaque(count), opaque(err_flag), blk, opaque(lds));
             wave_sync();  // the next step reuses the LDS buffers
         }
     }
 }
 
-template <int D>
-static void launch_multi_typed(const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0,
-                               const int32_t *list, const int32_t *count_dev, StepGrid g, int32_t *err,
-                               hipStream_t s) {
+template <int D, bool ZB>
+static void launch_multi_typed(const als_csr *Y, const void *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
+                               const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
     using C = MultiCfg<D, MULTI_M>;
     if (g.known > 0)
-        hipLaunchKernelGGL((dual_multi_kernel<D, MULTI_M, false>), dim3(g.known), dim3(64), C::LDS_FLOATS * sizeof(float),
-                           s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count_dev, 0, err);
+        hipLaunchKernelGGL((dual_multi_kernel<D, MULTI_M, ZB, false>), dim3(g.known), dim3(64),
+                           C::LDS_FLOATS * sizeof(float), s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list,
+                           count_dev, 0, err);
     if (g.rest > 0)
-        hipLaunchKernelGGL((dual_multi_kernel<D, MULTI_M, true>), dim3(g.rest), dim3(64), C::LDS_FLOATS * sizeof(float),
-                           s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count_dev, (int)g.known, err);
+        hipLaunchKernelGGL((dual_multi_kernel<D, MULTI_M, ZB, true>), dim3(g.rest), dim3(64),
+                           C::LDS_FLOATS * sizeof(float), s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list,
+                           count_dev, (int)g.known, err);
 }
 
-void launch_dual_multi2(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                        const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
-    switch (d) {  // the dual form stops at k = d
-        case 32: launch_multi_typed<32>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
-        case 64: launch_multi_typed<64>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
-        case 128: launch_multi_typed<128>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
-    }
+void launch_dual_multi2(int d, const als_csr *Y, const void *Z, bool zb16, float *R, int64_t ldr, int64_t r0,
+                        const int32_t *list, const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
+#define ALS_MULTI_CASE(dd)                                                                       \
+    case dd:                                                                                     \
+        if (zb16) launch_multi_typed<dd, true>(Y, Z, R, ldr, r0, list, count_dev, g, err, s);    \
+        else launch_multi_typed<dd, false>(Y, Z, R, ldr, r0, list, count_dev, g, err, s);        \
+        break;
+    switch (d) { ALS_MULTI_CASE(32) ALS_MULTI_CASE(64) ALS_MULTI_CASE(128) }  // the dual form stops at k = d
+#undef ALS_MULTI_CASE
 }
 
 }  // namespace als

@@ -23,16 +23,16 @@
 
 namespace als {
 
-void launch_dual_small4(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                        const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s);
-void launch_dual_small8(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                        const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s);
-void launch_dual_multi2(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                        const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s);
-#define ALS_DECL_WIDE(kt)                                                                                         \
-    als_status launch_dual_wide##kt(als_ctx *ctx, int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, \
-                                    int64_t r0, const int32_t *list, const int32_t *count_dev, StepGrid g,        \
-                                    int32_t *err, hipStream_t s);
+void launch_dual_small4(int d, const als_csr *Y, const void *Z, bool zb16, float *R, int64_t ldr, int64_t r0,
+                        const int32_t *list, const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s);
+void launch_dual_small8(int d, const als_csr *Y, const void *Z, bool zb16, float *R, int64_t ldr, int64_t r0,
+                        const int32_t *list, const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s);
+void launch_dual_multi2(int d, const als_csr *Y, const void *Z, bool zb16, float *R, int64_t ldr, int64_t r0,
+                        const int32_t *list, const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s);
+#define ALS_DECL_WIDE(kt)                                                                                          \
+    als_status launch_dual_wide##kt(als_ctx *ctx, int d, const als_csr *Y, const void *Z, bool zb16, float *R,     \
+                                    int64_t ldr, int64_t r0, const int32_t *list, const int32_t *count_dev,        \
+                                    StepGrid g, int32_t *err, hipStream_t s);
 ALS_DECL_WIDE(3) ALS_DECL_WIDE(4) ALS_DECL_WIDE(5) ALS_DECL_WIDE(6) ALS_DECL_WIDE(7) ALS_DECL_WIDE(8)
 #undef ALS_DECL_WIDE
 
@@ -173,32 +173,152 @@ __global__ __launch_bounds__(256) void transform_kernel(const void *In, int64_t 
     }
 }
 
+// ---------------------------------------------------------------------------------------------- transform, bf16 output
+// The same product for bf16 tables (d >= 32), where both passes write bf16 (Z and X): on the bf16 matrix cores,
+// which turns the pass from matrix-core-bound (fp32 instruction) into HBM-bound.  M is cut once per workgroup
+// into hi = bf16(M) and lo = bf16(M - hi) (LDS, transposed); bf16 input rows are exact operands (two products
+// per step: x hi + x lo), fp32 input rows (the dual solutions R) are cut the same way (three products,
+// dropping lo lo).  The error of the cut, 2^-17 relative, is far below the bf16 rounding of the output.
+// The roles of the operands are swapped against transform_kernel: the matrix supplies the M dimension
+// (output columns) and the table rows the N dimension, so that a lane ends up with 16 consecutive output
+// columns of ONE table row (the output columns are assigned to the instruction's row index in the order
+// that makes them consecutive) and stores them as two 16-byte pieces.
+template <int D> struct Xf16Cfg {
+    static constexpr int MLD = D + 8;  // bf16 elements per LDS row (rows stay 16-byte aligned)
+    static constexpr size_t LDS_BYTES = (size_t)2 * D * MLD * sizeof(uint16_t);
+};
+
+template <int D, bool IN_BF16, bool UPPER>
+__global__ __launch_bounds__(256, 2) void transform16_kernel(const void *__restrict__ In, int64_t ldi,
+                                                          uint16_t *__restrict__ Out, int64_t ldo,
+                                                          const float *__restrict__ M, int64_t r0, int64_t r1,
+                                                          const int64_t *__restrict__ indptr, int64_t k_max) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float floatx2 __attribute__((ext_vector_type(2)));
+    constexpr int MLD = Xf16Cfg<D>::MLD, NKB = D / 16, NJB = D / 32;
+    extern __shared__ uint16_t mt[];  // hi: mt[c * MLD + j] = bf16(M[j][c]); lo: the same at offset D * MLD
+    auto rne = [](float x, float y) { return __builtin_bit_cast(uint32_t, __builtin_convertvector((floatx2){x, y}, bf16x2)); };
+    for (int e = threadIdx.x; e < D * D; e += 256) {
+        const int j = e / D, c = e % D;
+        const float v = M[e];
+        const uint32_t h = rne(v, 0.f) & 0xffffu;
+        mt[c * MLD + j] = (uint16_t)h;
+        mt[D * MLD + c * MLD + j] = (uint16_t)(rne(v - __uint_as_float(h << 16), 0.f) & 0xffffu);
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 31, kq = lane >> 5;
+    // output column (inside a block of 32) that this lane supplies as row n of the matrix operand
+    const int pi = 16 * ((n >> 2) & 1) + 4 * (n >> 3) + (n & 3);
+    const int64_t ntiles = (r1 - r0 + 31) / 32;
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < ntiles; tile += nwaves) {
+        const int64_t row = r0 + tile * 32 + n;
+        bool keep = row < r1;
+        if (keep && indptr) {  // only rows solved in the dual form are written
+            const int64_t k = indptr[row + 1] - indptr[row];
+            keep = k > 0 && k <= k_max;
+        }
+        // this lane's share of its row: columns 16 kb + 8 kq .., as bf16 operands (hi and, for fp32 input, lo)
+        bf16x8 xh[NKB], xl[IN_BF16 ? 1 : NKB];
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) {
+            if constexpr (IN_BF16) {
+                u32x4 w = {0u, 0u, 0u, 0u};
+                if (row < r1) w = *(const u32x4 *)((const uint16_t *)In + row * ldi + 16 * kb + 8 * kq);
+                xh[kb] = __builtin_bit_cast(bf16x8, w);
+            } else {
+                float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                if (row < r1) {
+                    const float4 p = *(const float4 *)((const float *)In + row * ldi + 16 * kb + 8 * kq);
+                    const float4 q4 = *(const float4 *)((const float *)In + row * ldi + 16 * kb + 8 * kq + 4);
+                    x[0] = p.x; x[1] = p.y; x[2] = p.z; x[3] = p.w; x[4] = q4.x; x[5] = q4.y; x[6] = q4.z; x[7] = q4.w;
+                }
+                u32x4 h, l;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    h[w] = rne(x[2 * w], x[2 * w + 1]);
+                    l[w] = rne(x[2 * w] - __uint_as_float(h[w] << 16), x[2 * w + 1] - __uint_as_float(h[w] & 0xffff0000u));
+                }
+                xh[kb] = __builtin_bit_cast(bf16x8, h);
+                xl[kb] = __builtin_bit_cast(bf16x8, l);
+            }
+        }
+#pragma unroll
+        for (int J = 0; J < NJB; ++J) {
+            floatx16 acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+            const uint16_t *mrow = mt + (32 * J + pi) * MLD + 8 * kq;
+#pragma unroll
+            for (int kb = 0; kb < NKB; ++kb) {
+                if (UPPER ? (kb <= 2 * J + 1) : (kb >= 2 * J)) {  // compile-time after unrolling: other steps only meet zeros
+                    const bf16x8 mh = *(const bf16x8 *)(mrow + 16 * kb), ml = *(const bf16x8 *)(mrow + D * MLD + 16 * kb);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(mh, xh[kb], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ml, xh[kb], acc, 0, 0, 0);
+                    if constexpr (!IN_BF16) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(mh, xl[kb], acc, 0, 0, 0);
+                }
+            }
+            // acc[v] = Out[row][32 J + 16 kq + v]
+            if (keep) {
+                u32x4 lo4, hi4;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    lo4[w] = rne(acc[2 * w], acc[2 * w + 1]);
+                    hi4[w] = rne(acc[8 + 2 * w], acc[8 + 2 * w + 1]);
+                }
+                u32x4 *dst = (u32x4 *)(Out + row * ldo + 32 * J + 16 * kq);
+                dst[0] = lo4;
+                dst[1] = hi4;
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------- launchers
 int dual_supported_max_k(int d) { return d < 128 ? (d < 64 ? d : 64) : 128; }
+
+// bf16 tables with d >= 32: Z is stored as bf16 too (one more rounding, to the tables' own element type, of a
+// table that is only ever used to solve rows whose result is rounded to bf16 anyway; half the gather
+// traffic, and a row piece is a matrix-core operand as loaded).  At d = 16 a row is shorter than one
+// 32-column matrix-core step and Z stays fp32.
+template <int D, bool BF16> constexpr bool z_is_bf16() { return BF16 && D >= 32; }
 
 // Part 1 (needs no row classification): factorise B and build Z = V L^{-T}.
 template <int D, bool BF16>
 static als_status dual_prepare_typed(als_ctx *ctx, const als_table *V, const float *G, const als_params *prm,
                                      hipStream_t s) {
-    als_status st = ensure(ctx, ctx->ztable, (size_t)V->rows * D * sizeof(float));
+    constexpr bool ZB = z_is_bf16<D, BF16>();
+    als_status st = ensure(ctx, ctx->ztable, (size_t)V->rows * D * (ZB ? 2 : 4));
     if (st != ALS_OK) return st;
     float *Linv = (float *)((char *)ctx->small.p + SM_FACTOR), *LinvT = Linv + 128 * 128;
     int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
     constexpr size_t factor_lds = (size_t)(D * (D + 1) + D) * sizeof(double);
     static const hipError_t attr_f = hipFuncSetAttribute((const void *)factor_kernel<D>,
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)factor_lds);
-    static const hipError_t attr_t = hipFuncSetAttribute((const void *)transform_kernel<D, BF16, false, true>,
-                                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                         (int)XfCfg<D>::LDS_BYTES);  // both once per process
     ALS_HIP(ctx, attr_f);
-    ALS_HIP(ctx, attr_t);
     timer_begin(ctx, T_TRANSFORM, s);
     hipLaunchKernelGGL(factor_kernel<D>, dim3(1), dim3(256), factor_lds, s, G, prm->alpha, prm->lambda, Linv, LinvT,
                        err);
     const unsigned tblocks = (unsigned)std::min<int64_t>(1024, std::max<int64_t>(1, (V->rows + 127) / 128));
-    hipLaunchKernelGGL((transform_kernel<D, BF16, false, true>), dim3(tblocks), dim3(256), XfCfg<D>::LDS_BYTES, s, V->data, V->ld,
-                       ctx->ztable.p, (int64_t)D, (const float *)LinvT, (int64_t)0, V->rows,
-                       (const int64_t *)nullptr, (int64_t)0);
+    if constexpr (ZB) {
+        static const hipError_t attr_t = hipFuncSetAttribute((const void *)transform16_kernel<D, true, true>,
+                                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                             (int)Xf16Cfg<D>::LDS_BYTES);  // once per process
+        ALS_HIP(ctx, attr_t);
+        hipLaunchKernelGGL((transform16_kernel<D, true, true>), dim3(tblocks), dim3(256), Xf16Cfg<D>::LDS_BYTES, s, V->data,
+                           V->ld, (uint16_t *)ctx->ztable.p, (int64_t)D, (const float *)LinvT, (int64_t)0, V->rows,
+                           (const int64_t *)nullptr, (int64_t)0);
+    } else {
+        static const hipError_t attr_t = hipFuncSetAttribute((const void *)transform_kernel<D, BF16, false, true>,
+                                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                             (int)XfCfg<D>::LDS_BYTES);  // once per process
+        ALS_HIP(ctx, attr_t);
+        hipLaunchKernelGGL((transform_kernel<D, BF16, false, true>), dim3(tblocks), dim3(256), XfCfg<D>::LDS_BYTES, s,
+                           V->data, V->ld, ctx->ztable.p, (int64_t)D, (const float *)LinvT, (int64_t)0, V->rows,
+                           (const int64_t *)nullptr, (int64_t)0);
+    }
     timer_end(ctx, s);
     ALS_HIP(ctx, hipGetLastError());
     return ALS_OK;
@@ -221,7 +341,8 @@ static als_status dual_rows_typed(als_ctx *ctx, const als_csr *Y, als_table *X, 
     }
     const float *Linv = (const float *)((char *)ctx->small.p + SM_FACTOR);
     int32_t *err = (int32_t *)((char *)ctx->small.p + SM_COUNTERS) + 2;
-    const float *Z = (const float *)ctx->ztable.p;
+    const void *Z = ctx->ztable.p;
+    constexpr bool zb16 = z_is_bf16<D, BF16>();
     als_status stb = ALS_OK;
     // workgroups of class `cls` whose kernel takes `rpw` rows per step
     auto grid = [&](int cls, int rpw) {
@@ -236,27 +357,36 @@ static als_status dual_rows_typed(als_ctx *ctx, const als_csr *Y, als_table *X, 
         call;                                           \
         timer_end(ctx, s);                              \
     }
-    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 1, 1, 4, (launch_dual_multi2(D, Y, Z, R, ldr, r0, lists[1], counts_dev[1], g, err, s)))
-    ALS_TIMED_CLASS(T_DUAL_CLASS0, 0, 4, (launch_dual_k16(D, Y, Z, R, ldr, r0, lists[0], counts_dev[0], g, err, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 1, 1, 4, (launch_dual_multi2(D, Y, Z, zb16, R, ldr, r0, lists[1], counts_dev[1], g, err, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0, 0, 4, (launch_dual_k16(D, Y, Z, zb16, R, ldr, r0, lists[0], counts_dev[0], g, err, s)))
     // 5 <= k <= 8 and k <= 4: several rows per MFMA tile
-    ALS_TIMED_CLASS(T_SMALL8, 9, 8, (launch_dual_small8(D, Y, Z, R, ldr, r0, lists[9], counts_dev[9], g, err, s)))
-    ALS_TIMED_CLASS(T_SMALL4, 8, 16, (launch_dual_small4(D, Y, Z, R, ldr, r0, lists[8], counts_dev[8], g, err, s)))
-    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 2, 2, 1, (stb = launch_dual_wide3(ctx, D, Y, Z, R, ldr, r0, lists[2], counts_dev[2], g, err, s)))
-    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 3, 3, 1, (stb = launch_dual_wide4(ctx, D, Y, Z, R, ldr, r0, lists[3], counts_dev[3], g, err, s)))
-    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 4, 4, 1, (stb = launch_dual_wide5(ctx, D, Y, Z, R, ldr, r0, lists[4], counts_dev[4], g, err, s)))
-    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 5, 5, 1, (stb = launch_dual_wide6(ctx, D, Y, Z, R, ldr, r0, lists[5], counts_dev[5], g, err, s)))
-    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 6, 6, 1, (stb = launch_dual_wide7(ctx, D, Y, Z, R, ldr, r0, lists[6], counts_dev[6], g, err, s)))
-    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 7, 7, 1, (stb = launch_dual_wide8(ctx, D, Y, Z, R, ldr, r0, lists[7], counts_dev[7], g, err, s)))
+    ALS_TIMED_CLASS(T_SMALL8, 9, 8, (launch_dual_small8(D, Y, Z, zb16, R, ldr, r0, lists[9], counts_dev[9], g, err, s)))
+    ALS_TIMED_CLASS(T_SMALL4, 8, 16, (launch_dual_small4(D, Y, Z, zb16, R, ldr, r0, lists[8], counts_dev[8], g, err, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 2, 2, 1, (stb = launch_dual_wide3(ctx, D, Y, Z, zb16, R, ldr, r0, lists[2], counts_dev[2], g, err, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 3, 3, 1, (stb = launch_dual_wide4(ctx, D, Y, Z, zb16, R, ldr, r0, lists[3], counts_dev[3], g, err, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 4, 4, 1, (stb = launch_dual_wide5(ctx, D, Y, Z, zb16, R, ldr, r0, lists[4], counts_dev[4], g, err, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 5, 5, 1, (stb = launch_dual_wide6(ctx, D, Y, Z, zb16, R, ldr, r0, lists[5], counts_dev[5], g, err, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 6, 6, 1, (stb = launch_dual_wide7(ctx, D, Y, Z, zb16, R, ldr, r0, lists[6], counts_dev[6], g, err, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 7, 7, 1, (stb = launch_dual_wide8(ctx, D, Y, Z, zb16, R, ldr, r0, lists[7], counts_dev[7], g, err, s)))
 #undef ALS_TIMED_CLASS
     if (stb != ALS_OK) return stb;
-    static const hipError_t attr_x = hipFuncSetAttribute((const void *)transform_kernel<D, false, BF16, false>,
-                                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                         (int)XfCfg<D>::LDS_BYTES);  // once per process
-    ALS_HIP(ctx, attr_x);
     timer_begin(ctx, T_TRANSFORM_X, s);
     const unsigned xblocks = (unsigned)std::min<int64_t>(1024, std::max<int64_t>(1, (r1 - r0 + 127) / 128));
-    hipLaunchKernelGGL((transform_kernel<D, false, BF16, false>), dim3(xblocks), dim3(256), XfCfg<D>::LDS_BYTES, s, (const void *)R, ldr,
-                       X->data, X->ld, Linv, r0, r1, Y->indptr, (int64_t)dual_max);
+    if constexpr (zb16) {
+        static const hipError_t attr_x = hipFuncSetAttribute((const void *)transform16_kernel<D, false, false>,
+                                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                             (int)Xf16Cfg<D>::LDS_BYTES);  // once per process
+        ALS_HIP(ctx, attr_x);
+        hipLaunchKernelGGL((transform16_kernel<D, false, false>), dim3(xblocks), dim3(256), Xf16Cfg<D>::LDS_BYTES, s,
+                           (const void *)R, ldr, (uint16_t *)X->data, X->ld, Linv, r0, r1, Y->indptr, (int64_t)dual_max);
+    } else {
+        static const hipError_t attr_x = hipFuncSetAttribute((const void *)transform_kernel<D, false, BF16, false>,
+                                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                             (int)XfCfg<D>::LDS_BYTES);  // once per process
+        ALS_HIP(ctx, attr_x);
+        hipLaunchKernelGGL((transform_kernel<D, false, BF16, false>), dim3(xblocks), dim3(256), XfCfg<D>::LDS_BYTES, s,
+                           (const void *)R, ldr, X->data, X->ld, Linv, r0, r1, Y->indptr, (int64_t)dual_max);
+    }
     timer_end(ctx, s);
     ALS_HIP(ctx, hipGetLastError());
     return ALS_OK;

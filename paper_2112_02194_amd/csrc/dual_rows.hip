@@ -26,15 +26,17 @@ template <int D> struct DualCfg {
 //   2. lane i of a row's group of 16 lanes owns row i of S: right-looking Cholesky with the column
 //      broadcast by DPP inside the group, then L w = y, then L^T t = w with L read back transposed;
 //   3. r = Z_I^T t with one lane per pair of output columns, from an LDS copy of Z_I.
-template <int D>
+template <int D, bool ZB>
 __device__ __forceinline__ void dual_rows_step(const int64_t *__restrict__ indptr, const int32_t *__restrict__ indices,
-                                               const float *__restrict__ values, const float *__restrict__ Z,
+                                               const float *__restrict__ values, const void *__restrict__ Z,
                                                float *__restrict__ R, int64_t ldr, int64_t r0,
                                                const int32_t *__restrict__ list, int count,
                                                int32_t *__restrict__ err_flag, int blk, float *lds) {
     using C = DualCfg<D>;
-    constexpr int K = C::K, KT = 1, GW = C::GW, RPW = C::RPW, KP = C::KP, NJ = C::NJ, ZLD = C::ZLD;
-    float *sb = lds, *zb = lds, *tb = lds + (C::LDS_FLOATS - C::TAIL);
+    constexpr int K = C::K, KT = 1, GW = C::GW, RPW = C::RPW, KP = C::KP, NJ = z_pieces<D, ZB>();
+    constexpr int ZLDB = D * ZT<ZB>::ES + 16;  // row stride in bytes of the LDS copy of Z_I
+    float *sb = lds, *tb = lds + (C::LDS_FLOATS - C::TAIL);
+    char *zb = (char *)lds;
     const int lane = opaque_tid();
     const int a = lane & 15, q = lane >> 4;
     const int grp = lane / GW, gi = lane % GW;
@@ -83,7 +85,7 @@ __device__ __forceinline__ void dual_rows_step(const int64_t *__restrict__ indpt
         for (int j = 0; j < NJ; ++j) z[p][0][j] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (idx[p] >= 0) {  // one masked region per tile, not one per load
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) z[p][0][j] = *(const float4 *)(Z + idx[p] * D + (4 * j + q) * 4);
+            for (int j = 0; j < NJ; ++j) z[p][0][j] = load_piece<D, ZB>(Z, idx[p], j, q);
         }
     }
     int myk = 0;
@@ -103,7 +105,9 @@ __device__ __forceinline__ void dual_rows_step(const int64_t *__restrict__ indpt
         for (int t1 = 0; t1 < KT; ++t1)
 #pragma unroll
             for (int t2 = 0; t2 <= t1; ++t2) acc[t1][t2] = floatx4{0.f, 0.f, 0.f, 0.f};
-        if constexpr (NJ >= 2) {  // split products on the bf16 matrix cores (dual_common.h)
+        if constexpr (ZB) {  // bf16 rows are matrix-core operands as loaded
+            acc[0][0] = mfma_pieces_bf16<NJ>(z[p][0], z[p][0], acc[0][0]);
+        } else if constexpr (NJ >= 2) {  // split products on the bf16 matrix cores (dual_common.h)
 #pragma unroll
             for (int h = 0; h < NJ / 2; ++h) {
                 const SplitOperand zs = split_operand(z[p][0][2 * h], z[p][0][2 * h + 1]);
@@ -200,7 +204,7 @@ __device__ __forceinline__ void dual_rows_step(const int64_t *__restrict__ indpt
 #pragma unroll
             for (int t = 0; t < KT; ++t)
 #pragma unroll
-                for (int j = 0; j < NJ; ++j) *(float4 *)(zb + (16 * t + a) * ZLD + (4 * j + q) * 4) = z[p][t][j];
+                for (int j = 0; j < NJ; ++j) *(float4 *)(zb + (16 * t + a) * ZLDB + (4 * j + q) * 16) = z[p][t][j];
             wave_sync();
             if (u[p] >= 0 && lane * CPL < D) {
                 // four slots at a time (slots past the row's k hold t = 0 and zero entries): the LDS reads of a
@@ -214,13 +218,10 @@ __device__ __forceinline__ void dual_rows_step(const int64_t *__restrict__ indpt
 #pragma unroll
                         for (int x = 0; x < 4; ++x) {
                             const int e = 4 * h + x;
-                            if constexpr (CPL == 2) {
-                                const float2 zz = *(const float2 *)(zb + e * ZLD + 2 * lane);
-                                r0v += te[x] * zz.x;
-                                r1v += te[x] * zz.y;
-                            } else {
-                                r0v += te[x] * zb[e * ZLD + lane];
-                            }
+                            float zz[CPL];
+                            row_cols<ZB, CPL>(zb + e * ZLDB, lane, zz);
+                            r0v += te[x] * zz[0];
+                            if constexpr (CPL == 2) r1v += te[x] * zz[1];
                         }
                     }
                 }
@@ -233,11 +234,11 @@ __device__ __forceinline__ void dual_rows_step(const int64_t *__restrict__ indpt
 
 // The two launch forms of a step kernel (see StepGrid): one step per workgroup, or a grid-stride walk from
 // step first_blk to the end of the list.
-template <int D, bool LOOP>
+template <int D, bool ZB, bool LOOP>
 __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict__ indptr,
                                                        const int32_t *__restrict__ indices,
                                                        const float *__restrict__ values,
-                                                       const float *__restrict__ Z, float *__restrict__ R,
+                                                       const void *__restrict__ Z, float *__restrict__ R,
                                                        int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
                                                        const int32_t *__restrict__ count_ptr, int first_blk,
                                                        int32_t *__restrict__ err_flag) {
@@ -245,36 +246,37 @@ __global__ __launch_bounds__(64) void dual_rows_kernel(const int64_t *__restrict
     const int count = *count_ptr;
     int blk = first_blk + blockIdx.x;
     if constexpr (!LOOP) {
-        if (blk * DualCfg<D>::RPW < count) dual_rows_step<D>(indptr, indices, values, Z, R, ldr, r0, list, count, err_flag, blk, lds);
+        if (blk * DualCfg<D>::RPW < count) dual_rows_step<D, ZB>(indptr, indices, values, Z, R, ldr, r0, list, count, err_flag, blk, lds);
     } else {
         for (; blk * DualCfg<D>::RPW < count; blk += gridDim.x) {
-            dual_rows_step<D>(opaque(indptr), opaque(indices), opaque(values), opaque(Z), opaque(R), opaque(ldr), opaque(r0),
+            dual_rows_step<D, ZB>(opaque(indptr), opaque(indices), opaque(values), opaque(Z), opaque(R), opaque(ldr), opaque(r0),
                               opaque(list), opaque(count), opaque(err_flag), blk, opaque(lds));
             wave_sync();  // the next step reuses the LDS buffers
         }
     }
 }
 
-template <int D>
-static void launch_rows_typed(const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
+template <int D, bool ZB>
+static void launch_rows_typed(const als_csr *Y, const void *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
                               const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
     using C = DualCfg<D>;
     if (g.known > 0)
-        hipLaunchKernelGGL((dual_rows_kernel<D, false>), dim3(g.known), dim3(64), C::LDS_FLOATS * sizeof(float), s,
+        hipLaunchKernelGGL((dual_rows_kernel<D, ZB, false>), dim3(g.known), dim3(64), C::LDS_FLOATS * sizeof(float), s,
                            Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count_dev, 0, err);
     if (g.rest > 0)
-        hipLaunchKernelGGL((dual_rows_kernel<D, true>), dim3(g.rest), dim3(64), C::LDS_FLOATS * sizeof(float), s,
+        hipLaunchKernelGGL((dual_rows_kernel<D, ZB, true>), dim3(g.rest), dim3(64), C::LDS_FLOATS * sizeof(float), s,
                            Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count_dev, (int)g.known, err);
 }
 
-void launch_dual_k16(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                     const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
-    switch (d) {
-        case 16: launch_rows_typed<16>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
-        case 32: launch_rows_typed<32>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
-        case 64: launch_rows_typed<64>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
-        case 128: launch_rows_typed<128>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
-    }
+void launch_dual_k16(int d, const als_csr *Y, const void *Z, bool zb16, float *R, int64_t ldr, int64_t r0,
+                     const int32_t *list, const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
+#define ALS_ROWS_CASE(dd)                                                                             \
+    case dd:                                                                                          \
+        if (zb16 && dd >= 32) launch_rows_typed<dd, (dd >= 32)>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); \
+        else launch_rows_typed<dd, false>(Y, Z, R, ldr, r0, list, count_dev, g, err, s);              \
+        break;
+    switch (d) { ALS_ROWS_CASE(16) ALS_ROWS_CASE(32) ALS_ROWS_CASE(64) ALS_ROWS_CASE(128) }
+#undef ALS_ROWS_CASE
 }
 
 }  // namespace als

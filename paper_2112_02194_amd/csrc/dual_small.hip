@@ -36,15 +36,17 @@ template <int D, int G> struct SmallCfg {
     static constexpr int LDS_FLOATS = OFF_META + 3 * NR + 1;
 };
 
-template <int D, int G>
+template <int D, int G, bool ZB>
 __device__ __forceinline__ void dual_small_step(const int64_t *__restrict__ indptr, const int32_t *__restrict__ indices,
-                                                const float *__restrict__ values, const float *__restrict__ Z,
+                                                const float *__restrict__ values, const void *__restrict__ Z,
                                                 float *__restrict__ R, int64_t ldr, int64_t r0,
                                                 const int32_t *__restrict__ list, int count,
                                                 int32_t *__restrict__ err_flag, int blk, float *lds) {
     using C = SmallCfg<D, G>;
-    constexpr int SPT = C::SPT, NR = C::NR, KP = C::KP, ZLD = C::ZLD, NJ = D / 16, CPL = D >= 128 ? 2 : 1;
-    float *sb = lds, *zb = lds, *tb = lds + C::OFF_T;
+    constexpr int SPT = C::SPT, NR = C::NR, KP = C::KP, NJ = z_pieces<D, ZB>(), CPL = D >= 128 ? 2 : 1;
+    constexpr int ZLDB = D * ZT<ZB>::ES + 16;  // row stride in bytes of the LDS copy of a tile's entries
+    float *sb = lds, *tb = lds + C::OFF_T;
+    char *zb = (char *)lds;
     int32_t *meta = (int32_t *)(lds + C::OFF_META);  // [NR][3]: u lo, u hi, k
     const int lane = opaque_tid(), a = lane & 15, q = lane >> 4;
     const int sub = a / G, e = a % G;  // MFMA view: sub-system of the tile and entry slot
@@ -94,14 +96,16 @@ __device__ __forceinline__ void dual_small_step(const int64_t *__restrict__ indp
         for (int j = 0; j < NJ; ++j) z[p][j] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (idx[p] >= 0) {  // one masked region per tile, not one per load
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) z[p][j] = *(const float4 *)(Z + idx[p] * D + (4 * j + q) * 4);
+            for (int j = 0; j < NJ; ++j) z[p][j] = load_piece<D, ZB>(Z, idx[p], j, q);
         }
     }
     // ---- 2. the tiles' products; tile p's 16 x 16 result to LDS (only its diagonal blocks are used)
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
-        if constexpr (NJ >= 2) {  // split products on the bf16 matrix cores (dual_common.h)
+        if constexpr (ZB) {  // bf16 rows are matrix-core operands as loaded
+            acc = mfma_pieces_bf16<NJ>(z[p], z[p], acc);
+        } else if constexpr (NJ >= 2) {  // split products on the bf16 matrix cores (dual_common.h)
 #pragma unroll
             for (int h = 0; h < NJ / 2; ++h) {
                 const SplitOperand zs = split_operand(z[p][2 * h], z[p][2 * h + 1]);
@@ -173,7 +177,7 @@ __device__ __forceinline__ void dual_small_step(const int64_t *__restrict__ indp
     for (int p = 0; p < 4; ++p) {
         if (p > 0) wave_sync();  // the previous tile's copy has been read
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) *(float4 *)(zb + a * ZLD + (4 * j + q) * 4) = z[p][j];
+        for (int j = 0; j < NJ; ++j) *(float4 *)(zb + a * ZLDB + (4 * j + q) * 16) = z[p][j];
         wave_sync();
 #pragma unroll
         for (int sidx = 0; sidx < SPT; ++sidx) {
@@ -192,13 +196,10 @@ __device__ __forceinline__ void dual_small_step(const int64_t *__restrict__ indp
 #pragma unroll
                         for (int x = 0; x < 4; ++x) {
                             const int e = sidx * G + 4 * h + x;
-                            if constexpr (CPL == 2) {
-                                const float2 zz = *(const float2 *)(zb + e * ZLD + 2 * lane);
-                                r0v += te[x] * zz.x;
-                                r1v += te[x] * zz.y;
-                            } else {
-                                r0v += te[x] * zb[e * ZLD + lane];
-                            }
+                            float zz[CPL];
+                            row_cols<ZB, CPL>(zb + e * ZLDB, lane, zz);
+                            r0v += te[x] * zz[0];
+                            if constexpr (CPL == 2) r1v += te[x] * zz[1];
                         }
                     }
                 }
@@ -211,11 +212,11 @@ __device__ __forceinline__ void dual_small_step(const int64_t *__restrict__ indp
 
 // The two launch forms of a step kernel (see StepGrid): one step per workgroup, or a grid-stride walk from
 // step first_blk to the end of the list.
-template <int D, int G, bool LOOP>
+template <int D, int G, bool ZB, bool LOOP>
 __global__ __launch_bounds__(64) void dual_small_kernel(const int64_t *__restrict__ indptr,
                                                         const int32_t *__restrict__ indices,
                                                         const float *__restrict__ values,
-                                                        const float *__restrict__ Z, float *__restrict__ R,
+                                                        const void *__restrict__ Z, float *__restrict__ R,
                                                         int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
                                                         const int32_t *__restrict__ count_ptr, int first_blk,
                                                         int32_t *__restrict__ err_flag) {
@@ -224,42 +225,44 @@ __global__ __launch_bounds__(64) void dual_small_kernel(const int64_t *__restric
     const int count = *count_ptr;
     int blk = first_blk + blockIdx.x;
     if constexpr (!LOOP) {
-        if (blk * NR < count) dual_small_step<D, G>(indptr, indices, values, Z, R, ldr, r0, list, count, err_flag, blk, lds);
+        if (blk * NR < count) dual_small_step<D, G, ZB>(indptr, indices, values, Z, R, ldr, r0, list, count, err_flag, blk, lds);
     } else {
         for (; blk * NR < count; blk += gridDim.x) {
-            dual_small_step<D, G>(opaque(indptr), opaque(indices), opaque(values), opaque(Z), opaque(R), opaque(ldr), opaque(r0),
+            dual_small_step<D, G, ZB>(opaque(indptr), opaque(indices), opaque(values), opaque(Z), opaque(R), opaque(ldr), opaque(r0),
                               opaque(list), opaque(count), opaque(err_flag), blk, opaque(lds));
             wave_sync();  // the next step reuses the LDS buffers
         }
     }
 }
 
-template <int D>
-static void launch_small_typed(const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0,
-                               const int32_t *list, const int32_t *count_dev, StepGrid g, int32_t *err,
-                               hipStream_t s) {
+template <int D, bool ZB>
+static void launch_small_typed(const als_csr *Y, const void *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
+                               const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
     using C = SmallCfg<D, SMALL_G>;
     if (g.known > 0)
-        hipLaunchKernelGGL((dual_small_kernel<D, SMALL_G, false>), dim3(g.known), dim3(64), C::LDS_FLOATS * sizeof(float),
-                           s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count_dev, 0, err);
+        hipLaunchKernelGGL((dual_small_kernel<D, SMALL_G, ZB, false>), dim3(g.known), dim3(64),
+                           C::LDS_FLOATS * sizeof(float), s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list,
+                           count_dev, 0, err);
     if (g.rest > 0)
-        hipLaunchKernelGGL((dual_small_kernel<D, SMALL_G, true>), dim3(g.rest), dim3(64), C::LDS_FLOATS * sizeof(float),
-                           s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count_dev, (int)g.known, err);
+        hipLaunchKernelGGL((dual_small_kernel<D, SMALL_G, ZB, true>), dim3(g.rest), dim3(64),
+                           C::LDS_FLOATS * sizeof(float), s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list,
+                           count_dev, (int)g.known, err);
 }
 
 #if SMALL_G == 8
-void launch_dual_small8(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                        const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
+void launch_dual_small8(int d, const als_csr *Y, const void *Z, bool zb16, float *R, int64_t ldr, int64_t r0,
+                        const int32_t *list, const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
 #else
-void launch_dual_small4(int d, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
-                        const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
+void launch_dual_small4(int d, const als_csr *Y, const void *Z, bool zb16, float *R, int64_t ldr, int64_t r0,
+                        const int32_t *list, const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
 #endif
-    switch (d) {
-        case 16: launch_small_typed<16>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
-        case 32: launch_small_typed<32>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
-        case 64: launch_small_typed<64>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
-        case 128: launch_small_typed<128>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); break;
-    }
+#define ALS_SMALL_CASE(dd)                                                                              \
+    case dd:                                                                                            \
+        if (zb16 && dd >= 32) launch_small_typed<dd, (dd >= 32)>(Y, Z, R, ldr, r0, list, count_dev, g, err, s); \
+        else launch_small_typed<dd, false>(Y, Z, R, ldr, r0, list, count_dev, g, err, s);               \
+        break;
+    switch (d) { ALS_SMALL_CASE(16) ALS_SMALL_CASE(32) ALS_SMALL_CASE(64) ALS_SMALL_CASE(128) }
+#undef ALS_SMALL_CASE
 }
 
 }  // namespace als

@@ -24,14 +24,14 @@ template <int D, int KT> struct WideCfg {
     static constexpr int LDS_FLOATS = OFF_ID + K;
 };
 
-template <int D, int KT>
+template <int D, int KT, bool ZB>
 __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indptr, const int32_t *__restrict__ indices,
-                                               const float *__restrict__ values, const float *__restrict__ Z,
+                                               const float *__restrict__ values, const void *__restrict__ Z,
                                                float *__restrict__ R, int64_t ldr, int64_t r0,
                                                const int32_t *__restrict__ list, int32_t *__restrict__ err_flag,
                                                int item, float *lds) {
     using C = WideCfg<D, KT>;
-    constexpr int K = C::K, NJ = D / 16;
+    constexpr int K = C::K, NJ = z_pieces<D, ZB>();
     float *tri = lds, *aux = lds + C::OFF_COL, *tbuf = lds + C::OFF_T;
     int32_t *ids = (int32_t *)(lds + C::OFF_ID);
     const int lane = opaque_tid(), a = lane & 15, q = lane >> 4;
@@ -51,51 +51,47 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
     // the first RT tiles stay in registers for the whole phase (one round of loads, all in flight
     // together), already cut into the hi/lo bf16 operands of the split products (dual_common.h); later
     // tiles are fetched and cut when they are needed
-    constexpr int RT = KT < 5 ? KT : (KT < 7 ? 5 : 4), NH = NJ / 2;
+    constexpr int RT = KT < 5 ? KT : (KT < 7 ? 5 : 4);
+    typedef TileOperand<D, ZB> Op;
     auto fetch = [&](int t, float4 (&raw)[NJ]) {
 #pragma unroll
         for (int j = 0; j < NJ; ++j) raw[j] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (myid[t] >= 0) {  // one masked region per tile, not one per load
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) raw[j] = *(const float4 *)(Z + (int64_t)myid[t] * D + (4 * j + q) * 4);
+            for (int j = 0; j < NJ; ++j) raw[j] = load_piece<D, ZB>(Z, myid[t], j, q);
         }
     };
-    SplitOperand zop[RT][NH];
+    Op zop[RT];
     {
         float4 raw[RT][NJ];
 #pragma unroll
         for (int t = 0; t < RT; ++t) fetch(t, raw[t]);
 #pragma unroll
-        for (int t = 0; t < RT; ++t)
-#pragma unroll
-            for (int h = 0; h < NH; ++h) zop[t][h] = split_operand(raw[t][2 * h], raw[t][2 * h + 1]);
+        for (int t = 0; t < RT; ++t) zop[t].set(raw[t]);
     }
 #pragma unroll
     for (int t1 = 0; t1 < KT; ++t1) {
-        SplitOperand zb[NH];
+        Op zb;
         if (t1 < RT) {
-#pragma unroll
-            for (int h = 0; h < NH; ++h) zb[h] = zop[t1 < RT ? t1 : 0][h];
+            zb = zop[t1 < RT ? t1 : 0];
         } else {
             float4 raw[NJ];
             fetch(t1, raw);
-#pragma unroll
-            for (int h = 0; h < NH; ++h) zb[h] = split_operand(raw[2 * h], raw[2 * h + 1]);
+            zb.set(raw);
         }
 #pragma unroll
         for (int t2 = 0; t2 <= t1; ++t2) {
             floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
             if (t2 == t1) {
-#pragma unroll
-                for (int h = 0; h < NH; ++h) acc = split_mfma(zb[h], zb[h], acc);
+                acc = tile_product<D, ZB>(zb, zb, acc);
             } else if (t2 < RT) {
-#pragma unroll
-                for (int h = 0; h < NH; ++h) acc = split_mfma(zop[t2 < RT ? t2 : 0][h], zb[h], acc);
+                acc = tile_product<D, ZB>(zop[t2 < RT ? t2 : 0], zb, acc);
             } else {
                 float4 raw[NJ];
                 fetch(t2, raw);
-#pragma unroll
-                for (int h = 0; h < NH; ++h) acc = split_mfma(split_operand(raw[2 * h], raw[2 * h + 1]), zb[h], acc);
+                Op za;
+                za.set(raw);
+                acc = tile_product<D, ZB>(za, zb, acc);
             }
             // acc[v] = S[Rr][c], Rr = 16*t1 + a, c = 16*t2 + 4q + v (S is symmetric); keep c <= Rr
             const int Rr = 16 * t1 + a;
@@ -133,14 +129,7 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int id = idr[i];
-                const float *zp = Z + (int64_t)id * D + CPL * lane;
-                if constexpr (CPL == 2) {
-                    const float2 t2 = *(const float2 *)zp;
-                    zz[i][0] = t2.x;
-                    zz[i][1] = t2.y;
-                } else {
-                    zz[i][0] = *zp;
-                }
+                row_cols<ZB, CPL>((const char *)Z + (int64_t)id * D * ZT<ZB>::ES, lane, zz[i]);
             }
 #pragma unroll
             for (int i = 0; i < 8; ++i)
@@ -154,11 +143,11 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
 
 // The two launch forms of a step kernel (see StepGrid): one row per workgroup, or a grid-stride walk from
 // row first_item to the end of the list.
-template <int D, int KT, bool LOOP>
+template <int D, int KT, bool ZB, bool LOOP>
 __global__ __launch_bounds__(64, LOOP ? 1 : 2) void dual_wide_kernel(const int64_t *__restrict__ indptr,
                                                           const int32_t *__restrict__ indices,
                                                           const float *__restrict__ values,
-                                                          const float *__restrict__ Z, float *__restrict__ R,
+                                                          const void *__restrict__ Z, float *__restrict__ R,
                                                           int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
                                                           const int32_t *__restrict__ count_ptr, int first_item,
                                                           int32_t *__restrict__ err_flag) {
@@ -166,10 +155,10 @@ __global__ __launch_bounds__(64, LOOP ? 1 : 2) void dual_wide_kernel(const int64
     const int count = *count_ptr;
     int item = first_item + blockIdx.x;
     if constexpr (!LOOP) {
-        if (item < count) dual_wide_step<D, KT>(indptr, indices, values, Z, R, ldr, r0, list, err_flag, item, lds);
+        if (item < count) dual_wide_step<D, KT, ZB>(indptr, indices, values, Z, R, ldr, r0, list, err_flag, item, lds);
     } else {
         for (; item < count; item += gridDim.x) {
-            dual_wide_step<D, KT>(opaque(indptr), opaque(indices), opaque(values), opaque(Z), opaque(R), opaque(ldr),
+            dual_wide_step<D, KT, ZB>(opaque(indptr), opaque(indices), opaque(values), opaque(Z), opaque(R), opaque(ldr),
                                   opaque(r0), opaque(list), opaque(err_flag), item, opaque(lds));
             wave_sync();  // the next step reuses the LDS buffers
         }
@@ -179,12 +168,12 @@ __global__ __launch_bounds__(64, LOOP ? 1 : 2) void dual_wide_kernel(const int64
 #define ALS_WIDE_NAME2(kt) launch_dual_wide##kt
 #define ALS_WIDE_NAME(kt) ALS_WIDE_NAME2(kt)
 
-template <int D>
-static als_status wide_typed(als_ctx *ctx, const als_csr *Y, const float *Z, float *R, int64_t ldr, int64_t r0,
+template <int D, bool ZB>
+static als_status wide_typed(als_ctx *ctx, const als_csr *Y, const void *Z, float *R, int64_t ldr, int64_t r0,
                              const int32_t *list, const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
     using C = WideCfg<D, WIDE_KT>;
-    auto kern = dual_wide_kernel<D, WIDE_KT, false>;
-    auto kern_loop = dual_wide_kernel<D, WIDE_KT, true>;
+    auto kern = dual_wide_kernel<D, WIDE_KT, ZB, false>;
+    auto kern_loop = dual_wide_kernel<D, WIDE_KT, ZB, true>;
     constexpr int lds_bytes = (int)(C::LDS_FLOATS * sizeof(float));
     static const hipError_t attr = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     static const hipError_t attr_loop =
@@ -200,13 +189,17 @@ static als_status wide_typed(als_ctx *ctx, const als_csr *Y, const float *Z, flo
     return ALS_OK;
 }
 
-als_status ALS_WIDE_NAME(WIDE_KT)(als_ctx *ctx, int d, const als_csr *Y, const float *Z, float *R, int64_t ldr,
+als_status ALS_WIDE_NAME(WIDE_KT)(als_ctx *ctx, int d, const als_csr *Y, const void *Z, bool zb16, float *R, int64_t ldr,
                                   int64_t r0, const int32_t *list, const int32_t *count_dev, StepGrid g,
                                   int32_t *err, hipStream_t s) {
     if (g.known == 0 && g.rest == 0) return ALS_OK;
-    if (d == 128) return wide_typed<128>(ctx, Y, Z, R, ldr, r0, list, count_dev, g, err, s);
+    if (d == 128)
+        return zb16 ? wide_typed<128, true>(ctx, Y, Z, R, ldr, r0, list, count_dev, g, err, s)
+                    : wide_typed<128, false>(ctx, Y, Z, R, ldr, r0, list, count_dev, g, err, s);
     if constexpr (WIDE_KT <= 4) {  // the dual form reaches k <= 64 at d = 64
-        if (d == 64) return wide_typed<64>(ctx, Y, Z, R, ldr, r0, list, count_dev, g, err, s);
+        if (d == 64)
+            return zb16 ? wide_typed<64, true>(ctx, Y, Z, R, ldr, r0, list, count_dev, g, err, s)
+                        : wide_typed<64, false>(ctx, Y, Z, R, ldr, r0, list, count_dev, g, err, s);
     }
     return fail(ctx, ALS_EDTYPE, "wide dual kernel: unsupported d");
 }

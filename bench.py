@@ -172,27 +172,32 @@ def main():
 
     # ---- roofline per kernel ------------------------------------------------------------------------
     # Algorithmic work per epoch of each timed kernel (what the method itself must move or compute):
-    #   dual row kernel of a class:  HBM-bound,  nnz_c*(4*d + 4) [gathered fp32 rows of Z + column ids]
-    #                                           + rows_c*(4*d + 8 + 4) [r store, indptr, list entry] bytes
+    #   dual row kernel of a class:  HBM-bound,  nnz_c*(s_z*d + 4) [gathered rows of Z (s_z = 4 bytes, 2 for bf16
+    #                                           tables) + column ids] + rows_c*(4*d + 8 + 4) [r store, indptr, list entry]
     #   Z = V L^-T and X = R L^-1:   HBM-bound,  rows*d*(s_in + s_out) bytes
     #   Gramian:                     fp32 tables: fp32-MFMA-bound, 2*rows*d^2 flop; bf16 tables: HBM-bound, rows*d*2 bytes
-    #   primal fused rows:           fp32-MFMA-bound, 2*nnz_p*d^2 + rows_p*(d^3/3 + 2*d^2) flop
-    #   long-row segments:           fp32-MFMA-bound, 2*nnz_l*d^2 flop
+    #   primal fused rows:           fp32 tables: fp32-MFMA-bound, 2*nnz_p*d^2 + rows_p*(d^3/3 + 2*d^2) flop;
+    #                                bf16 tables: the fp32 solves on the vector ALU, rows_p*(d^3/3 + 2*d^2) flop
+    #   long-row segments:           fp32 tables: fp32-MFMA-bound, 2*nnz_l*d^2 flop; bf16 tables: HBM-bound gather
     # achieved = work of the launches timed / their summed duration (HIP events on the launch stream).
     nsteps = max(args.steps, 1)
     deg = {"row": p.indptr[1:] - p.indptr[:-1], "col": p.t_indptr[1:] - p.t_indptr[:-1]}
     dual_max = 0 if args.path == "primal" else {16: 16, 32: 32, 64: 64, 128: 128}[d]
     bounds = [("dual_k4", 0, 4), ("dual_k8", 4, 8)] + [(f"dual_k{16 * (c + 1)}", max(16 * c, 8), 16 * (c + 1)) for c in range(8)]
     bft = "true" if es == 2 else "false"  # the kernels' template arguments as rocprofv3 prints them
-    kernel_names = {"dual_k4": f"dual_small_kernel<{d},4,false>", "dual_k8": f"dual_small_kernel<{d},8,false>",
-                    "dual_k16": f"dual_rows_kernel<{d},false>", "dual_k32": f"dual_multi_kernel<{d},2,false>"}
+    zbt = "true" if (es == 2 and d >= 32) else "false"  # Z kept as bf16
+    kernel_names = {"dual_k4": f"dual_small_kernel<{d},4,{zbt},false>", "dual_k8": f"dual_small_kernel<{d},8,{zbt},false>",
+                    "dual_k16": f"dual_rows_kernel<{d},{zbt},false>", "dual_k32": f"dual_multi_kernel<{d},2,{zbt},false>"}
     for c in range(2, 8):
-        kernel_names[f"dual_k{16 * (c + 1)}"] = f"dual_wide_kernel<{d},{c + 1},false>"
-    kernel_names.update({"gramian": f"gramian_partial_kernel<{d},{bft}>",
-                         "transform_z": f"transform_kernel<{d},{bft},false,true>",    # Z = V L^-T
-                         "transform_x": f"transform_kernel<{d},false,{bft},false>",   # X = R L^-1
+        kernel_names[f"dual_k{16 * (c + 1)}"] = f"dual_wide_kernel<{d},{c + 1},{zbt},false>"
+    kernel_names.update({"gramian": f"gramian_bf16_kernel<{d}>" if (es == 2 and d >= 64) else f"gramian_partial_kernel<{d},{bft}>",
+                         "transform_z": f"transform16_kernel<{d},true,true>" if zbt == "true"      # Z = V L^-T
+                         else f"transform_kernel<{d},{bft},false,true>",
+                         "transform_x": f"transform16_kernel<{d},false,false>" if zbt == "true"    # X = R L^-1
+                         else f"transform_kernel<{d},false,{bft},false>",
                          "primal": f"primal_kernel<{d},{bft},0,false>",               # one workgroup per row
                          "segment": f"primal_kernel<{d},{bft},1,false>"})             # segments of long rows
+    zs = 2 if (es == 2 and d >= 32) else 4  # bytes per element of the transformed table Z the dual kernels gather
     work = {}
     long_nnz = prim_rows = prim_nnz = 0
     for kdeg in deg.values():
@@ -200,16 +205,24 @@ def main():
             msk = (kdeg > lo) & (kdeg <= min(hi, dual_max))
             r_c, n_c = int(msk.sum()), int(kdeg[msk].sum())
             w = work.setdefault(name, ["hbm", 0.0])
-            w[1] += n_c * (4 * d + 4) + r_c * (4 * d + 12)
-        msk = (kdeg > dual_max) & (kdeg <= 512)
+            w[1] += n_c * (zs * d + 4) + r_c * (4 * d + 12)
+        # the library's long-row threshold: 512, raised until the segments of all longer rows fit its workspace
+        beyond = int(kdeg[kdeg > 512].sum())
+        split = max(512, -(-beyond // 16384))
+        msk = (kdeg > dual_max) & (kdeg <= split)
         prim_rows += int(msk.sum())
         prim_nnz += int(kdeg[msk].sum())
-        long_nnz += int(kdeg[kdeg > 512].sum())
-    work["primal"] = ["mfma", 2.0 * prim_nnz * d * d + prim_rows * (d ** 3 / 3.0 + 2.0 * d * d)]
-    work["segment"] = ["mfma", 2.0 * long_nnz * d * d]
-    work["transform_z"] = ["hbm", float(m + n) * d * (es + 4)]
+        long_nnz += int(kdeg[kdeg > split].sum())
+    if es == 4:  # fp32 tables: the statistics run on the fp32 matrix cores
+        work["primal"] = ["mfma", 2.0 * prim_nnz * d * d + prim_rows * (d ** 3 / 3.0 + 2.0 * d * d)]
+        work["segment"] = ["mfma", 2.0 * long_nnz * d * d]
+        work["gramian"] = ["mfma", 2.0 * (m + n) * d * d]
+    else:       # bf16 tables: statistics on the bf16 matrix cores leave the gather (HBM) and the fp32 solve (vector ALU)
+        work["primal"] = ["alu", prim_rows * (d ** 3 / 3.0 + 2.0 * d * d)]
+        work["segment"] = ["hbm", float(long_nnz) * (d * es + 4)]
+        work["gramian"] = ["hbm", float(m + n) * d * es]
+    work["transform_z"] = ["hbm", float(m + n) * d * (es + zs)]
     work["transform_x"] = ["hbm", float(m + n) * d * (4 + es)]
-    work["gramian"] = ["mfma", 2.0 * (m + n) * d * d] if es == 4 else ["hbm", float(m + n) * d * es]
     stages = {}
     for name, (bound, per_epoch) in work.items():
         ms = stage_ms.get(name, 0.0) / nsteps
@@ -217,7 +230,7 @@ def main():
             continue
         if bound == "hbm":
             ach, peak, unit = per_epoch / (ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
-        else:
+        else:  # "mfma": fp32 matrix cores; "alu": fp32 vector units - the same published 157.3 TFLOP/s
             ach, peak, unit = per_epoch / (ms * 1e-3) / 1e12, MFMA_F32_PEAK_TFLOPS, "TFLOP/s"
         launches = stage_launches.get(name, 0.0) / nsteps
         stages[name] = {"kernel": kernel_names.get(name, name), "ms_per_epoch": round(ms, 4), "launches_per_epoch": launches,

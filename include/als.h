@@ -98,9 +98,10 @@ als_status als_create(als_ctx **ctx, int device);
 als_status als_destroy(als_ctx *ctx);
 
 /* G = V^T V, the Gramian of a table (Section 3 after Eq. 4; Algorithm 1 line 2).
- * G: device fp32 [d*d], row-major, both triangles written.  bf16 tables are
- * widened exactly; products and sums are fp32 within a block of rows, fp64
- * across blocks.  Asynchronous on `stream` (a hipStream_t, NULL = default). */
+ * G: device fp32 [d*d], row-major, both triangles written, symmetric to the bit.
+ * bf16 entries are used exactly (their products are exact in fp32); sums are fp32
+ * inside the matrix core over at most 256 additions, fp64 across blocks of rows, in
+ * a fixed order.  Asynchronous on `stream` (a hipStream_t, NULL = default). */
 als_status als_gramian(als_ctx *ctx, const als_table *V, float *G, void *stream);
 
 /* als_gramian for callers that cannot allocate device memory: code under HIP graph capture, tight serving
@@ -123,8 +124,13 @@ const char *als_static_last_error(void);
  * produced by als_gramian.  A row with no stored entry gets X[u] = 0.  With
  * ALS_SOLVER_CG the rows of X in the range are also read (start vectors).  X must
  * have Y->rows rows, the same d and dtype as V, and must not overlap V.  All
- * arithmetic is fp32 (fp64 for the one shared d x d factorisation); the result
- * is rounded once (to nearest even) to X's dtype.  Rows outside the range are
+ * arithmetic is fp32 (fp64 for the one shared d x d factorisation; products on the
+ * bf16 matrix cores take fp32 operands as hi + lo bf16 parts, accurate to 2^-16, and
+ * accumulate in fp32); the result is rounded once (to nearest even) to X's dtype.
+ * With bf16 tables and d >= 32 the library's transformed copy of V (the table Z of
+ * the k x k form) is kept in bf16 as well, one more rounding to the tables' own
+ * element type (Section 4.4 keeps the tables in bf16 and the solve in fp32: the
+ * solve stays fp32).  Rows outside the range are
  * left untouched.  Asynchronous on `stream`: nothing waits for the GPU and nothing
  * is copied back (the first call with a larger problem than any before grows the
  * workspace, which allocates).  A non-positive pivot sets a device flag reported as
@@ -167,7 +173,7 @@ als_status als_status_sync(als_ctx *ctx, void *stream);
  * is out of range.  Synchronises `stream`. */
 als_status als_check_csr(als_ctx *ctx, const als_csr *Y, void *stream);
 
-/* Profiling aid: a plain device-to-device copy kernel of known size (`bytes`, a multiple of 16, both
+/* Diagnostics, not part of the method.  A plain device-to-device copy kernel of known size (`bytes`, a multiple of 16, both
  * pointers device and 16-byte aligned).  Hardware traffic counters (FETCH_SIZE, WRITE_SIZE) read for
  * this kernel give the scale factor applied to the counters of the other kernels. */
 als_status als_copy_probe(als_ctx *ctx, const void *src, void *dst, int64_t bytes, void *stream);

@@ -105,6 +105,26 @@ __device__ __forceinline__ floatx4 split_mfma(const SplitOperand &a, const Split
     return acc;
 }
 
+// Selection operands of v_mfma_f32_16x16x32_bf16: h[x] (depth 32, 16 columns) has a one at (16 x + n, n).  A
+// 16 x 32 operand times h[x] is its columns 16 x .. 16 x + 15 in the accumulator layout, exactly: the matrix
+// core used as a transposer.
+struct SelOperands { bf16x8 h[2]; };
+__device__ __forceinline__ SelOperands make_sel(int lane) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const int n = lane & 15, kq = lane >> 4;
+    SelOperands s;
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+        // this lane holds depth slots 8 kq .. 8 kq + 7 of column n; the one sits at slot 16 x + n
+        const int w = 16 * x + n - 8 * kq;  // 0 .. 7 if it is one of them
+        u32x4 v;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[c] = w == 2 * c ? 0x00003f80u : (w == 2 * c + 1 ? 0x3f800000u : 0u);
+        s.h[x] = __builtin_bit_cast(bf16x8, v);
+    }
+    return s;
+}
+
 // ---------------------------------------------------------------------------------------------- the table Z
 // The row kernels read the transformed table Z = V L^-T either as fp32 (fp32 tables) or as bf16 (ZB: bf16
 // tables with d >= 32, where Z is rounded once to the tables' own element type).  A lane (a, q) of a
@@ -171,6 +191,59 @@ __device__ __forceinline__ floatx4 tile_product(const TileOperand<D, ZB> &A, con
             acc = split_mfma(A.v[h], B.v[h], acc);
     }
     return acc;
+}
+
+// ---------------------------------------------------------------------------------------------- r = Z_I^T t on chip
+// r = Z_I^T t from tiles that are still in registers as S operands, on the matrix cores.  The product contracts
+// over the entries, so the tiles are needed with the entries along the operand's depth: a tile operand times
+// a selection operand is the same numbers in the accumulator layout (one column, entries 4q .. 4q+3 per lane),
+// exactly, and two tiles packed that way are the depth-32 operand of 16 columns.  The other operand (`top`,
+// one per pair of tiles) holds t cut into three bf16 parts, t = p0 + p1 + p2 exactly, in its rows 0 .. 2 and
+// zeros below; rows 0 .. 2 of the product, summed, are r on those 16 columns with fp32 accuracy.  out[2 j + x]
+// accumulates the product for operand piece j, half x; column_of_result() names the column a lane holds there.
+//
+// t_operand(): `mine` points at this lane's part of t (p0, p1, p2 or a block of zeros by its row a = lane % 16)
+// plus 4 q; the parts are fp32 numbers of which the operand takes the upper 16 bits.
+__device__ __forceinline__ bf16x8 t_operand(const float *mine, bool second_tile) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const float4 ta = *(const float4 *)mine;
+    float4 tb = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (second_tile) tb = *(const float4 *)(mine + 16);
+    const u32x4 w = {pack_upper(ta.x, ta.y), pack_upper(ta.z, ta.w), pack_upper(tb.x, tb.y), pack_upper(tb.z, tb.w)};
+    return __builtin_bit_cast(bf16x8, w);
+}
+// the two remainders of the cut: x - upper16(x) is exact
+__device__ __forceinline__ void t_parts(float x0, float &x1, float &x2) {
+    x1 = lower_part(x0);
+    x2 = lower_part(x1);
+}
+
+template <int NT, int NP, class Tile>  // Tile(t, j): operand piece j (32 columns) of tile t as bf16x8
+__device__ __forceinline__ void zt_times_t(Tile &&tile, const bf16x8 (&top)[(NT + 1) / 2], const SelOperands &sel,
+                                           floatx4 (&out)[2 * NP]) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const floatx4 zero = floatx4{0.f, 0.f, 0.f, 0.f};
+    static_for<0, NP>([&](auto jj) {
+        constexpr int j = decltype(jj)::value;
+        static_for<0, 2>([&](auto xx) {
+            constexpr int x = decltype(xx)::value;
+            static_for<0, (NT + 1) / 2>([&](auto pp) {
+                constexpr int P = decltype(pp)::value;
+                const floatx4 d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tile(2 * P, j), sel.h[x], zero, 0, 0, 0);
+                floatx4 d1 = zero;
+                if constexpr (2 * P + 1 < NT) d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tile(2 * P + 1, j), sel.h[x], zero, 0, 0, 0);
+                const u32x4 zw = {pack_upper(d0[0], d0[1]), pack_upper(d0[2], d0[3]), pack_upper(d1[0], d1[1]), pack_upper(d1[2], d1[3])};
+                out[2 * j + x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(top[P], __builtin_bit_cast(bf16x8, zw), out[2 * j + x], 0, 0, 0);
+            });
+        });
+    });
+}
+// Column of r that lanes (n, q = 0) hold in out[2 j + x]: depth slot 16 x + n of operand piece j.  A bf16 piece
+// is 32 consecutive columns; an operand cut from fp32 pieces holds columns 32 j + 4 q' + w and
+// 32 j + 16 + 4 q' + w (w = 0 .. 3) in the slots 8 q' .. 8 q' + 7.
+template <bool ZB> __device__ __forceinline__ int column_of_result(int j, int x, int n) {
+    if constexpr (ZB) return 32 * j + 16 * x + n;
+    else return 32 * j + 8 * x + 4 * (n >> 3) + 16 * ((n >> 2) & 1) + (n & 3);
 }
 
 // per-class launchers, one translation unit each (they compile in parallel)

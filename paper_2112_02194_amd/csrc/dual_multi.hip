@@ -23,8 +23,17 @@ template <int C> __device__ __forceinline__ float bcast16(float x) {
 template <int D, int M> struct MultiCfg {
     static constexpr int K = 16 * M, TRI = K * (K + 1) / 2;
     static constexpr int OFF_T = 4 * TRI, OFF_ID = OFF_T + 4 * K, OFF_DUMP = OFF_ID + 4 * K;
-    static constexpr int LDS_FLOATS = OFF_DUMP + 64;  // one dump slot per lane for stores that must not land
+    static constexpr int OFF_PARTS = OFF_DUMP + 64;  // one dump slot per lane for stores that must not land
+    // bf16 Z only: t cut into three bf16 parts plus a block of zeros, [4][4 rows][K]; the finished rows r are
+    // staged in the (by then free) triangle area
+    static constexpr int LDS_FLOATS = OFF_PARTS;
+    static constexpr int LDS_FLOATS_RESIDENT = OFF_PARTS + 16 * K;
+    static_assert(4 * TRI >= 4 * D, "the triangle area stages four rows of r");
 };
+
+// bf16 Z with two tiles per row: the gathered tiles stay in registers (4 rows x 2 tiles x D/32 operands of
+// four registers) until r = Z_I^T t is formed from them on the matrix cores, so nothing is gathered twice.
+template <int D, int M, bool ZB> constexpr bool multi_resident() { return ZB && M == 2; }
 
 // One step: the four rows list[4 blk .. 4 blk + 3] (blk * 4 < count).
 template <int D, int M, bool ZB>
@@ -84,14 +93,17 @@ __device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indp
             const int32_t id = indices[b[p] + (e < k[p] ? e : 0)];  // clamped: unconditional load
             idv[p][t] = e < k[p] ? id : (id | (int32_t)0x80000000);
         }
+    constexpr bool RES = multi_resident<D, M, ZB>();
+    float4 zkeep[RES ? 4 : 1][M][NJ];
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-        float4 z[M][NJ];
+        float4 zrow[M][NJ];
+        float4 (&z)[M][NJ] = RES ? zkeep[RES ? p : 0] : zrow;
 #pragma unroll
         for (int t = 0; t < M; ++t) {
             const int e = 16 * t + a;
             const int32_t id = idv[p][t];
-            if (q == 0) ids[p * K + e] = id & 0x7fffffff;
+            if (!RES && q == 0) ids[p * K + e] = id & 0x7fffffff;
 #pragma unroll
             for (int j = 0; j < NJ; ++j) z[t][j] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (id >= 0) {  // one masked region per tile, not one per load
@@ -234,6 +246,46 @@ __device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indp
             });
         }
     });
+    if constexpr (RES) {
+        // ---- 4. r = Z_I^T t from the tiles in registers (zt_times_t, dual_common.h); parts[x][row][e]: part
+        // x of t, x = 3 a block of zeros; the finished rows are staged in the triangle area for 8-byte stores
+        float *parts = lds + C::OFF_PARTS;
+#pragma unroll
+        for (int bk = 0; bk < M; ++bk) {
+            float x1, x2;
+            t_parts(t[bk], x1, x2);
+            const int e = g * K + 16 * bk + i;
+            parts[e] = t[bk];
+            parts[4 * K + e] = x1;
+            parts[8 * K + e] = x2;
+            parts[12 * K + e] = 0.f;
+        }
+        const SelOperands sel = make_sel(lane);
+        wave_sync();
+        const float *mine = parts + (a < 3 ? a : 3) * 4 * K + 4 * q;
+        float *rbuf = tri;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const bf16x8 top[1] = {t_operand(mine + p * K, true)};
+            floatx4 out[2 * NJ];
+#pragma unroll
+            for (int x = 0; x < 2 * NJ; ++x) out[x] = floatx4{0.f, 0.f, 0.f, 0.f};
+            zt_times_t<2, NJ>([&](int tt, int j) { return __builtin_bit_cast(bf16x8, zkeep[RES ? p : 0][tt][j]); }, top, sel, out);
+#pragma unroll
+            for (int x = 0; x < 2 * NJ; ++x)
+                *(q == 0 ? rbuf + p * D + column_of_result<true>(x >> 1, x & 1, a) : dump) = out[x][0] + out[x][1] + out[x][2];
+        }
+        wave_sync();
+        const bool col_ok = lane * CPL < D;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            if (u[p] >= 0 && col_ok) {
+                if constexpr (CPL == 2) *(float2 *)(R + u[p] * ldr + 2 * lane) = *(const float2 *)(rbuf + p * D + 2 * lane);
+                else R[u[p] * ldr + lane] = rbuf[p * D + lane];
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int bk = 0; bk < M; ++bk) tbuf[g * K + 16 * bk + i] = t[bk];
     wave_sync();
@@ -328,14 +380,14 @@ template <int D, bool ZB>
 static void launch_multi_typed(const als_csr *Y, const void *Z, float *R, int64_t ldr, int64_t r0, const int32_t *list,
                                const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
     using C = MultiCfg<D, MULTI_M>;
+    constexpr size_t lds_bytes =
+        (multi_resident<D, MULTI_M, ZB>() ? C::LDS_FLOATS_RESIDENT : C::LDS_FLOATS) * sizeof(float);
     if (g.known > 0)
-        hipLaunchKernelGGL((dual_multi_kernel<D, MULTI_M, ZB, false>), dim3(g.known), dim3(64),
-                           C::LDS_FLOATS * sizeof(float), s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list,
-                           count_dev, 0, err);
+        hipLaunchKernelGGL((dual_multi_kernel<D, MULTI_M, ZB, false>), dim3(g.known), dim3(64), lds_bytes, s,
+                           Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count_dev, 0, err);
     if (g.rest > 0)
-        hipLaunchKernelGGL((dual_multi_kernel<D, MULTI_M, ZB, true>), dim3(g.rest), dim3(64),
-                           C::LDS_FLOATS * sizeof(float), s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list,
-                           count_dev, (int)g.known, err);
+        hipLaunchKernelGGL((dual_multi_kernel<D, MULTI_M, ZB, true>), dim3(g.rest), dim3(64), lds_bytes, s,
+                           Y->indptr, Y->indices, Y->values, Z, R, ldr, r0, list, count_dev, (int)g.known, err);
 }
 
 void launch_dual_multi2(int d, const als_csr *Y, const void *Z, bool zb16, float *R, int64_t ldr, int64_t r0,

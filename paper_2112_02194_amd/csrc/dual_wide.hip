@@ -14,7 +14,11 @@ namespace als {
 //      operand) and streams the tiles t2 <= t1 past them (A operand, fetched again from the caches);
 //      each finished 16x16 tile goes to LDS, where S is kept as a lower triangle.
 //   2./3. Block elimination S = M P M^T and back-substitution by the wavefront (tri_solve.h).
-//   4. r = Z_I^T t with D/64 adjacent output columns per lane, gathering the entries a second time.
+//   4. r = Z_I^T t: from the tiles still in registers, on the matrix cores (zt_times_t, dual_common.h), where all
+//      KT tiles fit the register file next to the solver and it pays (bf16 Z; fp32 Z at d = 64); otherwise with D/64
+//      adjacent output columns per lane, gathering the entries a second time.
+template <int D, int KT, bool ZB> constexpr bool wide_resident() { return ZB || (KT <= 4 && D <= 64); }
+
 template <int D, int KT> struct WideCfg {
     static constexpr int K = 16 * KT;
     static constexpr int TRI = tri_row(K);           // lower triangle, rows padded (tri_solve.h)
@@ -32,6 +36,7 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
                                                int item, float *lds) {
     using C = WideCfg<D, KT>;
     constexpr int K = C::K, NJ = z_pieces<D, ZB>();
+    constexpr bool RES = wide_resident<D, KT, ZB>();
     float *tri = lds, *aux = lds + C::OFF_COL, *tbuf = lds + C::OFF_T;
     int32_t *ids = (int32_t *)(lds + C::OFF_ID);
     const int lane = opaque_tid(), a = lane & 15, q = lane >> 4;
@@ -46,12 +51,12 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
         const int e = 16 * t + a;
         const int32_t id = indices[b + (e < k ? e : 0)];  // a slot past k: the row's first entry (meets t = 0 below)
         myid[t] = e < k ? id : -1;
-        if (q == 0) ids[e] = id;
+        if (!RES && q == 0) ids[e] = id;
     }
     // the first RT tiles stay in registers for the whole phase (one round of loads, all in flight
     // together), already cut into the hi/lo bf16 operands of the split products (dual_common.h); later
     // tiles are fetched and cut when they are needed
-    constexpr int RT = KT < 5 ? KT : (KT < 7 ? 5 : 4);
+    constexpr int RT = RES ? KT : (KT < 5 ? KT : (KT < 7 ? 5 : 4));
     typedef TileOperand<D, ZB> Op;
     auto fetch = [&](int t, float4 (&raw)[NJ]) {
 #pragma unroll
@@ -112,8 +117,46 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
         tri_solve<K>(tri, aux, tbuf, y0, y1, k, err_flag);
     }
 
-    // ---- 4. r = Z_I^T t, D/64 adjacent output columns per lane (second gather of the row's entries)
-    {
+    // ---- 4. r = Z_I^T t
+    if constexpr (RES) {
+        // the triangle is free now: the remainders of the cut of t, a block of zeros and the finished row go there
+        static_assert(tri_row(K) >= 3 * K + D, "the triangle area holds the parts of t and the row");
+        float *p1 = tri, *p2 = tri + K, *zeros = tri + 2 * K, *rbuf = tri + 3 * K;
+#pragma unroll
+        for (int e0 = 0; e0 < K; e0 += 64) {
+            const int e = e0 + lane;
+            if (e < K) {
+                float x1, x2;
+                t_parts(tbuf[e], x1, x2);
+                p1[e] = x1;
+                p2[e] = x2;
+                zeros[e] = 0.f;
+            }
+        }
+        const SelOperands sel = make_sel(lane);
+        wave_sync();
+        const float *mine = (a == 0 ? tbuf : (a == 1 ? p1 : (a == 2 ? p2 : zeros))) + 4 * q;
+        bf16x8 top[(KT + 1) / 2];
+#pragma unroll
+        for (int P = 0; P < (KT + 1) / 2; ++P) top[P] = t_operand(mine + 32 * P, 2 * P + 1 < KT);
+        constexpr int NP = D / 32;
+        floatx4 out[2 * NP];
+#pragma unroll
+        for (int x = 0; x < 2 * NP; ++x) out[x] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (ZB) {
+            zt_times_t<KT, NP>([&](int t, int j) { return __builtin_bit_cast(bf16x8, zop[t].v[j]); }, top, sel, out);
+        } else {  // z = hi + lo, both exact bf16 numbers
+            zt_times_t<KT, NP>([&](int t, int j) { return zop[t].v[j].hi; }, top, sel, out);
+            zt_times_t<KT, NP>([&](int t, int j) { return zop[t].v[j].lo; }, top, sel, out);
+        }
+        float *dump = aux + 128 + lane;  // the solver's per-lane dump slots
+#pragma unroll
+        for (int x = 0; x < 2 * NP; ++x)
+            *(q == 0 ? rbuf + column_of_result<ZB>(x >> 1, x & 1, a) : dump) = out[x][0] + out[x][1] + out[x][2];
+        wave_sync();
+        if constexpr (D >= 128) *(float2 *)(R + u * ldr + 2 * lane) = *(const float2 *)(rbuf + 2 * lane);
+        else R[u * ldr + lane] = rbuf[lane];
+    } else {
         constexpr int CPL = D / 64;
         float rv[CPL];
 #pragma unroll
@@ -144,7 +187,7 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
 // The two launch forms of a step kernel (see StepGrid): one row per workgroup, or a grid-stride walk from
 // row first_item to the end of the list.
 template <int D, int KT, bool ZB, bool LOOP>
-__global__ __launch_bounds__(64, LOOP ? 1 : 2) void dual_wide_kernel(const int64_t *__restrict__ indptr,
+__global__ __launch_bounds__(64, (LOOP || KT >= 7) ? 1 : 2) void dual_wide_kernel(const int64_t *__restrict__ indptr,
                                                           const int32_t *__restrict__ indices,
                                                           const float *__restrict__ values,
                                                           const void *__restrict__ Z, float *__restrict__ R,

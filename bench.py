@@ -98,6 +98,10 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--rows", type=int, default=0, help="override the node count (debugging only; invalidates the line)")
     ap.add_argument("--path", default="auto", choices=["auto", "primal"])
+    ap.add_argument("--solver", default="direct", choices=["direct", "cg", "cg_free"],
+                    help="direct (default, the headline line); cg: conjugate gradients on the dual / assembled systems; "
+                         "cg_free: matrix-free conjugate gradients (solver variants of Sec. 4.5, reported beside the default)")
+    ap.add_argument("--cg-tol", type=float, default=1e-6)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="run the library's plain copy kernel on this many MiB first (counter calibration when profiling)")
@@ -131,7 +135,9 @@ def main():
     Y = als.Csr(m, n, p.indptr, p.indices)
     Yt = als.Csr(n, m, p.t_indptr, p.t_indices)
     W, H = p.W0.clone(), p.H0.clone()
-    prm = als.make_params(p.alpha, p.lam, path=als.PATH_PRIMAL if args.path == "primal" else als.PATH_AUTO)
+    solver = {"direct": als.SOLVER_DIRECT, "cg": als.SOLVER_CG, "cg_free": als.SOLVER_CG_FREE}[args.solver]
+    prm = als.make_params(p.alpha, p.lam, path=als.PATH_PRIMAL if args.path == "primal" else als.PATH_AUTO,
+                          solver=solver, cg_tol=args.cg_tol if solver else 0.0)
     als.als_check_csr(ctx, Y)
     als.als_check_csr(ctx, Yt)
 
@@ -189,7 +195,13 @@ def main():
     kernel_names = {"dual_k4": f"dual_small_kernel<{d},4,{zbt},false>", "dual_k8": f"dual_small_kernel<{d},8,{zbt},false>",
                     "dual_k16": f"dual_rows_kernel<{d},{zbt},false>", "dual_k32": f"dual_multi_kernel<{d},2,{zbt},false>"}
     for c in range(2, 8):
-        kernel_names[f"dual_k{16 * (c + 1)}"] = f"dual_wide_kernel<{d},{c + 1},{zbt},false>"
+        kernel_names[f"dual_k{16 * (c + 1)}"] = f"dual_wide_kernel<{d},{c + 1},{zbt},false,false>"
+    if args.solver == "cg" and d >= 64:  # every class runs the one-row-per-wavefront kernel with the CG solver
+        for name, _, hi in bounds:
+            kernel_names[name] = f"dual_wide_kernel<{d},{max(3, hi // 16)},{zbt},true,true>"
+    if args.solver == "cg_free":
+        for name, _, _ in bounds:
+            kernel_names[name] = f"cg_free_kernel<{d},{bft}>"
     kernel_names.update({"gramian": f"gramian_bf16_kernel<{d}>" if (es == 2 and d >= 64) else f"gramian_partial_kernel<{d},{bft}>",
                          "transform_z": f"transform16_kernel<{d},true,true>" if zbt == "true"      # Z = V L^-T
                          else f"transform_kernel<{d},{bft},false,true>",
@@ -198,6 +210,8 @@ def main():
                          "primal": f"primal_kernel<{d},{bft},0,false>",               # one workgroup per row
                          "segment": f"primal_kernel<{d},{bft},1,false>"})             # segments of long rows
     zs = 2 if (es == 2 and d >= 32) else 4  # bytes per element of the transformed table Z the dual kernels gather
+    if args.solver == "cg_free":
+        zs = es  # the matrix-free solver gathers the fixed table itself (at least once)
     work = {}
     long_nnz = prim_rows = prim_nnz = 0
     for kdeg in deg.values():
@@ -255,7 +269,7 @@ def main():
         "dtype": "f32" if es == 4 else "bf16-stored/f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {m}x{n} link matrix, nnz={nnz}, d={d}, "
                                f"alpha={p.alpha}, lambda={p.lam}, 1 epoch = 2 half-epochs + 2 Gramians",
-                   "path": args.path, "row_deg_mean": stats["row_deg_mean"], "col_deg_max": stats["col_deg_max"]},
+                   "path": args.path, "solver": args.solver, "row_deg_mean": stats["row_deg_mean"], "col_deg_max": stats["col_deg_max"]},
         "epoch_ms": ms_per_step, "rows_per_sec": (m + n) / (ms_per_step * 1e-3),
         "loss_after": loss,
         "roofline": roof,

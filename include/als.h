@@ -68,13 +68,21 @@ typedef struct {
     als_dtype dtype; /* ALS_F32, or ALS_BF16 (Section 4.4: bf16 storage, fp32 arithmetic) */
 } als_table;
 
-/* How the d x d systems of the primal form are solved (Section 4.5 compares such solvers):
- *   ALS_SOLVER_DIRECT : Cholesky-type factorisation (exact up to rounding).
- *   ALS_SOLVER_CG     : conjugate gradients on the assembled system, started from the row's current
- *                       content in X (warm start), stopped when |residual| <= cg_tol * |b| or after
- *                       cg_max_iters iterations.  The paper's own choice on TPU.
- * Rows solved in the dual (k x k) form always use the direct solver. */
-typedef enum { ALS_SOLVER_DIRECT = 0, ALS_SOLVER_CG = 1 } als_solver;
+/* How a row's linear system is solved (Section 4.5 compares such solvers and settles on conjugate gradients):
+ *   ALS_SOLVER_DIRECT  : Cholesky-type factorisation (exact up to rounding), of the d x d system of rows taking
+ *                        the primal form and of the k x k system of rows taking the dual form.
+ *   ALS_SOLVER_CG      : conjugate gradients on the assembled system, stopped when |residual| <= cg_tol * |b|
+ *                        (or <= 1e-15, below which fp32 squares of it carry no information) or after
+ *                        cg_max_iters iterations.  Rows taking the primal form start from their
+ *                        current content in X (warm start; X must hold finite numbers); rows taking the dual
+ *                        form solve their k x k system from zero (available for d >= 64; for smaller d every
+ *                        row takes the primal form under this solver).
+ *   ALS_SOLVER_CG_FREE : conjugate gradients on the d x d system without assembling it: a product with the
+ *                        row's matrix is taken as (alpha G + lambda I) p + V_I^T (V_I p), the first term for
+ *                        sixteen rows at a time as one matrix product.  Used for the rows that ALS_PATH_AUTO /
+ *                        ALS_PATH_DUAL would solve in the dual form (0 < k <= dual_max_k), warm-started from X;
+ *                        longer rows, and every row under ALS_PATH_PRIMAL, are solved as with ALS_SOLVER_CG. */
+typedef enum { ALS_SOLVER_DIRECT = 0, ALS_SOLVER_CG = 1, ALS_SOLVER_CG_FREE = 2 } als_solver;
 
 typedef struct {
     float alpha;        /* weight of the all-pairs term of Eq. 3, >= 0                         */
@@ -84,7 +92,7 @@ typedef struct {
                            form, clipped to what the table's d supports                          */
     int32_t split_nnz;  /* 0 = library default; rows longer than this are cut into segments whose
                            partial statistics are summed (Section 4.3's row splitting)           */
-    int32_t solver;       /* als_solver, for rows taking the primal form                         */
+    int32_t solver;       /* als_solver                                                          */
     int32_t cg_max_iters; /* 0 = library default (2*d)                                           */
     float cg_tol;         /* 0 = library default (1e-6); relative residual at which CG stops     */
 } als_params;

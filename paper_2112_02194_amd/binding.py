@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libals.so")
 ALS_OK, ALS_EINVAL, ALS_ESHAPE, ALS_EDTYPE, ALS_EALIAS, ALS_ENOTSPD, ALS_ENOMEM, ALS_EHIP = range(8)
 ALS_F32, ALS_BF16 = 0, 1
 PATH_AUTO, PATH_PRIMAL, PATH_DUAL = 0, 1, 2
-SOLVER_DIRECT, SOLVER_CG = 0, 1
+SOLVER_DIRECT, SOLVER_CG, SOLVER_CG_FREE = 0, 1, 2
 
 EXPORTS = ["als_create", "als_destroy", "als_gramian", "als_solve_rows", "als_epoch", "als_loss",
            "als_status_sync", "als_check_csr", "als_copy_probe", "als_set_timing", "als_get_timing",

@@ -24,6 +24,7 @@ UNITS = [
     ("solve_rows.hip", "solve_rows", []),
     ("loss.hip", "loss", []),
     ("topk.hip", "topk", []),
+    ("cg_free.hip", "cg_free", []),
     ("dual_prepare.hip", "dual_prepare", []),
     ("dual_rows.hip", "dual_rows", []),
     ("dual_small.hip", "dual_small_g8", ["-DSMALL_G=8"]),

@@ -92,7 +92,7 @@ static als_status check_params(als_ctx *ctx, const als_params *p) {
     if (p->path < 0 || p->path > 2) return fail(ctx, ALS_EINVAL, "unknown path");
     if (p->dual_max_k < 0 || p->dual_max_k > 128) return fail(ctx, ALS_EINVAL, "dual_max_k must be in [0, 128]");
     if (p->split_nnz < 0) return fail(ctx, ALS_EINVAL, "split_nnz must be >= 0");
-    if (p->solver < 0 || p->solver > 1) return fail(ctx, ALS_EINVAL, "unknown solver");
+    if (p->solver < 0 || p->solver > 2) return fail(ctx, ALS_EINVAL, "unknown solver");
     if (p->cg_max_iters < 0 || !(p->cg_tol >= 0.0f)) return fail(ctx, ALS_EINVAL, "bad CG parameters");
     return ALS_OK;
 }

@@ -246,6 +246,19 @@ template <bool ZB> __device__ __forceinline__ int column_of_result(int j, int x,
     else return 32 * j + 8 * x + 4 * (n >> 3) + 16 * ((n >> 2) & 1) + (n & 3);
 }
 
+// The conjugate-gradient solvers work with squared residual norms: below this the squares lose their bits to
+// the bottom of the fp32 range and step lengths formed from them are noise, so a residual with |r|^2 at or
+// below it (|r| <= 1e-15) counts as converged whatever the right-hand side's size.
+constexpr float CG_RESIDUAL_FLOOR = 1e-30f;
+
+// How the one-row-per-wavefront kernels solve their k x k system: the panel elimination, or conjugate gradients
+// with these limits.
+struct WideSolver {
+    bool cg;
+    int iters;
+    float tol;
+};
+
 // per-class launchers, one translation unit each (they compile in parallel)
 // (`count_dev`: device address of the list's length; `g`: see StepGrid)
 // `zb16`: Z is stored as bf16

@@ -32,7 +32,7 @@ void launch_dual_multi2(int d, const als_csr *Y, const void *Z, bool zb16, float
 #define ALS_DECL_WIDE(kt)                                                                                          \
     als_status launch_dual_wide##kt(als_ctx *ctx, int d, const als_csr *Y, const void *Z, bool zb16, float *R,     \
                                     int64_t ldr, int64_t r0, const int32_t *list, const int32_t *count_dev,        \
-                                    StepGrid g, int32_t *err, hipStream_t s);
+                                    StepGrid g, int32_t *err, const WideSolver &ws, hipStream_t s);
 ALS_DECL_WIDE(3) ALS_DECL_WIDE(4) ALS_DECL_WIDE(5) ALS_DECL_WIDE(6) ALS_DECL_WIDE(7) ALS_DECL_WIDE(8)
 #undef ALS_DECL_WIDE
 
@@ -329,8 +329,9 @@ static als_status dual_prepare_typed(als_ctx *ctx, const als_table *V, const flo
 // the lengths seen by the previous call on the same matrix, or -1.
 template <int D, bool BF16>
 static als_status dual_rows_typed(als_ctx *ctx, const als_csr *Y, als_table *X, int64_t r0, int64_t r1,
-                                  int dual_max, const int32_t *const lists[10], const int32_t *const counts_dev[10],
-                                  const int64_t caps[10], const int hints[10], hipStream_t s) {
+                                  int dual_max, const als_params *prm, const int32_t *const lists[10],
+                                  const int32_t *const counts_dev[10], const int64_t caps[10], const int hints[10],
+                                  hipStream_t s) {
     float *R = (float *)X->data;
     int64_t ldr = X->ld;
     if (BF16) {
@@ -357,17 +358,29 @@ static als_status dual_rows_typed(als_ctx *ctx, const als_csr *Y, als_table *X, 
         call;                                           \
         timer_end(ctx, s);                              \
     }
+    // conjugate gradients on the k x k systems (Section 4.5's solver): every class goes through the
+    // one-row-per-wavefront kernel, the classes up to k = 32 through its smallest instance
+    const WideSolver ws = {prm->solver == ALS_SOLVER_CG, prm->cg_max_iters > 0 ? prm->cg_max_iters : 2 * D,
+                           prm->cg_tol > 0.f ? prm->cg_tol : 1e-6f};
+    if (ws.cg) {
+        if constexpr (D < 64) return fail(ctx, ALS_EINVAL, "conjugate gradients on the dual systems need d >= 64");
+        ALS_TIMED_CLASS(T_DUAL_CLASS0 + 1, 1, 1, (stb = launch_dual_wide3(ctx, D, Y, Z, zb16, R, ldr, r0, lists[1], counts_dev[1], g, err, ws, s)))
+        ALS_TIMED_CLASS(T_DUAL_CLASS0, 0, 1, (stb = launch_dual_wide3(ctx, D, Y, Z, zb16, R, ldr, r0, lists[0], counts_dev[0], g, err, ws, s)))
+        ALS_TIMED_CLASS(T_SMALL8, 9, 1, (stb = launch_dual_wide3(ctx, D, Y, Z, zb16, R, ldr, r0, lists[9], counts_dev[9], g, err, ws, s)))
+        ALS_TIMED_CLASS(T_SMALL4, 8, 1, (stb = launch_dual_wide3(ctx, D, Y, Z, zb16, R, ldr, r0, lists[8], counts_dev[8], g, err, ws, s)))
+    } else {
     ALS_TIMED_CLASS(T_DUAL_CLASS0 + 1, 1, 4, (launch_dual_multi2(D, Y, Z, zb16, R, ldr, r0, lists[1], counts_dev[1], g, err, s)))
     ALS_TIMED_CLASS(T_DUAL_CLASS0, 0, 4, (launch_dual_k16(D, Y, Z, zb16, R, ldr, r0, lists[0], counts_dev[0], g, err, s)))
     // 5 <= k <= 8 and k <= 4: several rows per MFMA tile
     ALS_TIMED_CLASS(T_SMALL8, 9, 8, (launch_dual_small8(D, Y, Z, zb16, R, ldr, r0, lists[9], counts_dev[9], g, err, s)))
     ALS_TIMED_CLASS(T_SMALL4, 8, 16, (launch_dual_small4(D, Y, Z, zb16, R, ldr, r0, lists[8], counts_dev[8], g, err, s)))
-    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 2, 2, 1, (stb = launch_dual_wide3(ctx, D, Y, Z, zb16, R, ldr, r0, lists[2], counts_dev[2], g, err, s)))
-    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 3, 3, 1, (stb = launch_dual_wide4(ctx, D, Y, Z, zb16, R, ldr, r0, lists[3], counts_dev[3], g, err, s)))
-    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 4, 4, 1, (stb = launch_dual_wide5(ctx, D, Y, Z, zb16, R, ldr, r0, lists[4], counts_dev[4], g, err, s)))
-    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 5, 5, 1, (stb = launch_dual_wide6(ctx, D, Y, Z, zb16, R, ldr, r0, lists[5], counts_dev[5], g, err, s)))
-    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 6, 6, 1, (stb = launch_dual_wide7(ctx, D, Y, Z, zb16, R, ldr, r0, lists[6], counts_dev[6], g, err, s)))
-    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 7, 7, 1, (stb = launch_dual_wide8(ctx, D, Y, Z, zb16, R, ldr, r0, lists[7], counts_dev[7], g, err, s)))
+    }
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 2, 2, 1, (stb = launch_dual_wide3(ctx, D, Y, Z, zb16, R, ldr, r0, lists[2], counts_dev[2], g, err, ws, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 3, 3, 1, (stb = launch_dual_wide4(ctx, D, Y, Z, zb16, R, ldr, r0, lists[3], counts_dev[3], g, err, ws, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 4, 4, 1, (stb = launch_dual_wide5(ctx, D, Y, Z, zb16, R, ldr, r0, lists[4], counts_dev[4], g, err, ws, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 5, 5, 1, (stb = launch_dual_wide6(ctx, D, Y, Z, zb16, R, ldr, r0, lists[5], counts_dev[5], g, err, ws, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 6, 6, 1, (stb = launch_dual_wide7(ctx, D, Y, Z, zb16, R, ldr, r0, lists[6], counts_dev[6], g, err, ws, s)))
+    ALS_TIMED_CLASS(T_DUAL_CLASS0 + 7, 7, 1, (stb = launch_dual_wide8(ctx, D, Y, Z, zb16, R, ldr, r0, lists[7], counts_dev[7], g, err, ws, s)))
 #undef ALS_TIMED_CLASS
     if (stb != ALS_OK) return stb;
     timer_begin(ctx, T_TRANSFORM_X, s);
@@ -405,14 +418,14 @@ als_status launch_dual_prepare(als_ctx *ctx, const als_table *V, const float *G,
 }
 
 als_status launch_dual_rows(als_ctx *ctx, const als_csr *Y, als_table *X, int64_t r0, int64_t r1, int dual_max,
-                            const int32_t *const lists[10], const int32_t *const counts[10], const int64_t caps[10],
-                            const int hints[10], hipStream_t s) {
+                            const als_params *prm, const int32_t *const lists[10], const int32_t *const counts[10],
+                            const int64_t caps[10], const int hints[10], hipStream_t s) {
     const bool bf = X->dtype == ALS_BF16;
     switch (X->d) {
-        case 16: return bf ? dual_rows_typed<16, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, caps, hints, s) : dual_rows_typed<16, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, caps, hints, s);
-        case 32: return bf ? dual_rows_typed<32, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, caps, hints, s) : dual_rows_typed<32, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, caps, hints, s);
-        case 64: return bf ? dual_rows_typed<64, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, caps, hints, s) : dual_rows_typed<64, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, caps, hints, s);
-        case 128: return bf ? dual_rows_typed<128, true>(ctx, Y, X, r0, r1, dual_max, lists, counts, caps, hints, s) : dual_rows_typed<128, false>(ctx, Y, X, r0, r1, dual_max, lists, counts, caps, hints, s);
+        case 16: return bf ? dual_rows_typed<16, true>(ctx, Y, X, r0, r1, dual_max, prm, lists, counts, caps, hints, s) : dual_rows_typed<16, false>(ctx, Y, X, r0, r1, dual_max, prm, lists, counts, caps, hints, s);
+        case 32: return bf ? dual_rows_typed<32, true>(ctx, Y, X, r0, r1, dual_max, prm, lists, counts, caps, hints, s) : dual_rows_typed<32, false>(ctx, Y, X, r0, r1, dual_max, prm, lists, counts, caps, hints, s);
+        case 64: return bf ? dual_rows_typed<64, true>(ctx, Y, X, r0, r1, dual_max, prm, lists, counts, caps, hints, s) : dual_rows_typed<64, false>(ctx, Y, X, r0, r1, dual_max, prm, lists, counts, caps, hints, s);
+        case 128: return bf ? dual_rows_typed<128, true>(ctx, Y, X, r0, r1, dual_max, prm, lists, counts, caps, hints, s) : dual_rows_typed<128, false>(ctx, Y, X, r0, r1, dual_max, prm, lists, counts, caps, hints, s);
     }
     return fail(ctx, ALS_EDTYPE, "unsupported d");
 }

@@ -1,6 +1,7 @@
 // Dual row update for 32 < k <= 128 (d = 128; k <= 64 also at d = 64), compiled once per class with
 // -DWIDE_KT=3..8 (k <= 16*WIDE_KT).  The algebra is in the header comment of dual_prepare.hip.
 #include "dual_common.h"
+#include "tri_cg.h"
 #include "tri_solve.h"
 
 #ifndef WIDE_KT
@@ -28,12 +29,13 @@ template <int D, int KT> struct WideCfg {
     static constexpr int LDS_FLOATS = OFF_ID + K;
 };
 
-template <int D, int KT, bool ZB>
+// CG: the k x k system is solved by conjugate gradients (tri_cg.h) instead of the panel elimination.
+template <int D, int KT, bool ZB, bool CG>
 __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indptr, const int32_t *__restrict__ indices,
                                                const float *__restrict__ values, const void *__restrict__ Z,
                                                float *__restrict__ R, int64_t ldr, int64_t r0,
                                                const int32_t *__restrict__ list, int32_t *__restrict__ err_flag,
-                                               int item, float *lds) {
+                                               int item, float *lds, int cg_iters, float cg_tol) {
     using C = WideCfg<D, KT>;
     constexpr int K = C::K, NJ = z_pieces<D, ZB>();
     constexpr bool RES = wide_resident<D, KT, ZB>();
@@ -114,7 +116,8 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
         float y0 = 0.f, y1 = 0.f;
         if (lane < k) y0 = values ? values[b + lane] : 1.f;
         if (64 + lane < k) y1 = values ? values[b + 64 + lane] : 1.f;
-        tri_solve<K>(tri, aux, tbuf, y0, y1, k, err_flag);
+        if constexpr (CG) tri_cg<K>(tri, aux, tbuf, y0, y1, k, cg_iters, cg_tol);
+        else tri_solve<K>(tri, aux, tbuf, y0, y1, k, err_flag);
     }
 
     // ---- 4. r = Z_I^T t
@@ -186,23 +189,25 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
 
 // The two launch forms of a step kernel (see StepGrid): one row per workgroup, or a grid-stride walk from
 // row first_item to the end of the list.
-template <int D, int KT, bool ZB, bool LOOP>
+template <int D, int KT, bool ZB, bool LOOP, bool CG>
 __global__ __launch_bounds__(64, (LOOP || KT >= 7) ? 1 : 2) void dual_wide_kernel(const int64_t *__restrict__ indptr,
                                                           const int32_t *__restrict__ indices,
                                                           const float *__restrict__ values,
                                                           const void *__restrict__ Z, float *__restrict__ R,
                                                           int64_t ldr, int64_t r0, const int32_t *__restrict__ list,
                                                           const int32_t *__restrict__ count_ptr, int first_item,
-                                                          int32_t *__restrict__ err_flag) {
+                                                          int32_t *__restrict__ err_flag, int cg_iters, float cg_tol) {
     extern __shared__ float lds[];
     const int count = *count_ptr;
     int item = first_item + blockIdx.x;
     if constexpr (!LOOP) {
-        if (item < count) dual_wide_step<D, KT, ZB>(indptr, indices, values, Z, R, ldr, r0, list, err_flag, item, lds);
+        if (item < count)
+            dual_wide_step<D, KT, ZB, CG>(indptr, indices, values, Z, R, ldr, r0, list, err_flag, item, lds, cg_iters, cg_tol);
     } else {
         for (; item < count; item += gridDim.x) {
-            dual_wide_step<D, KT, ZB>(opaque(indptr), opaque(indices), opaque(values), opaque(Z), opaque(R), opaque(ldr),
-                                  opaque(r0), opaque(list), opaque(err_flag), item, opaque(lds));
+            dual_wide_step<D, KT, ZB, CG>(opaque(indptr), opaque(indices), opaque(values), opaque(Z), opaque(R),
+                                          opaque(ldr), opaque(r0), opaque(list), opaque(err_flag), item, opaque(lds),
+                                          opaque(cg_iters), opaque(cg_tol));
             wave_sync();  // the next step reuses the LDS buffers
         }
     }
@@ -213,11 +218,21 @@ __global__ __launch_bounds__(64, (LOOP || KT >= 7) ? 1 : 2) void dual_wide_kerne
 
 template <int D, bool ZB>
 static als_status wide_typed(als_ctx *ctx, const als_csr *Y, const void *Z, float *R, int64_t ldr, int64_t r0,
-                             const int32_t *list, const int32_t *count_dev, StepGrid g, int32_t *err, hipStream_t s) {
+                             const int32_t *list, const int32_t *count_dev, StepGrid g, int32_t *err, const WideSolver &ws,
+                             hipStream_t s) {
     using C = WideCfg<D, WIDE_KT>;
-    auto kern = dual_wide_kernel<D, WIDE_KT, ZB, false>;
-    auto kern_loop = dual_wide_kernel<D, WIDE_KT, ZB, true>;
     constexpr int lds_bytes = (int)(C::LDS_FLOATS * sizeof(float));
+    if (ws.cg) {  // only the grid-stride form exists with this solver: one launch covers the list
+        auto kern_cg = dual_wide_kernel<D, WIDE_KT, ZB, true, true>;
+        static const hipError_t attr_cg =
+            hipFuncSetAttribute((const void *)kern_cg, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        ALS_HIP(ctx, attr_cg);
+        hipLaunchKernelGGL(kern_cg, dim3(g.known + g.rest), dim3(64), lds_bytes, s, Y->indptr, Y->indices, Y->values, Z,
+                           R, ldr, r0, list, count_dev, 0, err, ws.iters, ws.tol);
+        return ALS_OK;
+    }
+    auto kern = dual_wide_kernel<D, WIDE_KT, ZB, false, false>;
+    auto kern_loop = dual_wide_kernel<D, WIDE_KT, ZB, true, false>;
     static const hipError_t attr = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     static const hipError_t attr_loop =
         hipFuncSetAttribute((const void *)kern_loop, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);  // both once per process
@@ -225,24 +240,24 @@ static als_status wide_typed(als_ctx *ctx, const als_csr *Y, const void *Z, floa
     ALS_HIP(ctx, attr_loop);
     if (g.known > 0)
         hipLaunchKernelGGL(kern, dim3(g.known), dim3(64), lds_bytes, s, Y->indptr, Y->indices, Y->values, Z, R, ldr, r0,
-                           list, count_dev, 0, err);
+                           list, count_dev, 0, err, 0, 0.f);
     if (g.rest > 0)
         hipLaunchKernelGGL(kern_loop, dim3(g.rest), dim3(64), lds_bytes, s, Y->indptr, Y->indices, Y->values, Z, R, ldr,
-                           r0, list, count_dev, (int)g.known, err);
+                           r0, list, count_dev, (int)g.known, err, 0, 0.f);
     return ALS_OK;
 }
 
 als_status ALS_WIDE_NAME(WIDE_KT)(als_ctx *ctx, int d, const als_csr *Y, const void *Z, bool zb16, float *R, int64_t ldr,
                                   int64_t r0, const int32_t *list, const int32_t *count_dev, StepGrid g,
-                                  int32_t *err, hipStream_t s) {
+                                  int32_t *err, const WideSolver &ws, hipStream_t s) {
     if (g.known == 0 && g.rest == 0) return ALS_OK;
     if (d == 128)
-        return zb16 ? wide_typed<128, true>(ctx, Y, Z, R, ldr, r0, list, count_dev, g, err, s)
-                    : wide_typed<128, false>(ctx, Y, Z, R, ldr, r0, list, count_dev, g, err, s);
+        return zb16 ? wide_typed<128, true>(ctx, Y, Z, R, ldr, r0, list, count_dev, g, err, ws, s)
+                    : wide_typed<128, false>(ctx, Y, Z, R, ldr, r0, list, count_dev, g, err, ws, s);
     if constexpr (WIDE_KT <= 4) {  // the dual form reaches k <= 64 at d = 64
         if (d == 64)
-            return zb16 ? wide_typed<64, true>(ctx, Y, Z, R, ldr, r0, list, count_dev, g, err, s)
-                        : wide_typed<64, false>(ctx, Y, Z, R, ldr, r0, list, count_dev, g, err, s);
+            return zb16 ? wide_typed<64, true>(ctx, Y, Z, R, ldr, r0, list, count_dev, g, err, ws, s)
+                        : wide_typed<64, false>(ctx, Y, Z, R, ldr, r0, list, count_dev, g, err, ws, s);
     }
     return fail(ctx, ALS_EDTYPE, "wide dual kernel: unsupported d");
 }

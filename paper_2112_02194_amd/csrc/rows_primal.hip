@@ -317,13 +317,14 @@ __device__ __forceinline__ void cg_solve_lds(const float *a, float *aux, int max
     float pv = r;
     const float bb = block_dot<D>(b * b, red);
     float rs = block_dot<D>(r * r, red);
-    const float stop = tol * tol * bb;
+    const float stop = fmaxf(tol * tol * bb, CG_RESIDUAL_FLOOR);
     for (int it = 0; it < max_iters && rs > stop; ++it) {
         __syncthreads();
         if (mine) pvec[i] = pv;
         __syncthreads();
         const float ap = matvec(pvec);
         const float pap = block_dot<D>(pv * ap, red);
+        if (!(pap > 0.f)) break;  // only when the numbers have left the fp32 range; the same in every thread
         const float alpha = rs / pap;
         x += alpha * pv;
         r -= alpha * ap;

@@ -18,8 +18,11 @@ als_status launch_primal_long(als_ctx *ctx, const als_csr *Y, const als_table *V
 als_status launch_dual_prepare(als_ctx *ctx, const als_table *V, const float *G, const als_params *prm,
                                hipStream_t s);
 als_status launch_dual_rows(als_ctx *ctx, const als_csr *Y, als_table *X, int64_t r0, int64_t r1, int dual_max,
-                            const int32_t *const lists[10], const int32_t *const counts_dev[10],
+                            const als_params *prm, const int32_t *const lists[10], const int32_t *const counts_dev[10],
                             const int64_t caps[10], const int hints[10], hipStream_t s);
+als_status launch_cg_free(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G, const als_params *prm,
+                          als_table *X, int64_t r0, const int32_t *const lists[10], const int32_t *const counts_dev[10],
+                          const int64_t caps[10], const int hints[10], hipStream_t s);
 int dual_supported_max_k(int d);
 
 constexpr int DEFAULT_SPLIT = 512;
@@ -202,7 +205,13 @@ __global__ void publish_counts_kernel(int32_t *__restrict__ counters, int64_t ca
 }
 
 als_status launch_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V, const float *G,
-                             const als_params *prm, als_table *X, int64_t r0, int64_t r1, hipStream_t s) {
+                             const als_params *prm_in, als_table *X, int64_t r0, int64_t r1, hipStream_t s) {
+    // ALS_SOLVER_CG_FREE: the rows of the class lists never see an assembled system; longer rows take
+    // conjugate gradients on their assembled one
+    const bool cg_free = prm_in->solver == ALS_SOLVER_CG_FREE;
+    als_params prm_rows = *prm_in;
+    if (cg_free) prm_rows.solver = ALS_SOLVER_CG;
+    const als_params *prm = &prm_rows;
     const int64_t nrows = r1 - r0;
     if (nrows > INT32_MAX) return fail(ctx, ALS_EINVAL, "row range longer than 2^31-1: call per sub-range");
     const int64_t split = prm->split_nnz > 0 ? prm->split_nnz : DEFAULT_SPLIT;
@@ -211,6 +220,8 @@ als_status launch_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V,
         dual_max = dual_supported_max_k(V->d);
         if (prm->dual_max_k > 0 && prm->dual_max_k < dual_max) dual_max = prm->dual_max_k;
         if (dual_max > split) dual_max = (int)split;
+        // conjugate gradients on the k x k systems run in the one-row-per-wavefront kernels, which exist for d >= 64
+        if (prm_in->solver == ALS_SOLVER_CG && V->d < 64) dual_max = 0;
     }
     // list capacities: class c (k > 16(c-1)) holds at most nnz/(16(c-1)+1) rows, the mid list at most
     // nnz/(dual_max+1)
@@ -287,7 +298,7 @@ als_status launch_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V,
     timer_end(ctx, s);
     ALS_HIP(ctx, hipGetLastError());
 
-    if (dual_max > 0) {
+    if (dual_max > 0 && !cg_free) {
         if ((st = launch_dual_prepare(ctx, V, G, prm, s)) != ALS_OK) return st;
     }
     // segments: at most 2 nnz / split + 1 of them exist, and never more than the workspace holds
@@ -310,7 +321,9 @@ als_status launch_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V,
             caps[c] = off[c + 1] - off[c];
             hints[c] = hint[ci];
         }
-        if ((st = launch_dual_rows(ctx, Y, X, r0, r1, dual_max, lists, counts_dev, caps, hints, s)) != ALS_OK) return st;
+        st = cg_free ? launch_cg_free(ctx, Y, V, G, prm, X, r0, lists, counts_dev, caps, hints, s)
+                     : launch_dual_rows(ctx, Y, X, r0, r1, dual_max, prm, lists, counts_dev, caps, hints, s);
+        if (st != ALS_OK) return st;
     }
     return ALS_OK;
 }

@@ -110,12 +110,8 @@ def test_dual_threshold_sweep(ctx, gpu_device, dual_max_k):
                 row_range=(3, 590))
 
 
-@pytest.mark.parametrize("d,dtype", [(128, "f32"), (64, "f32"), (128, "bf16"), (32, "f32")])
-def test_every_row_length_0_to_140(ctx, gpu_device, d, dtype):
-    """Rows with exactly k = 0, 1, ..., 140 stored entries, four of each, in shuffled order: every boundary
-    between the row classes (4|5, 8|9, 16|17, 32|33, 48|49, ..., 128|129 and the switch to the d x d
-    system) is crossed, with general labels."""
-    say(f"solve_rows auto, every row length 0..140, d={d} {dtype}")
+def _every_row_length_problem(d, dtype):
+    """Rows with exactly k = 0, 1, ..., 140 stored entries, four of each, in shuffled order, general labels."""
     p = make_problem("c1", rows=4 * 141, cols=3000, d=d, values="uniform", dtype=dtype)
     gen = torch.Generator().manual_seed(20211206 + d)
     lengths = (torch.arange(4 * 141) % 141)[torch.randperm(4 * 141, generator=gen)]
@@ -124,7 +120,58 @@ def test_every_row_length_0_to_140(ctx, gpu_device, d, dtype):
     p.indptr[1:] = torch.cumsum(lengths, 0)
     p.indices = torch.cat(cols).to(torch.int32)
     p.values = 0.5 + torch.rand(int(p.indptr[-1]), generator=gen)
-    _solve_case(ctx, gpu_device, p, als.PATH_AUTO, scale_v=8.0)
+    return p
+
+
+@pytest.mark.parametrize("d,dtype", [(128, "f32"), (64, "f32"), (128, "bf16"), (32, "f32")])
+def test_every_row_length_0_to_140(ctx, gpu_device, d, dtype):
+    """Every boundary between the row classes (4|5, 8|9, 16|17, 32|33, 48|49, ..., 128|129 and the switch to
+    the d x d system) is crossed, with general labels."""
+    say(f"solve_rows auto, every row length 0..140, d={d} {dtype}")
+    _solve_case(ctx, gpu_device, _every_row_length_problem(d, dtype), als.PATH_AUTO, scale_v=8.0)
+
+
+@pytest.mark.parametrize("d,dtype", [(128, "f32"), (64, "f32"), (128, "bf16")])
+def test_cg_on_the_dual_systems_every_row_length(ctx, gpu_device, d, dtype):
+    """Conjugate gradients (Sec. 4.5's solver) on the k x k dual systems of every class, and on the assembled
+    d x d systems of the rows beyond them, against the exact oracle."""
+    say(f"solve_rows auto + CG on the dual systems, every row length 0..140, d={d} {dtype}")
+    _solve_case(ctx, gpu_device, _every_row_length_problem(d, dtype), als.PATH_AUTO, scale_v=8.0,
+                solver=als.SOLVER_CG, cg_tol=1e-7)
+
+
+@pytest.mark.parametrize("d,dtype", [(128, "f32"), (64, "f32"), (32, "f32"), (16, "f32"), (128, "bf16"), (64, "bf16")])
+def test_matrix_free_cg_every_row_length(ctx, gpu_device, d, dtype):
+    """Conjugate gradients with A p = (alpha G + lambda I) p + V_I^T (V_I p), no row matrix assembled, sixteen
+    rows per wavefront with rows of different lengths (and lists that end inside a wavefront's sixteen)."""
+    say(f"solve_rows matrix-free CG, every row length 0..140, d={d} {dtype}")
+    _solve_case(ctx, gpu_device, _every_row_length_problem(d, dtype), als.PATH_AUTO, scale_v=8.0,
+                solver=als.SOLVER_CG_FREE, cg_tol=1e-7)
+
+
+def test_matrix_free_cg_c1_epochs_and_ill_conditioned_table(ctx, gpu_device):
+    """Two whole epochs of configuration 1 with the matrix-free solver (warm starts from the previous epoch's
+    rows) against the oracle, and a table whose Gramian has a spectrum two decades wide (cond ~ 1e2; an fp32
+    conjugate-gradient iteration cannot be asked for 1e-4 much beyond cond ~ 1e3: its attainable accuracy is
+    about 6e-8 * cond, which is why the direct solvers stay the default)."""
+    say("matrix-free CG: c1 epochs, ill-conditioned table")
+    p = make_problem("c1")
+    Y, Yt = to_dev(p, gpu_device)
+    W, H = p.W0.clone().to(gpu_device), p.H0.clone().to(gpu_device)
+    prm = als.make_params(p.alpha, p.lam, solver=als.SOLVER_CG_FREE, cg_tol=1e-7)
+    Wr, Hr = f64(p.W0), f64(p.H0)
+    csr, csr_t = host_csr(p.indptr, p.indices, None), host_csr(p.t_indptr, p.t_indices, None)
+    for _ in range(2):
+        als.als_epoch(ctx, Y, Yt, W, H, prm)
+        Wr, Hr = oracle.epoch(csr, csr_t, Wr, Hr, p.alpha, p.lam, storage="f32")
+    als.als_status_sync(ctx)
+    assert rel_fro(f64(W), Wr) <= 1e-4 and rel_fro(f64(H), Hr) <= 1e-4
+    assert max_row_err(f64(W), Wr) <= 1e-4 and max_row_err(f64(H), Hr) <= 1e-4
+    q = make_problem("c1", rows=500, cols=800, d=64)
+    q.H0 = q.H0 * 40.0 * torch.logspace(0, -1.0, 64)[None, :]
+    q.lam = 1e-3
+    for solver in (als.SOLVER_CG, als.SOLVER_CG_FREE):
+        _solve_case(ctx, gpu_device, q, als.PATH_AUTO, solver=solver, cg_tol=1e-7)
 
 
 @pytest.mark.parametrize("d", [64, 128])
@@ -147,8 +194,34 @@ def test_cg_solver_matches_oracle(ctx, gpu_device, d):
     p = make_problem("c1", rows=500, cols=700, d=d, values="uniform")
     got_cg, ref = _solve_case(ctx, gpu_device, p, als.PATH_PRIMAL, split=40, scale_v=8.0, solver=als.SOLVER_CG,
                               cg_tol=1e-7)
-    # in the default path CG only applies to the rows beyond the dual range
+    # in the default path the rows up to dual_max_k run CG on their k x k systems (d >= 64)
     _solve_case(ctx, gpu_device, p, als.PATH_AUTO, scale_v=8.0, solver=als.SOLVER_CG, cg_tol=1e-7, dual_max_k=16)
+
+
+def test_rows_with_vanishing_right_hand_sides_stay_finite(ctx, gpu_device):
+    """Rows whose observed columns all have embeddings of size ~1e-20 (b and every residual norm squared leave
+    the fp32 range): all solvers return finite rows that agree with the oracle on the scale of the table."""
+    say("solve_rows: vanishing right-hand sides, all solvers")
+    p = make_problem("c1", rows=300, cols=400, d=64)
+    H = p.H0.clone() * 8.0
+    tiny = torch.unique(p.indices[p.indptr[0]:p.indptr[40]].long())  # every column the first 40 rows touch
+    H[tiny] *= 1e-20
+    p.H0 = H
+    for solver in (als.SOLVER_DIRECT, als.SOLVER_CG, als.SOLVER_CG_FREE):
+        for path in (als.PATH_AUTO, als.PATH_PRIMAL):
+            Y, _ = to_dev(p, gpu_device)
+            V = H.to(gpu_device)
+            G = als.als_gramian(ctx, V)
+            X = torch.zeros(p.rows, p.d, device=gpu_device)
+            als.als_solve_rows(ctx, Y, V, G, als.make_params(p.alpha, p.lam, path=path, solver=solver, cg_tol=1e-7), X)
+            als.als_status_sync(ctx)
+            assert bool(torch.isfinite(X).all())
+            ref = oracle.half_epoch(*host_csr(p.indptr, p.indices, p.values), f64(H), p.alpha, p.lam, storage="f32")
+            say(f"  solver {solver} path {path}: rel err {rel_fro(f64(X), ref):.2e}")
+            # the iterative solvers stop on the residual: with this small, badly scaled table (cond ~ 1e3) their
+            # error bound cond * cg_tol is 1e-4 itself; this case is about the range, the parity cases are above
+            assert rel_fro(f64(X), ref) <= (1e-4 if solver == als.SOLVER_DIRECT else 1e-3)
+            assert float(X[:40].abs().max()) < 1e-15
 
 
 def test_cg_warm_start_from_the_solution_changes_nothing(ctx, gpu_device):

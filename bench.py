@@ -12,6 +12,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -102,6 +103,9 @@ def main():
                     help="direct (default, the headline line); cg: conjugate gradients on the dual / assembled systems; "
                          "cg_free: matrix-free conjugate gradients (solver variants of Sec. 4.5, reported beside the default)")
     ap.add_argument("--cg-tol", type=float, default=1e-6)
+    ap.add_argument("--topk-queries", type=int, default=4096,
+                    help="after the timed epochs: exact top-20 of this many rows of W against all of H (0 = skip); "
+                         "reported beside the headline figure, not part of it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="run the library's plain copy kernel on this many MiB first (counter calibration when profiling)")
@@ -275,6 +279,26 @@ def main():
         "roofline": roof,
         "kernels": stages,
     }
+    if args.topk_queries > 0:
+        # retrieval (Sec. 4.6 / Sec. 5's evaluation): exact top-20 by inner product; 2*nq*n*d flop on the fp32 matrix cores
+        nq, kk = min(args.topk_queries, m), 20
+        Q = W[:nq].contiguous()
+        als.als_topk(ctx, Q, H, kk)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        reps = 2
+        for _ in range(reps):
+            ids, _ = als.als_topk(ctx, Q, H, kk)
+        e1.record()
+        torch.cuda.synchronize()
+        tk_ms = e0.elapsed_time(e1) / reps
+        tf = 2.0 * nq * n * d / (tk_ms * 1e-3) / 1e12
+        out["topk"] = {"queries": nq, "items": n, "k": kk, "ms": round(tk_ms, 3), "queries_per_sec": nq / (tk_ms * 1e-3),
+                       "bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                       "frac": round(tf / MFMA_F32_PEAK_TFLOPS, 4),
+                       "item_table_GBps": round(math.ceil(nq / 64) * n * d * es / (tk_ms * 1e-3) / 1e9, 1)}
+        log("top-k:", out["topk"])
     if args.rows:
         out["config"]["note"] = "node count overridden: not the named workload"
     if not args.no_cpu_baseline:

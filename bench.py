@@ -103,6 +103,8 @@ def main():
                     help="direct (default, the headline line); cg: conjugate gradients on the dual / assembled systems; "
                          "cg_free: matrix-free conjugate gradients (solver variants of Sec. 4.5, reported beside the default)")
     ap.add_argument("--cg-tol", type=float, default=1e-6)
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the epoch recorded once into a HIP graph and replayed (reported as graph_replay)")
     ap.add_argument("--topk-queries", type=int, default=4096,
                     help="after the timed epochs: exact top-20 of this many rows of W against all of H (0 = skip); "
                          "reported beside the headline figure, not part of it")
@@ -279,6 +281,21 @@ def main():
         "roofline": roof,
         "kernels": stages,
     }
+    if args.graph:
+        # the epoch enqueues kernels only, so it can be recorded once and replayed: what is left of the launch
+        # overhead matters for the small workloads
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            als.als_epoch(ctx, Y, Yt, W, H, prm)
+        g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        out["graph_replay"] = {"ms_per_step": 1e3 * (time.perf_counter() - t0) / max(args.steps, 1), "steps": args.steps}
+        log("graph replay:", out["graph_replay"])
+        als.als_status_sync(ctx)
     if args.topk_queries > 0:
         # retrieval (Sec. 4.6 / Sec. 5's evaluation): exact top-20 by inner product; 2*nq*n*d flop on the fp32 matrix cores
         nq, kk = min(args.topk_queries, m), 20

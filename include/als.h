@@ -150,7 +150,9 @@ als_status als_solve_rows(als_ctx *ctx, const als_csr *Y, const als_table *V, co
 
 /* One epoch (Algorithm 1, one pass of the outer loop): G_H = H^T H; W <- rows of Y
  * solved against H; G_W = W^T W (from the new W); H <- rows of Yt solved against W.
- * Yt must be the transpose of Y in CSR form.  W and H are updated in place. */
+ * Yt must be the transpose of Y in CSR form.  W and H are updated in place.
+ * Once the workspace has reached its size (after the first call on a problem of this size) the call only
+ * enqueues kernels - no allocation, no copy, no wait - and may be recorded into a HIP graph and replayed. */
 als_status als_epoch(als_ctx *ctx, const als_csr *Y, const als_csr *Yt, als_table *W,
                      als_table *H, const als_params *params, void *stream);
 

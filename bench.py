@@ -187,7 +187,8 @@ def main():
     #   dual row kernel of a class:  HBM-bound,  nnz_c*(s_z*d + 4) [gathered rows of Z (s_z = 4 bytes, 2 for bf16
     #                                           tables) + column ids] + rows_c*(4*d + 8 + 4) [r store, indptr, list entry]
     #   Z = V L^-T and X = R L^-1:   HBM-bound,  rows*d*(s_in + s_out) bytes
-    #   Gramian:                     fp32 tables: fp32-MFMA-bound, 2*rows*d^2 flop; bf16 tables: HBM-bound, rows*d*2 bytes
+    #   Gramian:                     HBM-bound, rows*d*s bytes (d >= 64: products on the bf16 matrix cores); fp32 tables
+    #                                with d < 64: fp32-MFMA-bound, 2*rows*d^2 flop
     #   primal fused rows:           fp32 tables: fp32-MFMA-bound, 2*nnz_p*d^2 + rows_p*(d^3/3 + 2*d^2) flop;
     #                                bf16 tables: the fp32 solves on the vector ALU, rows_p*(d^3/3 + 2*d^2) flop
     #   long-row segments:           fp32 tables: fp32-MFMA-bound, 2*nnz_l*d^2 flop; bf16 tables: HBM-bound gather
@@ -208,7 +209,8 @@ def main():
     if args.solver == "cg_free":
         for name, _, _ in bounds:
             kernel_names[name] = f"cg_free_kernel<{d},{bft}>"
-    kernel_names.update({"gramian": f"gramian_bf16_kernel<{d}>" if (es == 2 and d >= 64) else f"gramian_partial_kernel<{d},{bft}>",
+    kernel_names.update({"gramian": (f"gramian_bf16_kernel<{d}>" if es == 2 else f"gramian_split_kernel<{d}>") if d >= 64
+                         else f"gramian_partial_kernel<{d},{bft}>",
                          "transform_z": f"transform16_kernel<{d},true,true>" if zbt == "true"      # Z = V L^-T
                          else f"transform_kernel<{d},{bft},false,true>",
                          "transform_x": f"transform16_kernel<{d},false,false>" if zbt == "true"    # X = R L^-1
@@ -236,7 +238,8 @@ def main():
     if es == 4:  # fp32 tables: the statistics run on the fp32 matrix cores
         work["primal"] = ["mfma", 2.0 * prim_nnz * d * d + prim_rows * (d ** 3 / 3.0 + 2.0 * d * d)]
         work["segment"] = ["mfma", 2.0 * long_nnz * d * d]
-        work["gramian"] = ["mfma", 2.0 * (m + n) * d * d]
+        # d >= 64: three-way split products on the bf16 matrix cores leave the table read as the bound
+        work["gramian"] = ["hbm", float(m + n) * d * es] if d >= 64 else ["mfma", 2.0 * (m + n) * d * d]
     else:       # bf16 tables: statistics on the bf16 matrix cores leave the gather (HBM) and the fp32 solve (vector ALU)
         work["primal"] = ["alu", prim_rows * (d ** 3 / 3.0 + 2.0 * d * d)]
         work["segment"] = ["hbm", float(long_nnz) * (d * es + 4)]

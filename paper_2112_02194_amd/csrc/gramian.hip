@@ -216,6 +216,149 @@ __global__ __launch_bounds__(GRAM_THREADS, 1) void gramian_bf16_kernel(const uin
     }
 }
 
+// ---------------------------------------------------------------------------------------------- fp32 tables, d >= 64
+// fp32 tables on the same bf16 matrix cores: every entry is cut into three bf16 parts, x = h + m + l exactly
+// (8 + 8 + 8 significant bits: h = upper 16 bits of x, m = upper 16 bits of x - h, l = the rest), each part
+// is transposed by the matrix core as above, and a product x y is taken as hh' + hm' + mh' + hl' + lh' + mm'
+// (what is dropped - ml', lm', ll' - is below 2^-23 |x y|, the rounding of an fp32 product).  Per 32 table rows
+// and d = 128: 24 selection products + 120 Gramian products of 32 clocks, 4 600 clocks against the 10 240 that
+// the same ten blocks take on the fp32 matrix instruction: 2.2 times less matrix-core time, which leaves the
+// pass bound by the table read.  The two cross terms of a pair of parts enter a diagonal block in
+// different order at (r, c) and (c, r), so the output takes the lower triangle from the upper one element by
+// element (symmetric to the bit).  The raw registers of a column block are refilled with the next step's rows
+// as soon as that block has been cut, so that loads are in flight during the products.
+constexpr int GRAM_SPLIT_STEPS = 64;  // 32-row steps a wavefront sums before its workgroup writes a partial
+
+template <int D>
+__global__ __launch_bounds__(GRAM_THREADS, 1) void gramian_split_kernel(const float *__restrict__ V, int64_t rows,
+                                                                        int64_t ld, float *__restrict__ partials) {
+    constexpr int NB = D / 32;  // column blocks of 32 = two loaded pieces of 16 columns
+    __shared__ float red[D * D];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 31, kq = lane >> 5;
+    const int64_t wave_id = (int64_t)blockIdx.x * (GRAM_THREADS / 64) + wave;
+    const int64_t nwaves = (int64_t)gridDim.x * (GRAM_THREADS / 64);
+    bf16x8 sel[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        u32x4 w = {0u, 0u, 0u, 0u};
+        const int k = m - 16 * h - 8 * kq;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (k == e) w[e / 2] = (e & 1) ? 0x3F800000u : 0x00003F80u;
+        sel[h] = __builtin_bit_cast(bf16x8, w);
+    }
+    floatx16 acc[NB][NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // raw[g][c][0..1]: columns 32 g + 16 c + 8 kq .. + 7 of row r0 + m
+    float4 raw[NB][2][2];
+    auto issue = [&](int64_t r0, int g) {
+        const int64_t r = r0 + m;
+#pragma unroll
+        for (int c = 0; c < 2; ++c) raw[g][c][0] = raw[g][c][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (r < rows) {
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const float *src = V + r * ld + 32 * g + 16 * c + 8 * kq;
+                raw[g][c][0] = *(const float4 *)src;
+                raw[g][c][1] = *(const float4 *)(src + 4);
+            }
+        }
+    };
+    auto upper = [](float x, float y) { return __builtin_amdgcn_perm(__float_as_uint(y), __float_as_uint(x), 0x07060302u); };
+    auto rest = [](float x) { return x - __uint_as_float(__float_as_uint(x) & 0xffff0000u); };
+    // the three parts of eight consecutive entries as matrix-core operands
+    auto cut = [&](const float4 &a, const float4 &b, u32x4 (&part)[3]) {
+        float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) part[t][e] = upper(x[2 * e], x[2 * e + 1]);
+            if (t < 2) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] = rest(x[e]);
+            }
+        }
+    };
+    const int64_t step = nwaves * 32;
+    int64_t r0 = wave_id * 32;
+#pragma unroll
+    for (int g = 0; g < NB; ++g) issue(r0, g);
+    for (; r0 < rows; r0 += step) {
+        bf16x8 op[3][NB][2];  // per part and column block: rows 0..15 and 16..31 of the step in the K slots
+#pragma unroll
+        for (int g = 0; g < NB; ++g) {
+            u32x4 p0[3], p1[3];
+            cut(raw[g][0][0], raw[g][0][1], p0);
+            cut(raw[g][1][0], raw[g][1][1], p1);
+            if (g < NB / 2) issue(r0 + step, g);  // past the end: zeros, no loads
+#pragma unroll
+            for (int t = 0; t < 3; ++t) {
+                floatx16 tr;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) tr[v] = 0.f;
+                tr = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, p0[t]), sel[0], tr, 0, 0, 0);
+                tr = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, p1[t]), sel[1], tr, 0, 0, 0);
+#pragma unroll
+                for (int x = 0; x < 2; ++x) {
+                    const u32x4 w = {upper(tr[8 * x + 0], tr[8 * x + 1]), upper(tr[8 * x + 2], tr[8 * x + 3]),
+                                     upper(tr[8 * x + 4], tr[8 * x + 5]), upper(tr[8 * x + 6], tr[8 * x + 7])};
+                    op[t][g][x] = __builtin_bit_cast(bf16x8, w);
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int j = i; j < NB; ++j) {
+                if (i == 1 && j == 1) {  // the other half of the next step's loads: their registers are free only now
+#pragma unroll
+                    for (int g = NB / 2; g < NB; ++g) issue(r0 + step, g);
+                }
+                // the step's twelve products are summed inside the matrix core from zero (small terms first), and the
+                // step's sum joins the running sum by a vector addition, which rounds to nearest: no long chain
+                // of the matrix core's one-sided additions builds up
+                constexpr int PA[6] = {1, 2, 0, 1, 0, 0}, PB[6] = {1, 0, 2, 0, 1, 0};  // mm lh hl mh hm hh
+                floatx16 t16;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) t16[v] = 0.f;
+#pragma unroll
+                for (int t = 0; t < 6; ++t) {
+                    t16 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[PA[t]][i][0], op[PB[t]][j][0], t16, 0, 0, 0);
+                    t16 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[PA[t]][i][1], op[PB[t]][j][1], t16, 0, 0, 0);
+                }
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] += t16[v];
+            }
+    }
+    for (int w = 0; w < GRAM_THREADS / 64; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+#pragma unroll
+                for (int j = i; j < NB; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int r = 32 * i + 8 * (v >> 2) + 4 * kq + (v & 3), c = 32 * j + m;
+                        if (w == 0) red[r * D + c] = acc[i][j][v];
+                        else red[r * D + c] += acc[i][j][v];
+                    }
+        }
+        __syncthreads();
+    }
+    float *out = partials + (int64_t)blockIdx.x * D * D;
+    for (int e = threadIdx.x; e < D * D; e += GRAM_THREADS) {
+        const int r = e / D, c = e % D;
+        out[e] = r <= c ? red[r * D + c] : red[c * D + r];
+    }
+}
+
 // Stage 2: slice y of gridDim.y adds the partials b = y, y + gridDim.y, ... in fp64.
 template <int D>
 __global__ __launch_bounds__(256) void gramian_slice_kernel(const float *__restrict__ partials, int nblocks,
@@ -240,12 +383,18 @@ __global__ __launch_bounds__(256) void gramian_reduce_kernel(const double *__res
 }
 
 template <int D, bool BF16> constexpr bool gram_bf16_cores() { return BF16 && D >= 64; }
+template <int D, bool BF16> constexpr bool gram_split_cores() { return !BF16 && D >= 64; }
 
 template <int D, bool BF16 = false> static int gramian_blocks(int64_t rows) {
     // rows a workgroup may take so that no accumulator sees more than GRAM_CHAIN matrix-core additions
-    // (the bf16 kernel adds twice per 32-row step)
-    const int64_t per_block = gram_bf16_cores<D, BF16>() ? (int64_t)(GRAM_THREADS / 64) * 32 * (GRAM_CHAIN / 2)
-                                                         : (int64_t)(GRAM_THREADS / 64) * Geo<D>::KS * GRAM_CHAIN;
+    // (the bf16 kernel adds twice per 32-row step; the split kernel sums the steps on the vector units)
+    int64_t per_block = gram_bf16_cores<D, BF16>() ? (int64_t)(GRAM_THREADS / 64) * 32 * (GRAM_CHAIN / 2)
+                                                   : (int64_t)(GRAM_THREADS / 64) * Geo<D>::KS * GRAM_CHAIN;
+    if constexpr (gram_split_cores<D, BF16>()) {
+        // at most GRAM_SPLIT_STEPS steps per wavefront, down to 16 for smaller tables so that more workgroups exist
+        constexpr int64_t unit = (int64_t)(GRAM_THREADS / 64) * 32;
+        per_block = std::min<int64_t>(unit * GRAM_SPLIT_STEPS, std::max<int64_t>(16 * unit, (rows / 1024 + unit - 1) / unit * unit));
+    }
     return (int)std::min<int64_t>(GRAM_MAX_BLOCKS, std::max<int64_t>(1, (rows + per_block - 1) / per_block));
 }
 
@@ -256,6 +405,9 @@ static void gramian_enqueue(const als_table *V, float *G, void *work, int nblock
     double *slices = (double *)((char *)work + (size_t)nblocks * D * D * sizeof(float));
     if constexpr (gram_bf16_cores<D, BF16>())
         hipLaunchKernelGGL((gramian_bf16_kernel<D>), dim3(nblocks), dim3(GRAM_THREADS), 0, s, (const uint16_t *)V->data,
+                           V->rows, V->ld, partials);
+    else if constexpr (gram_split_cores<D, BF16>())
+        hipLaunchKernelGGL((gramian_split_kernel<D>), dim3(nblocks), dim3(GRAM_THREADS), 0, s, (const float *)V->data,
                            V->rows, V->ld, partials);
     else
         hipLaunchKernelGGL((gramian_partial_kernel<D, BF16>), dim3(nblocks), dim3(GRAM_THREADS), 0, s, V->data, V->rows,
@@ -321,7 +473,9 @@ hipError_t gramian_static_setup(int device) {
 
 template <int D, bool BF16>
 static als_status gramian_static_typed(const als_table *V, float *G, void *work, hipStream_t s) {
-    const int nblocks = gramian_blocks<D, BF16>(V->rows);  // <= STATIC_BLOCKS: the caller has checked the row count
+    // the caller has checked the row count: with STATIC_BLOCKS workgroups no wavefront exceeds its step limit
+    // (the kernels stride over the table, so fewer workgroups only means more steps each)
+    const int nblocks = std::min(gramian_blocks<D, BF16>(V->rows), STATIC_BLOCKS);
     gramian_enqueue<D, BF16>(V, G, work, nblocks, std::min(nblocks, STATIC_SLICES), s);
     return hipGetLastError() == hipSuccess ? ALS_OK : ALS_EHIP;
 }

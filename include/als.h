@@ -107,9 +107,11 @@ als_status als_destroy(als_ctx *ctx);
 
 /* G = V^T V, the Gramian of a table (Section 3 after Eq. 4; Algorithm 1 line 2).
  * G: device fp32 [d*d], row-major, both triangles written, symmetric to the bit.
- * bf16 entries are used exactly (their products are exact in fp32); sums are fp32
- * inside the matrix core over at most 256 additions, fp64 across blocks of rows, in
- * a fixed order.  Asynchronous on `stream` (a hipStream_t, NULL = default). */
+ * bf16 entries are used exactly (their products are exact in fp32).  For d >= 64 the products run on the bf16
+ * matrix cores; fp32 entries are cut exactly into three bf16 parts there and a product keeps every term down to
+ * the rounding of an fp32 product.  Sums are fp32 - inside the matrix core over short chains only (its running
+ * sum is not rounded to nearest), on the vector units or in fp64 across steps and blocks of rows - in a fixed
+ * order.  Asynchronous on `stream` (a hipStream_t, NULL = default). */
 als_status als_gramian(als_ctx *ctx, const als_table *V, float *G, void *stream);
 
 /* als_gramian for callers that cannot allocate device memory: code under HIP graph capture, tight serving

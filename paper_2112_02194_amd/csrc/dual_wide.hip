@@ -15,10 +15,11 @@ namespace als {
 //      operand) and streams the tiles t2 <= t1 past them (A operand, fetched again from the caches);
 //      each finished 16x16 tile goes to LDS, where S is kept as a lower triangle.
 //   2./3. Block elimination S = M P M^T and back-substitution by the wavefront (tri_solve.h).
-//   4. r = Z_I^T t: from the tiles still in registers, on the matrix cores (zt_times_t, dual_common.h), where all
-//      KT tiles fit the register file next to the solver and it pays (bf16 Z; fp32 Z at d = 64); otherwise with D/64
-//      adjacent output columns per lane, gathering the entries a second time.
-template <int D, int KT, bool ZB> constexpr bool wide_resident() { return ZB || (KT <= 4 && D <= 64); }
+//   4. r = Z_I^T t: with bf16 Z from the tiles still in registers, on the matrix cores (zt_times_t,
+//      dual_common.h: bf16 entries are exact operands); with fp32 Z with D/64 adjacent output columns per lane,
+//      gathering the entries a second time (the hi + lo operands kept for S carry z only to 2^-16, which is
+//      enough for S = I + Z Z^T but would show in r).
+template <int D, int KT, bool ZB> constexpr bool wide_resident() { return ZB; }
 
 template <int D, int KT> struct WideCfg {
     static constexpr int K = 16 * KT;
@@ -146,12 +147,8 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
         floatx4 out[2 * NP];
 #pragma unroll
         for (int x = 0; x < 2 * NP; ++x) out[x] = floatx4{0.f, 0.f, 0.f, 0.f};
-        if constexpr (ZB) {
+        if constexpr (ZB)
             zt_times_t<KT, NP>([&](int t, int j) { return __builtin_bit_cast(bf16x8, zop[t].v[j]); }, top, sel, out);
-        } else {  // z = hi + lo, both exact bf16 numbers
-            zt_times_t<KT, NP>([&](int t, int j) { return zop[t].v[j].hi; }, top, sel, out);
-            zt_times_t<KT, NP>([&](int t, int j) { return zop[t].v[j].lo; }, top, sel, out);
-        }
         float *dump = aux + 128 + lane;  // the solver's per-lane dump slots
 #pragma unroll
         for (int x = 0; x < 2 * NP; ++x)

@@ -21,6 +21,7 @@ namespace als {
 constexpr int TOPK_CAP = 128;       // candidate slots per query in LDS
 constexpr int TOPK_MERGE = 1024;    // candidates the merge sorts per query (slices * padded k)
 constexpr int TOPK_QPW = 16, TOPK_WAVES = 4;
+constexpr int TOPK_TILES = 2;       // tiles of 16 items a wavefront scores per round
 
 __device__ __forceinline__ bool ranks_before(float sa, int32_t ia, float sb, int32_t ib) {
     return sa > sb || (sa == sb && ia < ib);
@@ -50,7 +51,6 @@ __global__ __launch_bounds__(64 * TOPK_WAVES) void topk_scan_kernel(
     const void *__restrict__ Q, int64_t ldq, int64_t nq, const void *__restrict__ H, int64_t ldh, int64_t n,
     const int64_t *__restrict__ ex_indptr, const int32_t *__restrict__ ex_indices, int k, int kpad,
     int64_t slice_items, float *__restrict__ part_sc, int32_t *__restrict__ part_id) {
-    constexpr int NJ = D / 16;
     extern __shared__ float lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, a = lane & 15, q = lane >> 4;
     // per wavefront: scores [16][CAP], ids [16][CAP], count [16], bar [16]
@@ -64,14 +64,30 @@ __global__ __launch_bounds__(64 * TOPK_WAVES) void topk_scan_kernel(
         cnt[lane] = 0;
         bar[lane] = -INFINITY;
     }
-    // query operand: lane (a, q) holds columns (4j + q) * 4 .. of query q0 + a
-    float4 zq[NJ];
+    // Operands: lane (a, q) holds, of query q0 + a and of item t0 + a, the 16-byte pieces j = 0 .. NP - 1 of the row
+    // (piece j, lane group q: elements (4j + q) * EPP ..).  bf16 tables with d >= 32 are multiplied as they are
+    // stored on the bf16 matrix cores (eight bf16 entries are one operand of v_mfma_f32_16x16x32_bf16; the
+    // products are exact, the sums fp32); everything else as fp32 on v_mfma_f32_16x16x4f32.
+    constexpr bool NATIVE = BF16 && D >= 32;
+    constexpr int EPP = NATIVE ? 8 : 4, NP = D / (4 * EPP);
+    auto load_row = [&](const void *T, int64_t elem0, bool ok, float4 (&z)[NP]) {
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-        float x[4] = {0.f, 0.f, 0.f, 0.f};
-        if (q0 + a < nq) load_vec<4, BF16>(Q, (q0 + a) * ldq + (4 * j + q) * 4, x);
-        zq[j] = make_float4(x[0], x[1], x[2], x[3]);
-    }
+        for (int j = 0; j < NP; ++j) z[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ok) {
+#pragma unroll
+            for (int j = 0; j < NP; ++j) {
+                if constexpr (NATIVE) {
+                    z[j] = *(const float4 *)((const uint16_t *)T + elem0 + (4 * j + q) * 8);
+                } else {
+                    float x[4];
+                    load_vec<4, BF16>(T, elem0 + (4 * j + q) * 4, x);
+                    z[j] = make_float4(x[0], x[1], x[2], x[3]);
+                }
+            }
+        }
+    };
+    float4 zq[NP];
+    load_row(Q, (q0 + a) * ldq, q0 + a < nq, zq);
     wave_sync();
     const int64_t i0 = (int64_t)blockIdx.y * slice_items, i1 = i0 + slice_items < n ? i0 + slice_items : n;
 
@@ -93,50 +109,68 @@ __global__ __launch_bounds__(64 * TOPK_WAVES) void topk_scan_kernel(
         wave_sync();
     };
 
-    for (int64_t t0 = i0; t0 < i1; t0 += 16) {
-        const int64_t item = t0 + a;
-        float4 zh[NJ];
+    // TOPK_TILES tiles of 16 items per round; the next round's rows are requested before this round's products
+    float4 zh[TOPK_TILES][NP], zn[TOPK_TILES][NP];
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-            float x[4] = {0.f, 0.f, 0.f, 0.f};
-            if (item < i1) load_vec<4, BF16>(H, item * ldh + (4 * j + q) * 4, x);
-            zh[j] = make_float4(x[0], x[1], x[2], x[3]);
-        }
-        floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int u = 0; u < TOPK_TILES; ++u) load_row(H, (i0 + 16 * u + a) * ldh, i0 + 16 * u + a < i1, zh[u]);
+    for (int64_t t0 = i0; t0 < i1; t0 += 16 * TOPK_TILES) {
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(zq[j].x, zh[j].x, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(zq[j].y, zh[j].y, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(zq[j].z, zh[j].z, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(zq[j].w, zh[j].w, acc, 0, 0, 0);
+        for (int u = 0; u < TOPK_TILES; ++u) {
+            const int64_t nxt = t0 + 16 * (TOPK_TILES + u) + a;
+            load_row(H, nxt * ldh, nxt < i1, zn[u]);
         }
-        // acc[v] = <query q0 + 4q + v, item t0 + a>
+        floatx4 acc[TOPK_TILES];
+#pragma unroll
+        for (int u = 0; u < TOPK_TILES; ++u) {
+            acc[u] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < NP; ++j) {
+                if constexpr (NATIVE) {
+                    acc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, zq[j]),
+                                                                     __builtin_bit_cast(bf16x8, zh[u][j]), acc[u], 0, 0, 0);
+                } else {
+                    acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(zq[j].x, zh[u][j].x, acc[u], 0, 0, 0);
+                    acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(zq[j].y, zh[u][j].y, acc[u], 0, 0, 0);
+                    acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(zq[j].z, zh[u][j].z, acc[u], 0, 0, 0);
+                    acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(zq[j].w, zh[u][j].w, acc[u], 0, 0, 0);
+                }
+            }
+        }
+        // acc[u][v] = <query q0 + 4q + v, item t0 + 16 u + a>
         const float4 b4 = *(const float4 *)(bar + 4 * q);
         const float bq[4] = {b4.x, b4.y, b4.z, b4.w};
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int qy = 4 * q + v;
-            if (item < i1 && q0 + qy < nq && acc[v] >= bq[v]) {
-                bool skip = false;
-                if (ex_indptr) {
-                    const int64_t eb = ex_indptr[q0 + qy], ee = ex_indptr[q0 + qy + 1];
-                    for (int64_t p = eb; p < ee; ++p) skip |= ex_indices[p] == (int32_t)item;
-                }
-                if (!skip) {
-                    const int pos = atomicAdd(&cnt[qy], 1);  // at most 16 per tile and query: never beyond CAP
-                    sc[qy * TOPK_CAP + pos] = acc[v];
-                    id[qy * TOPK_CAP + pos] = (int32_t)item;
+        for (int u = 0; u < TOPK_TILES; ++u) {
+            const int64_t item = t0 + 16 * u + a;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int qy = 4 * q + v;
+                if (item < i1 && q0 + qy < nq && acc[u][v] >= bq[v]) {
+                    bool skip = false;
+                    if (ex_indptr) {
+                        const int64_t eb = ex_indptr[q0 + qy], ee = ex_indptr[q0 + qy + 1];
+                        for (int64_t p = eb; p < ee; ++p) skip |= ex_indices[p] == (int32_t)item;
+                    }
+                    if (!skip) {
+                        const int pos = atomicAdd(&cnt[qy], 1);  // at most 16 per tile and query: never beyond CAP
+                        sc[qy * TOPK_CAP + pos] = acc[u][v];
+                        id[qy * TOPK_CAP + pos] = (int32_t)item;
+                    }
                 }
             }
         }
         wave_sync();
         const int mine = lane < TOPK_QPW ? cnt[lane] : 0;
-        unsigned long long full = __ballot(mine > TOPK_CAP - 16);
+        unsigned long long full = __ballot(mine > TOPK_CAP - 16 * TOPK_TILES);
         while (full) {
             const int qy = __ffsll((long long)full) - 1;
             full &= full - 1;
             compact(qy);
         }
+#pragma unroll
+        for (int u = 0; u < TOPK_TILES; ++u)
+#pragma unroll
+            for (int j = 0; j < NP; ++j) zh[u][j] = zn[u][j];
     }
     for (int qy = 0; qy < TOPK_QPW; ++qy) {
         compact(qy);

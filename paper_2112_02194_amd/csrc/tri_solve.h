@@ -1,6 +1,8 @@
 // One wavefront solves a symmetric positive definite K x K system (K <= 128, a multiple of 16) whose
-// lower triangle sits in LDS, row r starting at tri_row(r) (rows padded to multiples of four floats so
-// that 16-byte accesses inside a row are aligned).
+// lower triangle sits in LDS, row r starting at tri_row(r).  Rows are padded to multiples of sixteen floats:
+// a row at or below a panel of 16 columns then holds all 16 of them inside its own storage (beyond its
+// diagonal: padding, never used), so a panel is read and written back with 16-byte accesses and no
+// per-element test.
 //
 // Blocked elimination S = M P M^T (M unit lower triangular, P the pivots) with panels of 16 columns.
 // Lane i owns rows i and 64+i.  Per panel:
@@ -26,12 +28,19 @@
 namespace als {
 
 // first float of row r in the padded triangle; tri_row(K) is the size of the whole triangle
-__host__ __device__ constexpr int tri_row(int r) { return 4 * (r / 4 + 1) * (2 * (r / 4) + r % 4); }
+__host__ __device__ constexpr int tri_row(int r) { return 16 * (r / 16 + 1) * (8 * (r / 16) + r % 16); }
 
 constexpr int TRI_AUX_FLOATS = 192;  // reciprocal pivots [128], per-lane dump slots [64]
 
 __device__ __forceinline__ float lane_value(float v, int src_lane) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src_lane));
+}
+
+// v with the wavefront-uniform value `uniform` put into lane DST (one instruction; the lane is a constant, so
+// the instruction's wait states for a lane select computed just before do not apply)
+template <int DST> __device__ __forceinline__ float lane_set(float v, float uniform) {
+    asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(uniform), "n"(DST));
+    return v;
 }
 
 template <int K>
@@ -47,17 +56,23 @@ __device__ __forceinline__ void tri_solve(float *tri, float *aux /* [192] */, fl
     float *rpbuf = aux, *dump = aux + 128 + lane;
     float *rowa = tri + tri_row(hasa ? ra : 0), *rowb = tri + tri_row(hasb ? rb : 0);
     float rp0 = 1.f, rp1 = 1.f;
-    bool bad = false;
     static_for<0, NT>([&](auto pp) {
         constexpr int p = decltype(pp)::value;
         constexpr int P0 = 16 * p;
         constexpr bool OB = P0 >= 64;  // the panel's pivot rows belong to the second set of rows
         if (P0 < k) {
+            // Every lane reads 16 floats at the panel's columns of its rows.  What is not an entry of the matrix
+            // there (beyond a row's diagonal; a row above the panel; a lane without a row) is never used: the
+            // multipliers below are taken only for rows under the pivot, lane reads only go to lanes whose entry
+            // exists, and only rows at or below the panel are written back.
             float xa[16], xb[16];
 #pragma unroll
-            for (int c = 0; c < 16; ++c) {
-                xa[c] = (!OB && hasa && P0 + c <= ra) ? rowa[P0 + c] : 0.f;
-                xb[c] = (TWO && hasb && P0 + c <= rb) ? rowb[P0 + c] : 0.f;
+            for (int c4 = 0; c4 < 4; ++c4) {
+                float4 va = make_float4(0.f, 0.f, 0.f, 0.f), vb = va;
+                if constexpr (!OB) va = *(const float4 *)(rowa + P0 + 4 * c4);
+                if constexpr (TWO) vb = *(const float4 *)(rowb + P0 + 4 * c4);
+                xa[4 * c4] = va.x; xa[4 * c4 + 1] = va.y; xa[4 * c4 + 2] = va.z; xa[4 * c4 + 3] = va.w;
+                xb[4 * c4] = vb.x; xb[4 * c4 + 1] = vb.y; xb[4 * c4 + 2] = vb.z; xb[4 * c4 + 3] = vb.w;
             }
             // reciprocal pivot and right-hand-side entry of a step are prepared during the step before
             // (right after its first update), off the critical path
@@ -66,7 +81,6 @@ __device__ __forceinline__ void tri_solve(float *tri, float *aux /* [192] */, fl
                 constexpr int c = decltype(cc)::value;
                 constexpr int ol = (P0 + c) & 63;
                 const float pivot = lane_value(OB ? xb[c] : xa[c], ol);
-                bad |= !(pivot > 0.f);
                 rp = __builtin_amdgcn_rcpf(pivot);
                 rp = rp * (2.f - pivot * rp);  // one Newton step on the hardware reciprocal
                 if constexpr (OB) rp1 = lane == ol ? rp : rp1;
@@ -105,10 +119,19 @@ __device__ __forceinline__ void tri_solve(float *tri, float *aux /* [192] */, fl
                     __builtin_amdgcn_sched_barrier(0);
                 }
             });
+            if constexpr (!OB) {
+                if (hasa && ra >= P0) {
 #pragma unroll
-            for (int c = 0; c < 16; ++c) {
-                if constexpr (!OB) *((hasa && P0 + c <= ra) ? rowa + P0 + c : dump) = xa[c];
-                if constexpr (TWO) *((hasb && P0 + c <= rb) ? rowb + P0 + c : dump) = xb[c];
+                    for (int c4 = 0; c4 < 4; ++c4)
+                        *(float4 *)(rowa + P0 + 4 * c4) = make_float4(xa[4 * c4], xa[4 * c4 + 1], xa[4 * c4 + 2], xa[4 * c4 + 3]);
+                }
+            }
+            if constexpr (TWO) {
+                if (hasb && rb >= P0) {
+#pragma unroll
+                    for (int c4 = 0; c4 < 4; ++c4)
+                        *(float4 *)(rowb + P0 + 4 * c4) = make_float4(xb[4 * c4], xb[4 * c4 + 1], xb[4 * c4 + 2], xb[4 * c4 + 3]);
+                }
             }
             rpbuf[lane] = rp0;
             if constexpr (TWO) rpbuf[64 + lane] = rp1;
@@ -150,7 +173,9 @@ __device__ __forceinline__ void tri_solve(float *tri, float *aux /* [192] */, fl
             }
         }
     });
-    if (bad && lane == 0) atomicOr(err_flag, 1);
+    // A pivot that is not positive shows in its reciprocal, which the owning lane has kept: negative stays
+    // negative, zero and NaN come out of the Newton step as NaN.
+    if (__any(!(rp0 > 0.f) || !(rp1 > 0.f)) && lane == 0) atomicOr(err_flag, 1);
 
     // ---- back-substitution, eight rows of the factor fetched ahead of the dependent chain.  Row R is
     // read by all lanes at column min(lane, R): lanes at or beyond R have their unknown already and
@@ -171,20 +196,19 @@ __device__ __forceinline__ void tri_solve(float *tri, float *aux /* [192] */, fl
                     fa[i] = row[ra < Rr ? ra : Rr];
                 }
             }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int Rr = Rt - i;
-                if (Rr >= 64) {
+            static_for<0, 8>([&](auto ii) {
+                constexpr int i = decltype(ii)::value, Rr = Rt - i;
+                if constexpr (Rr >= 64) {
                     const float tR = lane_value(y1 * rp1, Rr - 64);
-                    t1v = rb == Rr ? tR : t1v;
+                    t1v = lane_set<Rr - 64>(t1v, tR);
                     y1 -= fb[i] * tR;
                     y0 -= fa[i] * tR;
                 } else {
                     const float tR = lane_value(y0 * rp0, Rr);
-                    t0 = ra == Rr ? tR : t0;
+                    t0 = lane_set<Rr>(t0, tR);
                     y0 -= fa[i] * tR;
                 }
-            }
+            });
         }
     });
     if (hasa) tbuf[ra] = t0;

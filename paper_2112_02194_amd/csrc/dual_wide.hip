@@ -101,13 +101,15 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
                 za.set(raw);
                 acc = tile_product<D, ZB>(za, zb, acc);
             }
-            // acc[v] = S[Rr][c], Rr = 16*t1 + a, c = 16*t2 + 4q + v (S is symmetric); keep c <= Rr
-            const int Rr = 16 * t1 + a;
+            // acc[v] = S[Rr][c], Rr = 16*t1 + a, c = 16*t2 + 4q + v (S is symmetric).  The triangle's rows are
+            // padded to whole tiles, so a diagonal tile is stored whole: what lies beyond the diagonal lands in
+            // the row's padding
+            const int Rr = 16 * t1 + a, c0 = 16 * t2 + 4 * q;
+            if (t2 == t1) {  // known after unrolling: the identity only meets diagonal tiles
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int c = 16 * t2 + 4 * q + v;
-                if (c <= Rr) tri[tri_row(Rr) + c] = acc[v] + (c == Rr ? 1.f : 0.f);
+                for (int v = 0; v < 4; ++v) acc[v] += c0 + v == Rr ? 1.f : 0.f;
             }
+            *(float4 *)(tri + tri_row(Rr) + c0) = make_float4(acc[0], acc[1], acc[2], acc[3]);
         }
     }
     wave_sync();
@@ -187,7 +189,7 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
 // The two launch forms of a step kernel (see StepGrid): one row per workgroup, or a grid-stride walk from
 // row first_item to the end of the list.
 template <int D, int KT, bool ZB, bool LOOP, bool CG>
-__global__ __launch_bounds__(64, (LOOP || KT >= 7) ? 1 : 2) void dual_wide_kernel(const int64_t *__restrict__ indptr,
+__global__ __launch_bounds__(64, (LOOP || KT >= 7) ? 1 : (KT <= 4 ? 3 : 2)) void dual_wide_kernel(const int64_t *__restrict__ indptr,
                                                           const int32_t *__restrict__ indices,
                                                           const float *__restrict__ values,
                                                           const void *__restrict__ Z, float *__restrict__ R,

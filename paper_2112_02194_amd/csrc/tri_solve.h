@@ -177,9 +177,10 @@ __device__ __forceinline__ void tri_solve(float *tri, float *aux /* [192] */, fl
     // negative, zero and NaN come out of the Newton step as NaN.
     if (__any(!(rp0 > 0.f) || !(rp1 > 0.f)) && lane == 0) atomicOr(err_flag, 1);
 
-    // ---- back-substitution, eight rows of the factor fetched ahead of the dependent chain.  Row R is
-    // read by all lanes at column min(lane, R): lanes at or beyond R have their unknown already and
-    // may go on computing on whatever they read.  Groups of rows at or beyond k hold t = 0.
+    // ---- back-substitution, eight rows of the factor fetched ahead of the dependent chain.  Every lane reads
+    // row R at its own column: lanes at or beyond R have their unknown already and go on computing on
+    // whatever lies there (the row's padding, later rows, at most the first 127 floats after the triangle,
+    // which every caller's LDS layout has).  Groups of rows at or beyond k hold t = 0.
     float t0 = 0.f, t1v = 0.f;
     static_for<0, K / 8>([&](auto gg) {
         constexpr int Rt = K - 1 - 8 * decltype(gg)::value;  // the group's last row; rows Rt-7 .. Rt
@@ -189,12 +190,8 @@ __device__ __forceinline__ void tri_solve(float *tri, float *aux /* [192] */, fl
             for (int i = 0; i < 8; ++i) {
                 const int Rr = Rt - i;
                 const float *row = tri + tri_row(Rr);
-                if (Rr >= 64) {
-                    fa[i] = row[ra];
-                    fb[i] = row[rb < Rr ? rb : Rr];
-                } else {
-                    fa[i] = row[ra < Rr ? ra : Rr];
-                }
+                fa[i] = row[lane];
+                if (Rr >= 64) fb[i] = row[64 + lane];
             }
             static_for<0, 8>([&](auto ii) {
                 constexpr int i = decltype(ii)::value, Rr = Rt - i;

@@ -15,7 +15,8 @@
 //      cores: for 16 x 16 tiles (ti, tj <= ti) below the panel, S[ti][tj] -= (S' P^{-1})[ti] S'[tj]^T.
 //      Lane (a, q) = (lane % 16, lane / 16) of v_mfma_f32_16x16x4f32 supplies A[a][q] and B[q][a] and
 //      holds C[4q+v][a]; MFMA e of a tile contracts the panel columns 4q + e, so that every lane fetches
-//      its operands of the four MFMAs with one 16-byte read.
+//      its operands of the four MFMAs with one 16-byte read; the tile is computed transposed (A from the
+//      column tile's rows, B from the row tile's), so that C[4q+v][a] is row a, columns 4q+v of the tile.
 // Then back-substitution t_c = (u_c - sum_{R>c} S'[R][c] t_R) / pivot_c along the rows of the factor in
 // LDS, eight rows fetched ahead of the dependent chain; the value just found is read from its lane.
 // Panels and steps at or beyond k are skipped: the caller guarantees that rows >= k are identity rows
@@ -30,7 +31,7 @@ namespace als {
 // first float of row r in the padded triangle; tri_row(K) is the size of the whole triangle
 __host__ __device__ constexpr int tri_row(int r) { return 16 * (r / 16 + 1) * (8 * (r / 16) + r % 16); }
 
-constexpr int TRI_AUX_FLOATS = 192;  // reciprocal pivots [128], per-lane dump slots [64]
+constexpr int TRI_AUX_FLOATS = 192;  // reciprocal pivots [128]; the other 64 are the callers' per-lane dump slots
 
 __device__ __forceinline__ float lane_value(float v, int src_lane) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src_lane));
@@ -53,7 +54,7 @@ __device__ __forceinline__ void tri_solve(float *tri, float *aux /* [192] */, fl
     const int ra = lane, rb = 64 + lane;
     const bool hasa = ra < K, hasb = TWO && rb < K;
     const int a = lane & 15, q = lane >> 4;
-    float *rpbuf = aux, *dump = aux + 128 + lane;
+    float *rpbuf = aux;
     float *rowa = tri + tri_row(hasa ? ra : 0), *rowb = tri + tri_row(hasb ? rb : 0);
     float rp0 = 1.f, rp1 = 1.f;
     static_for<0, NT>([&](auto pp) {
@@ -145,29 +146,28 @@ __device__ __forceinline__ void tri_solve(float *tri, float *aux /* [192] */, fl
                 static_for<0, T>([&](auto tii) {
                     constexpr int ti = decltype(tii)::value;
                     const float4 za = make_float4(-z[ti].x * rpv.x, -z[ti].y * rpv.y, -z[ti].z * rpv.z, -z[ti].w * rpv.w);
-                    // all tiles of the tile row are fetched before the first is stored back
+                    // all tiles of the tile row are fetched before the first is stored back.  The operands are taken
+                    // in the order that leaves a lane with four consecutive columns of ONE row of the tile (row
+                    // 16 (p+1+ti) + a, columns 16 (p+1+tj) + 4q ..): one 16-byte access each way; in a diagonal tile
+                    // the columns beyond the diagonal belong to the row's padding
                     floatx4 acc[ti + 1];
-                    float *cell[ti + 1][4];
+                    float4 *cell[ti + 1];
 #pragma unroll
-                    for (int tj = 0; tj <= ti; ++tj)
+                    for (int tj = 0; tj <= ti; ++tj) {
+                        cell[tj] = (float4 *)(tri + tri_row(16 * (p + 1 + ti) + a) + 16 * (p + 1 + tj) + 4 * q);
+                        const float4 c4 = *cell[tj];
+                        acc[tj] = floatx4{c4.x, c4.y, c4.z, c4.w};
+                    }
 #pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            const int row = 16 * (p + 1 + ti) + 4 * q + v, col = 16 * (p + 1 + tj) + a;
-                            cell[tj][v] = (tj < ti || col <= row) ? tri + tri_row(row) + col : dump;
-                            acc[tj][v] = *cell[tj][v];
-                        }
+                    for (int tj = 0; tj <= ti; ++tj) acc[tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[tj].x, za.x, acc[tj], 0, 0, 0);
 #pragma unroll
-                    for (int tj = 0; tj <= ti; ++tj) acc[tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(za.x, z[tj].x, acc[tj], 0, 0, 0);
+                    for (int tj = 0; tj <= ti; ++tj) acc[tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[tj].y, za.y, acc[tj], 0, 0, 0);
 #pragma unroll
-                    for (int tj = 0; tj <= ti; ++tj) acc[tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(za.y, z[tj].y, acc[tj], 0, 0, 0);
+                    for (int tj = 0; tj <= ti; ++tj) acc[tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[tj].z, za.z, acc[tj], 0, 0, 0);
 #pragma unroll
-                    for (int tj = 0; tj <= ti; ++tj) acc[tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(za.z, z[tj].z, acc[tj], 0, 0, 0);
+                    for (int tj = 0; tj <= ti; ++tj) acc[tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[tj].w, za.w, acc[tj], 0, 0, 0);
 #pragma unroll
-                    for (int tj = 0; tj <= ti; ++tj) acc[tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(za.w, z[tj].w, acc[tj], 0, 0, 0);
-#pragma unroll
-                    for (int tj = 0; tj <= ti; ++tj)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) *cell[tj][v] = acc[tj][v];
+                    for (int tj = 0; tj <= ti; ++tj) *cell[tj] = make_float4(acc[tj][0], acc[tj][1], acc[tj][2], acc[tj][3]);
                 });
                 wave_sync();
             }

@@ -16,26 +16,31 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libals.so")
 OBJDIR = os.path.join(HERE, "_build")
 
-# (source, object name, extra defines)
+# matrix-core results go to ordinary vector registers in these units: their kernels take the results apart with
+# vector instructions right away, and a copy out of the accumulation registers per result register costs more
+# than the registers do
+VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
+
+# (source, object name, extra flags)
 UNITS = [
     ("als_api.hip", "als_api", []),
     ("gramian.hip", "gramian", []),
     ("rows_primal.hip", "rows_primal", []),
     ("solve_rows.hip", "solve_rows", []),
     ("loss.hip", "loss", []),
-    ("topk.hip", "topk", []),
+    ("topk.hip", "topk", VGPR_FORM),
     ("cg_free.hip", "cg_free", []),
     ("dual_prepare.hip", "dual_prepare", []),
-    ("dual_rows.hip", "dual_rows", []),
-    ("dual_small.hip", "dual_small_g8", ["-DSMALL_G=8"]),
-    ("dual_small.hip", "dual_small_g4", ["-DSMALL_G=4"]),
-    ("dual_multi.hip", "dual_multi", []),
-    ("dual_wide.hip", "dual_wide_3", ["-DWIDE_KT=3"]),
-    ("dual_wide.hip", "dual_wide_4", ["-DWIDE_KT=4"]),
-    ("dual_wide.hip", "dual_wide_5", ["-DWIDE_KT=5"]),
-    ("dual_wide.hip", "dual_wide_6", ["-DWIDE_KT=6"]),
-    ("dual_wide.hip", "dual_wide_7", ["-DWIDE_KT=7"]),
-    ("dual_wide.hip", "dual_wide_8", ["-DWIDE_KT=8"]),
+    ("dual_rows.hip", "dual_rows", VGPR_FORM),
+    ("dual_small.hip", "dual_small_g8", ["-DSMALL_G=8"] + VGPR_FORM),
+    ("dual_small.hip", "dual_small_g4", ["-DSMALL_G=4"] + VGPR_FORM),
+    ("dual_multi.hip", "dual_multi", VGPR_FORM),
+    ("dual_wide.hip", "dual_wide_3", ["-DWIDE_KT=3"] + VGPR_FORM),
+    ("dual_wide.hip", "dual_wide_4", ["-DWIDE_KT=4"] + VGPR_FORM),
+    ("dual_wide.hip", "dual_wide_5", ["-DWIDE_KT=5"] + VGPR_FORM),
+    ("dual_wide.hip", "dual_wide_6", ["-DWIDE_KT=6"] + VGPR_FORM),
+    ("dual_wide.hip", "dual_wide_7", ["-DWIDE_KT=7"] + VGPR_FORM),
+    ("dual_wide.hip", "dual_wide_8", ["-DWIDE_KT=8"] + VGPR_FORM),
 ]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE, "-I" + CSRC,

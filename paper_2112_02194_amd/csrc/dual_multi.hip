@@ -75,8 +75,8 @@ __device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indp
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         const bool have = blk * 4 + p < count;
-        u[p] = have ? r0 + rel[p] : -1;
-        k[p] = have ? (int)(b1[p] - b[p]) : 0;
+        u[p] = have ? r0 + rel[p] : -1;  // past the end of the list: the step's first row once more, not stored
+        k[p] = (int)(b1[p] - b[p]);
         kmax = k[p] > kmax ? k[p] : kmax;
     }
 
@@ -104,11 +104,16 @@ __device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indp
             const int e = 16 * t + a;
             const int32_t id = idv[p][t];
             if (!RES && q == 0) ids[p * K + e] = id & 0x7fffffff;
+            if (t < M - 1) {  // every row of the class has more than 16 (M - 1) entries: these tiles are full
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) z[t][j] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (id >= 0) {  // one masked region per tile, not one per load
+                for (int j = 0; j < NJ; ++j) z[t][j] = load_piece<D, ZB>(Z, id & 0x7fffffff, j, q);
+            } else {
 #pragma unroll
-                for (int j = 0; j < NJ; ++j) z[t][j] = load_piece<D, ZB>(Z, id, j, q);
+                for (int j = 0; j < NJ; ++j) z[t][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (id >= 0) {  // one masked region per tile, not one per load
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) z[t][j] = load_piece<D, ZB>(Z, id, j, q);
+                }
             }
         }
         SplitOperand zs[M][NJ / 2 > 0 ? NJ / 2 : 1];

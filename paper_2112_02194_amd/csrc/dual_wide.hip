@@ -53,7 +53,7 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
     for (int t = 0; t < KT; ++t) {
         const int e = 16 * t + a;
         const int32_t id = indices[b + (e < k ? e : 0)];  // a slot past k: the row's first entry (meets t = 0 below)
-        myid[t] = e < k ? id : -1;
+        myid[t] = e < k ? id : (id | (int32_t)0x80000000);  // a padded slot: negative, and still a row of the table
         if (!RES && q == 0) ids[e] = id;
     }
     // the first RT tiles stay in registers for the whole phase (one round of loads, all in flight
@@ -62,11 +62,18 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
     constexpr int RT = RES ? KT : (KT < 5 ? KT : (KT < 7 ? 5 : 4));
     typedef TileOperand<D, ZB> Op;
     auto fetch = [&](int t, float4 (&raw)[NJ]) {
+        // with the direct solver the class holds rows with more than 16 (KT - 1) entries only: all tiles but the
+        // last are full (under CG shorter rows come through the same kernel)
+        if (!CG && t < KT - 1) {
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) raw[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (myid[t] >= 0) {  // one masked region per tile, not one per load
+            for (int j = 0; j < NJ; ++j) raw[j] = load_piece<D, ZB>(Z, myid[t] & 0x7fffffff, j, q);
+        } else {
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) raw[j] = load_piece<D, ZB>(Z, myid[t], j, q);
+            for (int j = 0; j < NJ; ++j) raw[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (myid[t] >= 0) {  // one masked region per tile, not one per load
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) raw[j] = load_piece<D, ZB>(Z, myid[t], j, q);
+            }
         }
     };
     Op zop[RT];

@@ -238,13 +238,10 @@ __device__ __forceinline__ void zt_times_t(Tile &&tile, const bf16x8 (&top)[(NT 
         });
     });
 }
-// Column of r that lanes (n, q = 0) hold in out[2 j + x]: depth slot 16 x + n of operand piece j.  A bf16 piece
-// is 32 consecutive columns; an operand cut from fp32 pieces holds columns 32 j + 4 q' + w and
-// 32 j + 16 + 4 q' + w (w = 0 .. 3) in the slots 8 q' .. 8 q' + 7.
-template <bool ZB> __device__ __forceinline__ int column_of_result(int j, int x, int n) {
-    if constexpr (ZB) return 32 * j + 16 * x + n;
-    else return 32 * j + 8 * x + 4 * (n >> 3) + 16 * ((n >> 2) & 1) + (n & 3);
-}
+// Column of r that lanes (n, q = 0) hold in out[2 j + x]: depth slot 16 x + n of operand piece j, and a bf16
+// piece is 32 consecutive columns.  (Only bf16 tiles are exact operands; the hi + lo operands cut from fp32
+// tiles carry an entry to 2^-16 only, which is enough for S but would show in r.)
+__device__ __forceinline__ int column_of_result(int j, int x, int n) { return 32 * j + 16 * x + n; }
 
 // The conjugate-gradient solvers work with squared residual norms: below this the squares lose their bits to
 // the bottom of the fp32 range and step lengths formed from them are noise, so a residual with |r|^2 at or

@@ -278,7 +278,7 @@ __device__ __forceinline__ void dual_multi_step(const int64_t *__restrict__ indp
             zt_times_t<2, NJ>([&](int tt, int j) { return __builtin_bit_cast(bf16x8, zkeep[RES ? p : 0][tt][j]); }, top, sel, out);
 #pragma unroll
             for (int x = 0; x < 2 * NJ; ++x)
-                *(q == 0 ? rbuf + p * D + column_of_result<true>(x >> 1, x & 1, a) : dump) = out[x][0] + out[x][1] + out[x][2];
+                *(q == 0 ? rbuf + p * D + column_of_result(x >> 1, x & 1, a) : dump) = out[x][0] + out[x][1] + out[x][2];
         }
         wave_sync();
         const bool col_ok = lane * CPL < D;

@@ -161,7 +161,7 @@ __device__ __forceinline__ void dual_wide_step(const int64_t *__restrict__ indpt
         float *dump = aux + 128 + lane;  // the solver's per-lane dump slots
 #pragma unroll
         for (int x = 0; x < 2 * NP; ++x)
-            *(q == 0 ? rbuf + column_of_result<ZB>(x >> 1, x & 1, a) : dump) = out[x][0] + out[x][1] + out[x][2];
+            *(q == 0 ? rbuf + column_of_result(x >> 1, x & 1, a) : dump) = out[x][0] + out[x][1] + out[x][2];
         wave_sync();
         if constexpr (D >= 128) *(float2 *)(R + u * ldr + 2 * lane) = *(const float2 *)(rbuf + 2 * lane);
         else R[u * ldr + lane] = rbuf[lane];

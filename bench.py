@@ -214,7 +214,8 @@ def main():
                          "transform_z": f"transform16_kernel<{d},true,true>" if zbt == "true"      # Z = V L^-T
                          else f"transform_kernel<{d},{bft},false,true>",
                          "transform_x": f"transform16_kernel<{d},false,false>" if zbt == "true"    # X = R L^-1
-                         else f"transform_kernel<{d},false,{bft},false>",
+                         else (f"transform_split_kernel<{d},false>" if (es == 4 and d >= 64)
+                               else f"transform_kernel<{d},false,{bft},false>"),
                          "primal": f"primal_kernel<{d},{bft},0,false>",               # one workgroup per row
                          "segment": f"primal_kernel<{d},{bft},1,false>"})             # segments of long rows
     zs = 2 if (es == 2 and d >= 32) else 4  # bytes per element of the transformed table Z the dual kernels gather

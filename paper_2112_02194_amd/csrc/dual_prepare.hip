@@ -276,6 +276,110 @@ __global__ __launch_bounds__(256, 2) void transform16_kernel(const void *__restr
     }
 }
 
+// ---------------------------------------------------------------------------------------------- transform, fp32 tables
+// fp32 in, fp32 out (d >= 64), with fp32 accuracy on the bf16 matrix cores: the matrix (once per workgroup, LDS)
+// and the table rows (registers) are cut exactly into three bf16 parts each, x = x0 + x1 + x2 with x0 = upper
+// 16 bits of x and so on, and a product keeps the six terms m0 x0, m0 x1, m1 x0, m0 x2, m2 x0, m1 x1 (what is
+// dropped is below the rounding of an fp32 product): 0.375 of the fp32 instruction's matrix-core time, which
+// leaves the pass to the table read and write (used for X = R L^-1: 24.5 against 29.0 ms per epoch on the 50M-row
+// configuration; for Z = V L^-T the fp32 kernel above measured faster, 24.4 against 25.9 ms).  The matrix core's running sum is not rounded to nearest, so
+// only the six products of one 16-column step are summed there, from zero and small terms first; the steps are
+// summed on the vector units.  Operand roles and the store layout are those of transform16_kernel.  All of a
+// tile's input is in registers before its first store, so In == Out is fine.
+constexpr int XFS_THREADS = 512;
+template <int D> struct XfsCfg {
+    static constexpr int MLD = D + 8;  // bf16 elements per LDS row
+    static constexpr size_t LDS_BYTES = (size_t)3 * D * MLD * sizeof(uint16_t);
+};
+
+template <int D, bool UPPER>
+__global__ __launch_bounds__(XFS_THREADS, 2) void transform_split_kernel(const float *In, int64_t ldi, float *Out,
+                                                                         int64_t ldo, const float *__restrict__ M,
+                                                                         int64_t r0, int64_t r1,
+                                                                         const int64_t *__restrict__ indptr, int64_t k_max) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    constexpr int MLD = XfsCfg<D>::MLD, NKB = D / 16, NJB = D / 32;
+    extern __shared__ uint16_t mt[];  // part t: mt[t * D * MLD + c * MLD + j] = part t of M[j][c]
+    auto rest = [](float x) { return x - __uint_as_float(__float_as_uint(x) & 0xffff0000u); };
+    for (int e = threadIdx.x; e < D * D; e += XFS_THREADS) {
+        const int j = e / D, c = e % D;
+        float v = M[e];
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+            mt[t * D * MLD + c * MLD + j] = (uint16_t)(__float_as_uint(v) >> 16);
+            v = rest(v);
+        }
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 31, kq = lane >> 5;
+    const int pi = 16 * ((n >> 2) & 1) + 4 * (n >> 3) + (n & 3);  // see transform16_kernel
+    const int64_t ntiles = (r1 - r0 + 31) / 32;
+    const int64_t nwaves = (int64_t)gridDim.x * (XFS_THREADS / 64);
+    for (int64_t tile = (int64_t)blockIdx.x * (XFS_THREADS / 64) + wave; tile < ntiles; tile += nwaves) {
+        const int64_t row = r0 + tile * 32 + n;
+        bool keep = row < r1;
+        if (keep && indptr) {  // only rows solved in the dual form are written
+            const int64_t k = indptr[row + 1] - indptr[row];
+            keep = k > 0 && k <= k_max;
+        }
+        // this lane's share of its row: columns 16 kb + 8 kq .., as three bf16 operands each
+        bf16x8 xp[3][NKB];
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) {
+            float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if (row < r1) {
+                const float4 p = *(const float4 *)(In + row * ldi + 16 * kb + 8 * kq);
+                const float4 q4 = *(const float4 *)(In + row * ldi + 16 * kb + 8 * kq + 4);
+                x[0] = p.x; x[1] = p.y; x[2] = p.z; x[3] = p.w; x[4] = q4.x; x[5] = q4.y; x[6] = q4.z; x[7] = q4.w;
+            }
+#pragma unroll
+            for (int t = 0; t < 3; ++t) {
+                u32x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = pack_upper(x[2 * e], x[2 * e + 1]);
+                xp[t][kb] = __builtin_bit_cast(bf16x8, w);
+                if (t < 2) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) x[e] = rest(x[e]);
+                }
+            }
+        }
+#pragma unroll
+        for (int J = 0; J < NJB; ++J) {
+            floatx16 acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+            const uint16_t *mrow = mt + (32 * J + pi) * MLD + 8 * kq;
+#pragma unroll
+            for (int kb = 0; kb < NKB; ++kb) {
+                if (UPPER ? (kb <= 2 * J + 1) : (kb >= 2 * J)) {  // compile-time after unrolling: other steps only meet zeros
+                    const bf16x8 m0 = *(const bf16x8 *)(mrow + 16 * kb), m1 = *(const bf16x8 *)(mrow + D * MLD + 16 * kb),
+                                 m2 = *(const bf16x8 *)(mrow + 2 * D * MLD + 16 * kb);
+                    floatx16 t16;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) t16[v] = 0.f;
+                    t16 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(m1, xp[1][kb], t16, 0, 0, 0);  // small terms first
+                    t16 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(m2, xp[0][kb], t16, 0, 0, 0);
+                    t16 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(m0, xp[2][kb], t16, 0, 0, 0);
+                    t16 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(m1, xp[0][kb], t16, 0, 0, 0);
+                    t16 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(m0, xp[1][kb], t16, 0, 0, 0);
+                    t16 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(m0, xp[0][kb], t16, 0, 0, 0);
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[v] += t16[v];
+                }
+            }
+            // acc[v] = Out[row][32 J + 16 kq + v]
+            if (keep) {
+                float4 *dst = (float4 *)(Out + row * ldo + 32 * J + 16 * kq);
+#pragma unroll
+                for (int w = 0; w < 4; ++w) dst[w] = make_float4(acc[4 * w], acc[4 * w + 1], acc[4 * w + 2], acc[4 * w + 3]);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // keep the next column block's operand reads from piling up
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------- launchers
 int dual_supported_max_k(int d) { return d < 128 ? (d < 64 ? d : 64) : 128; }
 
@@ -392,6 +496,14 @@ static als_status dual_rows_typed(als_ctx *ctx, const als_csr *Y, als_table *X, 
         ALS_HIP(ctx, attr_x);
         hipLaunchKernelGGL((transform16_kernel<D, false, false>), dim3(xblocks), dim3(256), Xf16Cfg<D>::LDS_BYTES, s,
                            (const void *)R, ldr, (uint16_t *)X->data, X->ld, Linv, r0, r1, Y->indptr, (int64_t)dual_max);
+    } else if constexpr (!BF16 && D >= 64) {
+        static const hipError_t attr_x = hipFuncSetAttribute((const void *)transform_split_kernel<D, false>,
+                                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                             (int)XfsCfg<D>::LDS_BYTES);  // once per process
+        ALS_HIP(ctx, attr_x);
+        const unsigned sblocks = (unsigned)std::min<int64_t>(512, std::max<int64_t>(1, (r1 - r0 + 255) / 256));
+        hipLaunchKernelGGL((transform_split_kernel<D, false>), dim3(sblocks), dim3(XFS_THREADS), XfsCfg<D>::LDS_BYTES, s,
+                           (const float *)R, ldr, (float *)X->data, X->ld, Linv, r0, r1, Y->indptr, (int64_t)dual_max);
     } else {
         static const hipError_t attr_x = hipFuncSetAttribute((const void *)transform_kernel<D, false, BF16, false>,
                                                              hipFuncAttributeMaxDynamicSharedMemorySize,
